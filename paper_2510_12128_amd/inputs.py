@@ -75,16 +75,32 @@ def rademacher(seed: int, n: int, t: int) -> np.ndarray:
     return (2.0 * rng.integers(0, 2, size=(n, t)) - 1.0).astype(np.float32)
 
 
+def grid_centres(n_clusters: int, d: int, spacing: float) -> np.ndarray:
+    """Centres on the vertices of a d-dimensional grid of side `spacing`, enumerated
+    in mixed-radix order (the paper's synthetic sets put cluster centres on hypercube
+    vertices, Section 4.1)."""
+    side = int(np.ceil(n_clusters ** (1.0 / d)))
+    idx = np.arange(n_clusters)
+    cols = []
+    for _ in range(d):
+        cols.append(idx % side)
+        idx = idx // side
+    return spacing * np.stack(cols, axis=1).astype(np.float64)
+
+
 def blobs(sizes, d: int, centre_halfwidth: float, sigma_blob: float, target: str,
           noise_std: float, seed: int = 0, centre_shrink: float = 1.0,
-          rng: Optional[np.random.Generator] = None):
+          rng: Optional[np.random.Generator] = None, spacing: Optional[float] = None):
     """Gaussian blobs, one per cluster; returns X (float32), y (float32), offsets, centres."""
     sizes = np.asarray(sizes, dtype=np.int64)
     if rng is None:
         rng = np.random.default_rng(seed)
     n_clusters = sizes.shape[0]
     n = int(sizes.sum())
-    centres = rng.uniform(-centre_halfwidth, centre_halfwidth, size=(n_clusters, d)) / centre_shrink
+    if spacing is not None:
+        centres = grid_centres(n_clusters, d, spacing)
+    else:
+        centres = rng.uniform(-centre_halfwidth, centre_halfwidth, size=(n_clusters, d)) / centre_shrink
     X = np.empty((n, d), dtype=np.float64)
     offsets = np.zeros(n_clusters + 1, dtype=np.int64)
     offsets[1:] = np.cumsum(sizes)
@@ -173,11 +189,15 @@ def make_small(n_clusters: int = 3, sizes=None, d: int = 2, rank: int = 2, t: in
                ell: float = 1.5, outputscale: float = 1.3, noise: float = 0.2,
                sigma_blob: float = 0.6, halfwidth: float = 3.0, isotropic: bool = False,
                seed: int = 0, probe_seed: int = 1, tol: float = 1e-10,
-               max_iter: int = 200, target: str = "sin_of_sum") -> Workload:
-    """Tiny free-form workload for pins, edge cases and ragged-size parity tests."""
+               max_iter: int = 200, target: str = "sin_of_sum",
+               spacing: Optional[float] = None) -> Workload:
+    """Tiny free-form workload for pins, edge cases and ragged-size parity tests.
+    `spacing` puts the centres on a grid (well-separated clusters with a controlled
+    coupling strength) instead of drawing them uniformly."""
     if sizes is None:
         sizes = [8] * n_clusters
-    X, y, offsets, centres = blobs(sizes, d, halfwidth, sigma_blob, target, 0.1, seed=seed)
+    X, y, offsets, centres = blobs(sizes, d, halfwidth, sigma_blob, target, 0.1, seed=seed,
+                                   spacing=spacing)
     if isotropic:
         theta = np.array([ell, outputscale, noise], dtype=np.float64)
     else:

@@ -232,8 +232,8 @@ def test_rhs_layout():
 def test_pcg_matches_dense_solve_and_iteration_bound():
     # L^-1 K' L^-T = I + (rank <= n_c r): exact-arithmetic CG needs <= n_c r + 1 steps
     nc, r = 3, 2
-    w = I.make_small(n_clusters=nc, sizes=[12, 15, 10], d=2, rank=r, t=4, seed=29, ell=2.5,
-                     halfwidth=2.0)
+    w = I.make_small(n_clusters=nc, sizes=[12, 15, 10], d=2, rank=r, t=4, seed=29, ell=1.5,
+                     spacing=3.5, sigma_blob=0.3)
     prob = O.Problem(w.X, w.y, w.offsets, w.probes, r)
     fac = O.Factor(prob, w.theta)
     K = prob.dense(w.theta)
@@ -246,7 +246,7 @@ def test_pcg_matches_dense_solve_and_iteration_bound():
 
 
 def test_pcg_freezes_converged_columns_and_counts_iterations():
-    w = I.make_small(n_clusters=3, sizes=[8, 8, 8], d=2, rank=2, t=2, seed=31, ell=2.0, halfwidth=2.0)
+    w = I.make_small(n_clusters=3, sizes=[8, 8, 8], d=2, rank=2, t=2, seed=31, ell=1.5, spacing=3.5, sigma_blob=0.3)
     prob = O.Problem(w.X, w.y, w.offsets, w.probes, 2)
     fac = O.Factor(prob, w.theta)
     K = prob.dense(w.theta)
@@ -308,7 +308,7 @@ def preconditioned_operator(prob, fac, theta):
 
 
 def test_tridiagonal_equals_explicit_lanczos():
-    w = I.make_small(n_clusters=3, sizes=[10, 10, 12], d=2, rank=3, t=3, seed=37, ell=2.5, halfwidth=2.0)
+    w = I.make_small(n_clusters=3, sizes=[10, 10, 12], d=2, rank=3, t=3, seed=37, ell=1.5, spacing=3.5, sigma_blob=0.3)
     prob = O.Problem(w.X, w.y, w.offsets, w.probes, 3)
     fac = O.Factor(prob, w.theta)
     A, K = preconditioned_operator(prob, fac, w.theta)
@@ -343,7 +343,7 @@ def test_hadamard_probes_make_logdet_exact():
     # so the whole chain (factor, rhs, PCG, tridiagonals, quadrature, log det M) must
     # reproduce the dense log-determinant.
     sizes = [16, 16, 16, 16]
-    w = I.make_small(n_clusters=4, sizes=sizes, d=2, rank=2, t=1, seed=41, ell=2.0, halfwidth=2.5)
+    w = I.make_small(n_clusters=4, sizes=sizes, d=2, rank=2, t=1, seed=41, ell=1.5, spacing=3.5, sigma_blob=0.3)
     H = I.hadamard_probes(64)
     prob = O.Problem(w.X, w.y, w.offsets, H, 2)
     fac = O.Factor(prob, w.theta)
@@ -362,7 +362,7 @@ def test_hadamard_probes_make_logdet_exact():
 
 
 def test_random_probe_estimate_within_hutchinson_spread():
-    w = I.make_small(n_clusters=4, sizes=[16] * 4, d=2, rank=2, t=16, seed=43, ell=2.0, halfwidth=2.5)
+    w = I.make_small(n_clusters=4, sizes=[16] * 4, d=2, rank=2, t=16, seed=41, ell=1.5, spacing=3.5, sigma_blob=0.3)
     prob = O.Problem(w.X, w.y, w.offsets, w.probes, 2)
     fac = O.Factor(prob, w.theta)
     out = O.mll(prob, fac, w.theta, 1e-12, 200)
@@ -415,7 +415,7 @@ def test_fd_gradient_matches_analytic_gradient():
     # Hadamard probes make L(theta) the exact NLL of K', so the only difference between
     # central differences and the analytic gradient (Rasmussen & Williams eq. 5.9) is O(h^2).
     sizes = [8, 8, 8, 8]
-    w = I.make_small(n_clusters=4, sizes=sizes, d=2, rank=2, t=1, seed=53, ell=1.8, halfwidth=2.5)
+    w = I.make_small(n_clusters=4, sizes=sizes, d=2, rank=2, t=1, seed=53, ell=1.5, spacing=3.5, sigma_blob=0.3)
     H = I.hadamard_probes(32)
     prob = O.Problem(w.X, w.y, w.offsets, H, 2)
     phi = np.log(w.theta)
@@ -455,7 +455,7 @@ def test_adam_first_two_steps_by_hand():
 
 def test_train_step_reduces_loss_on_small_problem():
     sizes = [8, 8, 8, 8]
-    w = I.make_small(n_clusters=4, sizes=sizes, d=2, rank=2, t=1, seed=59, ell=1.0, halfwidth=2.5)
+    w = I.make_small(n_clusters=4, sizes=sizes, d=2, rank=2, t=1, seed=59, ell=1.5, spacing=3.5, sigma_blob=0.3)
     prob = O.Problem(w.X, w.y, w.offsets, I.hadamard_probes(32), 2)
     phi = np.log(w.theta)
     m = np.zeros_like(phi); v = np.zeros_like(phi); step = 0
