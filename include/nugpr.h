@@ -1,0 +1,188 @@
+/*
+ * nugpr.h -- C ABI of the MI355X (gfx950) implementation of the nuGPR
+ * marginal-log-likelihood hot path (Zhao & Sarin, "nuGPR: GPU-Accelerated
+ * Gaussian Process Regression with Iterative Algorithms and Low-Rank
+ * Approximations").
+ *
+ * One evaluation assembles the dense RBF diagonal blocks K_ii of a
+ * cluster-structured covariance plus the coupling matrix of the cluster
+ * representatives (Section 3.3), runs batched block-Jacobi preconditioned CG
+ * (Sections 3.1-3.2) on [y | t probe vectors] with the block-diagonal +
+ * low-rank product as inner kernel, recovers Lanczos tridiagonals from the CG
+ * coefficients for the stochastic log-determinant of eq. (logdet), and returns
+ * the loss of eq. (loss function).  Central differences over the
+ * hyperparameters and Adam replace back-propagation (Section 3.1, Algorithm 1).
+ *
+ * Conventions
+ *   - Pointers marked DEVICE are device pointers on the GPU current at
+ *     nugpr_create; pointers marked HOST are ordinary host memory.
+ *   - The caller owns every buffer, including ONE device workspace of at least
+ *     nugpr_workspace_bytes() bytes (256-byte aligned).  The library allocates
+ *     no device memory.  It never frees caller memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
+ *     GPU work is enqueued there.  Calls that return host scalars
+ *     (precond_factor, pcg_solve, mll, train_step, export) synchronise that
+ *     stream before returning; build_blocks, matvec and precond_apply do not.
+ *   - Return value: 0 = NUGPR_OK; negative = caller / runtime error (nothing
+ *     useful was computed); positive = numerical status (outputs are written).
+ *     No exception, abort or exit crosses this boundary.
+ *   - theta = [ell_1..ell_d, outputscale, noise_variance] on the natural scale
+ *     (HOST doubles, all > 0); with NUGPR_ISOTROPIC the layout is
+ *     [ell, outputscale, noise_variance], the paper's 3-tuple (Section 2.1).
+ *   - Vector blocks (right-hand sides, solutions, search directions) are
+ *     row-major n x ncols float arrays (column index fastest), ncols <= 33.
+ *   - Points are stored cluster-contiguous: cluster i owns rows
+ *     cluster_offsets[i] .. cluster_offsets[i+1]-1 of X, y and every vector block.
+ */
+#ifndef NUGPR_H
+#define NUGPR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct nugpr_ctx nugpr_ctx;        /* opaque; host-side bookkeeping only */
+
+enum {
+  NUGPR_OK = 0,
+  /* caller / runtime errors */
+  NUGPR_ERR_INVALID = -1,      /* bad argument (null pointer, sizes, theta <= 0, ...) */
+  NUGPR_ERR_WORKSPACE = -2,    /* workspace too small or misaligned */
+  NUGPR_ERR_HIP = -3,          /* a HIP runtime call failed; see nugpr_last_error_string */
+  NUGPR_ERR_STATE = -4,        /* call order violated (e.g. mll before precond_factor) */
+  /* numerical status */
+  NUGPR_NOT_PD = 1,            /* a diagonal block failed Cholesky (Section 3.3: not SPD) */
+  NUGPR_INDEFINITE = 2,        /* PCG met <d, K'd> <= 0: the approximated K' is not SPD */
+  NUGPR_NOT_CONVERGED = 3      /* max_iter reached before every column met the tolerance */
+};
+
+enum {
+  NUGPR_ISOTROPIC = 1u         /* one tied lengthscale: theta has 3 entries */
+};
+
+/* Problem description (Section 2.1 notation; Section 3.3 for representatives). */
+typedef struct {
+  int64_t n;                       /* training points                                  */
+  int32_t d;                       /* input dimension, 1..64                           */
+  int32_t n_clusters;              /* n_c                                              */
+  int32_t rank;                    /* r representatives per cluster, 1..min cluster size */
+  int32_t n_probes;                /* t Hutchinson probe vectors, 0..32                */
+  const int64_t* cluster_offsets;  /* HOST, n_clusters+1 ascending, [0]=0, [n_c]=n     */
+  const float* X;                  /* DEVICE, n*d row-major                            */
+  const float* y;                  /* DEVICE, n                                        */
+  const float* reps;               /* DEVICE, n_clusters*rank*d row-major, or NULL =
+                                      the first `rank` points of every cluster         */
+  const float* W;                  /* DEVICE, n*rank row-major basis (row p belongs to
+                                      point p, its cluster's r columns), or NULL =
+                                      one-hot nearest representative (plain Euclidean
+                                      distance, ties to the lowest index)              */
+  const float* probes;             /* DEVICE, n*n_probes row-major, entries +1/-1      */
+  void* workspace;                 /* DEVICE, caller-owned, 256-byte aligned           */
+  size_t workspace_bytes;
+} nugpr_problem;
+
+/* Solver / optimiser parameters. */
+typedef struct {
+  double tol;          /* PCG stops column c when ||r_c||_2 <= tol * ||b_c||_2         */
+  int32_t max_iter;    /* PCG iteration cap, 1..4096                                   */
+  double fd_step;      /* h of the central differences on log(theta)                   */
+  double lr;           /* Adam learning rate (paper: 0.05)                             */
+  double beta1, beta2, eps;  /* Adam moments / epsilon (0 selects 0.9, 0.999, 1e-8)    */
+  uint32_t flags;      /* NUGPR_ISOTROPIC or 0                                         */
+} nugpr_params;
+
+/* Result of one loss evaluation, eq. (loss function): nll = (quad + logdet + n log 2pi)/2. */
+typedef struct {
+  double nll;             /* the paper's L (negative log marginal likelihood)          */
+  double quad;            /* y^T K'^-1 y                                               */
+  double logdet;          /* log det K' estimate, eq. (logdet)                         */
+  double logdet_precond;  /* log det of the block-Jacobi preconditioner                */
+  int32_t max_iters_used; /* largest per-column PCG iteration count                    */
+  int32_t status;         /* NUGPR_OK or a positive numerical status                   */
+} nugpr_mll_result;
+
+/* Bytes of device workspace a problem of this shape needs.  Pure host arithmetic;
+ * only n, d, n_clusters, rank, n_probes and cluster_offsets are read.  Returns 0 on
+ * invalid input. */
+size_t nugpr_workspace_bytes(const nugpr_problem* problem);
+
+/* Validates the problem, lays out the workspace and builds the theta-independent
+ * pieces on `stream`: representatives (default: first r points per cluster) and the
+ * basis W (default: one-hot nearest representative), Section 3.3.  The problem's
+ * device buffers must stay alive and unchanged until nugpr_destroy. */
+int nugpr_create(nugpr_ctx** ctx, const nugpr_problem* problem, const nugpr_params* params,
+                 void* stream);
+int nugpr_destroy(nugpr_ctx* ctx);
+
+/* Message of the last negative return on this thread (never NULL). */
+const char* nugpr_last_error_string(void);
+
+/* Block assembly at theta (Section 2.1 kernel; K_diag of Section 3.2; K_rep of
+ * Section 3.3 generalised to r representatives per cluster):
+ *   K_ii[p,q] = alpha exp(-1/2 sum_k ((x_pk - x_qk)/ell_k)^2) + sigma^2 [p = q]
+ *   C[(i,a),(j,c)] = alpha exp(-1/2 sum_k ((R_iak - R_jck)/ell_k)^2), i != j (no noise).
+ * Overwrites the stored K_diag and C; never touches the preconditioner. */
+int nugpr_build_blocks(nugpr_ctx* ctx, const double* theta /*HOST*/, void* stream);
+
+/* Block-Jacobi preconditioner, eq. (cholesky factorization): per cluster
+ * K_ii = L_i L_i^T (the paper's R_i = L_i^T) from the CURRENT K_diag, the explicit
+ * inverses L_i^-1 (the paper applies R^-1 as an explicit inverse, Table 2), and the
+ * right-hand sides B = [y | L Z] for the probes Z.  *logdet_M receives
+ * log det of the preconditioner; *bad_cluster the first cluster whose block is not
+ * positive definite (or -1).  Returns NUGPR_NOT_PD in that case. */
+int nugpr_precond_factor(nugpr_ctx* ctx, double* logdet_M /*HOST*/, int32_t* bad_cluster /*HOST*/,
+                         void* stream);
+
+/* Q = K' D for ncols columns, K' = blockdiag(K_ii) + W (C - blockdiag(C_ii)) W^T
+ * (eq. (odsplit) with the rank-r blocks): the inner kernel of PCG, exposed for the
+ * bandwidth metric.  D, Q: DEVICE n x ncols, must not alias. */
+int nugpr_matvec(nugpr_ctx* ctx, const float* D, float* Q, int32_t ncols, void* stream);
+
+/* Z = M^-1 R with M the factored block-Jacobi preconditioner (Section 3.2).
+ * R, Z: DEVICE n x ncols, must not alias. */
+int nugpr_precond_apply(nugpr_ctx* ctx, const float* R, float* Z, int32_t ncols, void* stream);
+
+/* Batched PCG (Sections 3.1-3.2): solves K' X = B for ncols columns in lock step
+ * from X = 0, preconditioned by the stored factor, until every column meets the
+ * tolerance or max_iter.  B, Xout: DEVICE n x ncols.  iters: HOST ncols (iterations
+ * each column ran).  alpha, beta: HOST max_iter*ncols row-major CG coefficients
+ * (zero past a column's count), or NULL.  Returns NUGPR_OK, NUGPR_INDEFINITE or
+ * NUGPR_NOT_CONVERGED (Xout is written in every case). */
+int nugpr_pcg_solve(nugpr_ctx* ctx, const float* B, float* Xout, int32_t ncols,
+                    int32_t* iters, double* alpha, double* beta, void* stream);
+
+/* One loss evaluation (ComputeLoss of Algorithm 1) at theta with the stored
+ * preconditioner, which may have been factored at a different theta (Section 3.2,
+ * reuse of R within an epoch): build_blocks(theta), PCG on [y | L Z], quadratic
+ * term, SLQ log-determinant, eq. (loss function). */
+int nugpr_mll(nugpr_ctx* ctx, const double* theta /*HOST*/, nugpr_mll_result* result /*HOST*/,
+              void* stream);
+
+/* One pass of Algorithm 1's loop body on phi = log(theta): assemble and factor at
+ * theta_0 = exp(phi), base loss, central differences
+ *   g_i = (L(phi + h e_i) - L(phi - h e_i)) / (2h)
+ * all with the theta_0 preconditioner and the same probes, then a bias-corrected
+ * Adam update of phi.  log_theta, adam_m, adam_v: HOST, p entries, in/out
+ * (p = d+2, or 3 with NUGPR_ISOTROPIC); *step in/out; *nll0 and grad (p) out. */
+int nugpr_train_step(nugpr_ctx* ctx, double* log_theta, double* adam_m, double* adam_v,
+                     int64_t* step, double* nll0, double* grad, void* stream);
+
+/* Copies one stored matrix to a dense row-major DEVICE array `dst` with leading
+ * dimension `ld` (for verification).  what: 0 = K_ii (b_i x b_i), 1 = L_i lower
+ * factor (b_i x b_i, zeros above the diagonal), 2 = L_i^-1 (b_i x b_i), 3 = coupling
+ * C with zeroed diagonal blocks ((n_c r) x (n_c r); index ignored), 4 = W_i (b_i x r),
+ * 5 = right-hand sides B (n x (t+1); index ignored), 6 = representatives
+ * ((n_c r) x d; index ignored). */
+int nugpr_export(nugpr_ctx* ctx, int32_t what, int32_t index, float* dst /*DEVICE*/, int64_t ld,
+                 void* stream);
+
+/* Number of hyperparameters p the context expects in theta / log_theta. */
+int32_t nugpr_num_hyper(const nugpr_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NUGPR_H */

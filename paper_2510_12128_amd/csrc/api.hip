@@ -1,0 +1,354 @@
+// C ABI of libnugpr: context set-up, the five entry points of the hot path, and the
+// host-side parts of one loss evaluation (SLQ log-determinant, central differences, Adam).
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <limits>
+#include <new>
+#include <vector>
+
+#include "nugpr_internal.h"
+
+using namespace nugpr;
+
+namespace {
+
+hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+// ---- strip work tables ------------------------------------------------------
+StripItem make_item(uint64_t a_off, uint32_t lda, uint32_t nrows, uint32_t c_begin, uint32_t c_end,
+                    uint32_t in_row0, uint32_t out_row0, uint32_t row_in_block, int out_part, int port, int mode,
+                    float diag_add) {
+  StripItem it{};
+  it.a_off = a_off; it.lda = lda; it.nrows = nrows; it.c_begin = c_begin; it.c_end = c_end;
+  it.in_row0 = in_row0; it.out_row0 = out_row0; it.row_in_block = row_in_block;
+  it.out_part = (uint16_t)out_part; it.port = (uint8_t)port; it.mode = (uint8_t)mode; it.diag_add = diag_add;
+  return it;
+}
+
+void sort_longest_first(std::vector<StripItem>& v) {
+  std::stable_sort(v.begin(), v.end(), [](const StripItem& a, const StripItem& b) {
+    const uint32_t la = a.c_end > a.c_begin ? a.c_end - a.c_begin : 0;
+    const uint32_t lb = b.c_end > b.c_begin ? b.c_end - b.c_begin : 0;
+    return la > lb;
+  });
+}
+
+struct Tables {
+  std::vector<StripItem> WtD, KC, WP, lowG, upG, lowL;
+};
+
+void build_tables(const Layout& L, Tables& t) {
+  const uint32_t r = (uint32_t)L.r;
+  for (int i = 0; i < L.nc; ++i) {
+    const ClusterInfo& c = L.cl[i];
+    // S_i = W_i^T D_i: strips over the r rows of W_i^T, columns split into nsS slabs
+    const uint32_t chunks = c.nt, cpp = (chunks + L.nsS - 1) / L.nsS;
+    for (uint32_t rs = 0; rs * TILE < r; ++rs) {
+      const uint32_t nrows = std::min<uint32_t>(TILE, r - rs * TILE);
+      for (int k = 0; k < L.nsS; ++k) {
+        const uint32_t cb = std::min<uint32_t>(k * cpp, chunks) * TILE;
+        const uint32_t ce = std::min<uint32_t>(std::min<uint32_t>((k + 1) * cpp, chunks) * TILE, c.b);
+        t.WtD.push_back(make_item(c.wtoff + (uint64_t)rs * TILE * c.ld, c.ld, nrows, cb, std::max(cb, ce), c.row0,
+                                  (uint32_t)i * r + rs * TILE, 0, k, 0, 0, 0.f));
+      }
+    }
+    for (uint32_t s = 0; s < c.nt; ++s) {
+      const uint32_t nrows = std::min<uint32_t>(TILE, c.b - s * TILE);
+      const uint64_t a_off = c.koff + (uint64_t)s * TILE * c.ld;
+      const uint32_t row = c.row0 + s * TILE;
+      t.KC.push_back(make_item(a_off, c.ld, nrows, 0, c.b, c.row0, row, s * TILE, 0, 0, 0, 1.f));
+      t.WP.push_back(make_item((uint64_t)row * L.ldw, (uint32_t)L.ldw, nrows, 0, r, (uint32_t)i * r, row, 0, 0, 0, 0, 0.f));
+      t.lowG.push_back(make_item(a_off, c.ld, nrows, 0, s * TILE + nrows, c.row0, row, s * TILE, 0, 0, 1, 0.f));
+      t.upG.push_back(make_item(a_off, c.ld, nrows, s * TILE, c.b, c.row0, row, s * TILE, 0, 0, 2, 0.f));
+      t.lowL.push_back(make_item(a_off, c.ld, nrows, 0, s * TILE + nrows, c.row0, row, s * TILE, 0, 0, 1, 0.f));
+    }
+  }
+  // P = C S: strips over the n_c r rows of C, columns split into nsP slabs
+  {
+    const uint32_t ncr = (uint32_t)L.ncr, chunks = (uint32_t)L.ldc / TILE, cpp = (chunks + L.nsP - 1) / L.nsP;
+    for (uint32_t rs = 0; rs * TILE < ncr; ++rs) {
+      const uint32_t nrows = std::min<uint32_t>(TILE, ncr - rs * TILE);
+      for (int k = 0; k < L.nsP; ++k) {
+        const uint32_t cb = std::min<uint32_t>(k * cpp, chunks) * TILE;
+        const uint32_t ce = std::min<uint32_t>(std::min<uint32_t>((k + 1) * cpp, chunks) * TILE, ncr);
+        t.KC.push_back(make_item((uint64_t)rs * TILE * L.ldc, (uint32_t)L.ldc, nrows, cb, std::max(cb, ce), 0,
+                                 rs * TILE, 0, k, 1, 0, 0.f));
+      }
+    }
+  }
+  sort_longest_first(t.WtD);
+  sort_longest_first(t.KC);
+  sort_longest_first(t.lowG);
+  sort_longest_first(t.upG);
+  sort_longest_first(t.lowL);
+}
+
+int upload_table(const std::vector<StripItem>& v, StripItem*& cursor, StripTable& tab, hipStream_t s) {
+  tab.dev = cursor;
+  tab.count = (int)v.size();
+  if (!v.empty())
+    NUGPR_HIP(hipMemcpyAsync(cursor, v.data(), v.size() * sizeof(StripItem), hipMemcpyHostToDevice, s));
+  cursor += v.size();
+  return NUGPR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* nugpr_last_error_string(void) { return last_error_cstr(); }
+
+size_t nugpr_workspace_bytes(const nugpr_problem* problem) {
+  Layout L;
+  if (plan_layout(problem, 0, L) != NUGPR_OK) return 0;
+  return L.total;
+}
+
+int32_t nugpr_num_hyper(const nugpr_ctx* ctx) { return ctx ? ctx->L.p : 0; }
+
+int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* prm, void* stream) {
+  if (!out) { set_error("ctx out-pointer is null"); return NUGPR_ERR_INVALID; }
+  *out = nullptr;
+  if (!pb || !prm) { set_error("problem or params is null"); return NUGPR_ERR_INVALID; }
+  if (!(prm->tol > 0.0) || !(prm->tol < 1.0)) { set_error("tol must be in (0, 1)"); return NUGPR_ERR_INVALID; }
+  if (prm->max_iter < 1 || prm->max_iter > MAX_ITER_CAP) { set_error("max_iter must be 1..4096"); return NUGPR_ERR_INVALID; }
+  if (!(prm->fd_step > 0.0) || !(prm->lr >= 0.0)) { set_error("fd_step must be > 0 and lr >= 0"); return NUGPR_ERR_INVALID; }
+  Layout L;
+  int rc = plan_layout(pb, prm->flags, L);
+  if (rc) return rc;
+  if (!pb->X || !pb->y || (pb->n_probes > 0 && !pb->probes)) { set_error("X, y or probes is null"); return NUGPR_ERR_INVALID; }
+  if (!pb->workspace || (reinterpret_cast<uintptr_t>(pb->workspace) & 255u)) {
+    set_error("workspace is null or not 256-byte aligned");
+    return NUGPR_ERR_WORKSPACE;
+  }
+  if (pb->workspace_bytes < L.total) { set_error("workspace smaller than nugpr_workspace_bytes()"); return NUGPR_ERR_WORKSPACE; }
+  if ((reinterpret_cast<uintptr_t>(pb->X) & 3u) || (reinterpret_cast<uintptr_t>(pb->y) & 3u)) {
+    set_error("X / y misaligned");
+    return NUGPR_ERR_INVALID;
+  }
+  nugpr_ctx* c = new (std::nothrow) nugpr_ctx();
+  if (!c) { set_error("out of host memory"); return NUGPR_ERR_INVALID; }
+  c->L = L;
+  c->params = *prm;
+  if (c->params.beta1 == 0.0) c->params.beta1 = 0.9;
+  if (c->params.beta2 == 0.0) c->params.beta2 = 0.999;
+  if (c->params.eps == 0.0) c->params.eps = 1e-8;
+  c->ws = static_cast<char*>(pb->workspace);
+  c->X = pb->X; c->y = pb->y; c->probes = pb->probes;
+  char* w = c->ws;
+  c->d_cl = reinterpret_cast<ClusterInfo*>(w + L.o_cl);
+  c->Kd = reinterpret_cast<float*>(w + L.o_Kd);
+  c->Lf = reinterpret_cast<float*>(w + L.o_Lf);
+  c->G = reinterpret_cast<float*>(w + L.o_G);
+  c->C = reinterpret_cast<float*>(w + L.o_C);
+  c->Wd = reinterpret_cast<float*>(w + L.o_Wd);
+  c->Wt = reinterpret_cast<float*>(w + L.o_Wt);
+  c->reps = reinterpret_cast<float*>(w + L.o_reps);
+  c->Bv = reinterpret_cast<float*>(w + L.o_B);
+  c->Xv = reinterpret_cast<float*>(w + L.o_X);
+  c->Rv = reinterpret_cast<float*>(w + L.o_R);
+  c->Zv = reinterpret_cast<float*>(w + L.o_Z);
+  c->Dv = reinterpret_cast<float*>(w + L.o_D);
+  c->Qv = reinterpret_cast<float*>(w + L.o_Q);
+  c->Vv = reinterpret_cast<float*>(w + L.o_V);
+  c->Spart = reinterpret_cast<float*>(w + L.o_Spart);
+  c->Ppart = reinterpret_cast<float*>(w + L.o_Ppart);
+  c->dotpart = reinterpret_cast<double*>(w + L.o_dot);
+  c->d_state = reinterpret_cast<PcgState*>(w + L.o_state);
+  c->alog = reinterpret_cast<double*>(w + L.o_alog);
+  c->blog = reinterpret_cast<double*>(w + L.o_blog);
+  c->d_logdet = reinterpret_cast<double*>(w + L.o_logdet);
+  c->d_tiles = reinterpret_cast<uint64_t*>(w + L.o_tiles);
+  hipStream_t s = as_stream(stream);
+
+  auto fail = [&](int code) { nugpr_destroy(c); return code; };
+  // pinned host staging (host memory; the library allocates no device memory)
+  c->h_buf_doubles = (size_t)2 * MAX_ITER_CAP * MAX_COLS + (size_t)1024 * MAX_COLS + sizeof(PcgState) + L.nc;
+  hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&c->h_flags), sizeof(HostFlags), hipHostMallocDefault);
+  if (e != hipSuccess) return fail(hip_fail(e, "hipHostMalloc(flags)"));
+  e = hipHostMalloc(reinterpret_cast<void**>(&c->h_buf), c->h_buf_doubles * sizeof(double), hipHostMallocDefault);
+  if (e != hipSuccess) return fail(hip_fail(e, "hipHostMalloc(buf)"));
+  std::memset(c->h_flags, 0, sizeof(HostFlags));
+
+  e = hipMemcpyAsync(c->d_cl, L.cl.data(), sizeof(ClusterInfo) * L.nc, hipMemcpyHostToDevice, s);
+  if (e != hipSuccess) return fail(hip_fail(e, "upload cluster table"));
+  Tables t;
+  build_tables(L, t);
+  const size_t total_items = t.WtD.size() + t.KC.size() + t.WP.size() + t.lowG.size() + t.upG.size() + t.lowL.size();
+  if (total_items * sizeof(StripItem) > L.items_bytes) { set_error("internal: strip table overflow"); return fail(NUGPR_ERR_INVALID); }
+  StripItem* cur = reinterpret_cast<StripItem*>(w + L.o_items);
+  if ((rc = upload_table(t.WtD, cur, c->tab_WtD, s))) return fail(rc);
+  if ((rc = upload_table(t.KC, cur, c->tab_KC, s))) return fail(rc);
+  if ((rc = upload_table(t.WP, cur, c->tab_WP, s))) return fail(rc);
+  if ((rc = upload_table(t.lowG, cur, c->tab_lowG, s))) return fail(rc);
+  if ((rc = upload_table(t.upG, cur, c->tab_upG, s))) return fail(rc);
+  if ((rc = upload_table(t.lowL, cur, c->tab_lowL, s))) return fail(rc);
+  e = hipStreamSynchronize(s);          // host vectors go out of scope below
+  if (e != hipSuccess) return fail(hip_fail(e, "sync after table upload"));
+  if ((rc = launch_setup(c, pb->reps, pb->W, s))) return fail(rc);
+  e = hipStreamSynchronize(s);
+  if (e != hipSuccess) return fail(hip_fail(e, "sync after setup"));
+  *out = c;
+  return NUGPR_OK;
+}
+
+int nugpr_destroy(nugpr_ctx* c) {
+  if (!c) return NUGPR_OK;
+  if (c->h_flags) (void)hipHostFree(c->h_flags);
+  if (c->h_buf) (void)hipHostFree(c->h_buf);
+  delete c;
+  return NUGPR_OK;
+}
+
+int nugpr_build_blocks(nugpr_ctx* c, const double* theta, void* stream) {
+  if (!c) { set_error("ctx is null"); return NUGPR_ERR_INVALID; }
+  return launch_build(c, theta, as_stream(stream));
+}
+
+int nugpr_precond_factor(nugpr_ctx* c, double* logdet_M, int32_t* bad_cluster, void* stream) {
+  if (!c) { set_error("ctx is null"); return NUGPR_ERR_INVALID; }
+  if (!c->built) { set_error("precond_factor needs build_blocks first"); return NUGPR_ERR_STATE; }
+  hipStream_t s = as_stream(stream);
+  int rc = launch_factor(c, s);
+  if (rc) return rc;
+  const Layout& L = c->L;
+  NUGPR_HIP(hipMemcpyAsync(c->h_buf, c->d_logdet, (size_t)L.nc * sizeof(double), hipMemcpyDeviceToHost, s));
+  PcgState* hs = reinterpret_cast<PcgState*>(c->h_buf + L.nc);
+  NUGPR_HIP(hipMemcpyAsync(hs, c->d_state, sizeof(PcgState), hipMemcpyDeviceToHost, s));
+  NUGPR_HIP(hipStreamSynchronize(s));
+  double acc = 0.0;
+  for (int i = 0; i < L.nc; ++i) acc += c->h_buf[i];
+  c->logdetM = acc;
+  if (logdet_M) *logdet_M = acc;
+  const bool bad = hs->bad_cluster != std::numeric_limits<int>::max();
+  if (bad_cluster) *bad_cluster = bad ? hs->bad_cluster : -1;
+  c->factored = !bad;
+  return bad ? NUGPR_NOT_PD : NUGPR_OK;
+}
+
+static int check_block_args(nugpr_ctx* c, const void* a, const void* b, int ncols) {
+  if (!c || !a || !b) { set_error("null argument"); return NUGPR_ERR_INVALID; }
+  if (a == b) { set_error("input and output alias"); return NUGPR_ERR_INVALID; }
+  if (ncols < 1 || ncols > c->L.T) { set_error("ncols must be 1..n_probes+1"); return NUGPR_ERR_INVALID; }
+  return NUGPR_OK;
+}
+
+int nugpr_matvec(nugpr_ctx* c, const float* D, float* Q, int32_t ncols, void* stream) {
+  int rc = check_block_args(c, D, Q, ncols);
+  if (rc) return rc;
+  if (!c->built) { set_error("matvec needs build_blocks first"); return NUGPR_ERR_STATE; }
+  return run_matvec(c, D, Q, ncols, as_stream(stream));
+}
+
+int nugpr_precond_apply(nugpr_ctx* c, const float* R, float* Z, int32_t ncols, void* stream) {
+  int rc = check_block_args(c, R, Z, ncols);
+  if (rc) return rc;
+  if (!c->factored) { set_error("precond_apply needs precond_factor first"); return NUGPR_ERR_STATE; }
+  return run_precond(c, R, Z, ncols, as_stream(stream));
+}
+
+int nugpr_pcg_solve(nugpr_ctx* c, const float* B, float* Xout, int32_t ncols, int32_t* iters, double* alpha,
+                    double* beta, void* stream) {
+  int rc = check_block_args(c, B, Xout, ncols);
+  if (rc) return rc;
+  if (!c->built || !c->factored) { set_error("pcg_solve needs build_blocks and precond_factor first"); return NUGPR_ERR_STATE; }
+  return run_pcg(c, B, Xout, ncols, iters, alpha, beta, nullptr, as_stream(stream));
+}
+
+int nugpr_mll(nugpr_ctx* c, const double* theta, nugpr_mll_result* res, void* stream) {
+  if (!c || !res) { set_error("null argument"); return NUGPR_ERR_INVALID; }
+  if (!c->factored) { set_error("mll needs precond_factor first"); return NUGPR_ERR_STATE; }
+  hipStream_t s = as_stream(stream);
+  const Layout& L = c->L;
+  const double nan = std::numeric_limits<double>::quiet_NaN();
+  res->nll = res->quad = res->logdet = nan;
+  res->logdet_precond = c->logdetM;
+  res->max_iters_used = 0;
+  res->status = NUGPR_OK;
+  int rc = launch_build(c, theta, s);
+  if (rc) return rc;
+  const int T = L.T, max_iter = c->params.max_iter;
+  std::vector<int32_t> iters(T);
+  std::vector<double> alpha((size_t)max_iter * T), beta((size_t)max_iter * T);
+  int mx = 0;
+  rc = run_pcg(c, c->Bv, c->Xv, T, iters.data(), alpha.data(), beta.data(), &mx, s);
+  if (rc < 0) return rc;
+  res->max_iters_used = mx;
+  res->status = rc;
+  if (rc == NUGPR_INDEFINITE) return rc;
+  double dots[MAX_COLS];
+  int rc2 = run_dot_col(c, c->Bv, c->Xv, T, dots, s);
+  if (rc2) return rc2;
+  res->quad = dots[0];                           // <y, K'^-1 y>: column 0 of B is y
+  // squared norms of the Lanczos start vectors
+  PcgState* hs = reinterpret_cast<PcgState*>(c->h_buf);
+  NUGPR_HIP(hipMemcpyAsync(hs, c->d_state, sizeof(PcgState), hipMemcpyDeviceToHost, s));
+  NUGPR_HIP(hipStreamSynchronize(s));
+  double est = 0.0;
+  for (int col = 1; col < T; ++col) {
+    double q = 0.0;
+    if (slq_e1_log_e1(alpha.data() + col, beta.data() + col, T, iters[col], &q)) {
+      res->status = NUGPR_INDEFINITE;
+      return NUGPR_INDEFINITE;
+    }
+    est += hs->rho0[col] * q;
+  }
+  res->logdet = c->logdetM + (L.t > 0 ? est / L.t : 0.0);
+  res->nll = 0.5 * (res->quad + res->logdet + (double)L.n * std::log(2.0 * M_PI));
+  return rc;
+}
+
+int nugpr_train_step(nugpr_ctx* c, double* log_theta, double* adam_m, double* adam_v, int64_t* step, double* nll0,
+                     double* grad, void* stream) {
+  if (!c || !log_theta || !adam_m || !adam_v || !step || !nll0 || !grad) { set_error("null argument"); return NUGPR_ERR_INVALID; }
+  const int p = c->L.p;
+  const double h = c->params.fd_step;
+  std::vector<double> theta(p);
+  for (int i = 0; i < p; ++i) {
+    if (!std::isfinite(log_theta[i])) { set_error("log_theta is not finite"); return NUGPR_ERR_INVALID; }
+    theta[i] = std::exp(log_theta[i]);
+  }
+  int worst = NUGPR_OK;
+  int rc = nugpr_build_blocks(c, theta.data(), stream);
+  if (rc) return rc;
+  double ldm; int32_t bad;
+  rc = nugpr_precond_factor(c, &ldm, &bad, stream);
+  if (rc) return rc;
+  nugpr_mll_result r0;
+  rc = nugpr_mll(c, theta.data(), &r0, stream);
+  if (rc < 0 || rc == NUGPR_INDEFINITE) return rc;
+  worst = std::max(worst, rc);
+  *nll0 = r0.nll;
+  for (int i = 0; i < p; ++i) {
+    nugpr_mll_result rp, rm;
+    theta[i] = std::exp(log_theta[i] + h);
+    rc = nugpr_mll(c, theta.data(), &rp, stream);
+    if (rc < 0 || rc == NUGPR_INDEFINITE) return rc;
+    worst = std::max(worst, rc);
+    theta[i] = std::exp(log_theta[i] - h);
+    rc = nugpr_mll(c, theta.data(), &rm, stream);
+    if (rc < 0 || rc == NUGPR_INDEFINITE) return rc;
+    worst = std::max(worst, rc);
+    theta[i] = std::exp(log_theta[i]);
+    grad[i] = (rp.nll - rm.nll) / (2.0 * h);
+  }
+  // Adam (bias corrected), minimising the loss
+  const double b1 = c->params.beta1, b2 = c->params.beta2, eps = c->params.eps, lr = c->params.lr;
+  *step += 1;
+  const double c1 = 1.0 - std::pow(b1, (double)*step), c2 = 1.0 - std::pow(b2, (double)*step);
+  for (int i = 0; i < p; ++i) {
+    adam_m[i] = b1 * adam_m[i] + (1.0 - b1) * grad[i];
+    adam_v[i] = b2 * adam_v[i] + (1.0 - b2) * grad[i] * grad[i];
+    const double mh = adam_m[i] / c1, vh = adam_v[i] / c2;
+    log_theta[i] -= lr * mh / (std::sqrt(vh) + eps);
+  }
+  return worst;
+}
+
+int nugpr_export(nugpr_ctx* c, int32_t what, int32_t index, float* dst, int64_t ld, void* stream) {
+  if (!c) { set_error("ctx is null"); return NUGPR_ERR_INVALID; }
+  return launch_export(c, what, index, dst, ld, as_stream(stream));
+}
+
+}  // extern "C"

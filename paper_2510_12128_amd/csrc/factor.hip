@@ -1,0 +1,379 @@
+// Block-Jacobi preconditioner (Section 3.2, eq. (cholesky factorization)): batched
+// Cholesky K_ii = L_i L_i^T of every diagonal block, the explicit inverses L_i^-1 (the
+// paper applies the factor as an explicit inverse followed by batched products, Table 2),
+// log det of the preconditioner, and the right-hand sides B = [y | L Z].
+//
+// Everything is tiled in 64 x 64 fp32 tiles whose products run on the matrix cores
+// (v_mfma_f32_16x16x4_f32, four waves per tile, each 32 x 32).
+//   Cholesky: left-looking over tile columns.  Step k: every tile (m, k), m >= k, gets
+//     A[m,k] - sum_{j<k} L[m,j] L[k,j]^T in one batched launch over clusters; the
+//     workgroup that owns the diagonal tile factors it in LDS and also writes its
+//     inverse; a second launch multiplies the tiles below by that inverse.
+//   Inverse: the binary-tree identity
+//     [L11 0; L21 L22]^-1 = [Y11 0; -Y22 L21 Y11, Y22]
+//     applied bottom-up over tile ranges, two batched products per level
+//     (T = L21 Y11, kept transposed in the still unused upper triangle; Y21 = -Y22 T).
+//   The inverse is finally mirrored into the upper triangle so that both halves of the
+//   preconditioner apply, tril(G) r and triu(G) v, stream row-major strips.
+// log det of the preconditioner is taken from the STORED inverse, -2 sum log Y_pp, so the
+// split of eq. (logdet) holds exactly for the operator PCG really applies.
+#include <climits>
+#include <cmath>
+
+#include "nugpr_internal.h"
+
+namespace nugpr {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+constexpr int KS = 16;          // contraction depth per LDS stage
+constexpr int SP = KS + 1;      // padded LDS row
+
+struct Frag {          // one thread's share of a 64 x 16 operand stage
+  float v[4];
+};
+
+// Logical operand Op[r][k]; memory is base[r*ld + k] (TRANS = false) or base[k*ld + r].
+// tri: 0 none, 1 keep k <= r, 2 keep k >= r (r, k are coordinates inside the same square block).
+template <bool TRANS>
+__device__ __forceinline__ Frag fetch(const float* __restrict__ base, uint32_t ld, int r0, int k0, int rmax,
+                                      int tri, int tid) {
+  Frag f;
+  if (!TRANS) {
+    const int r = r0 + (tid >> 2), k = k0 + (tid & 3) * 4;
+    if (r < rmax) {
+      const float4 x = *reinterpret_cast<const float4*>(base + (uint64_t)r * ld + k);
+      f.v[0] = x.x; f.v[1] = x.y; f.v[2] = x.z; f.v[3] = x.w;
+    } else {
+      f.v[0] = f.v[1] = f.v[2] = f.v[3] = 0.f;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (tri == 1 && k + j > r) f.v[j] = 0.f;
+      if (tri == 2 && k + j < r) f.v[j] = 0.f;
+    }
+  } else {
+    const int k = k0 + (tid >> 4), r = r0 + (tid & 15) * 4;
+    const float4 x = *reinterpret_cast<const float4*>(base + (uint64_t)k * ld + r);
+    f.v[0] = x.x; f.v[1] = x.y; f.v[2] = x.z; f.v[3] = x.w;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (r + j >= rmax) f.v[j] = 0.f;
+      if (tri == 1 && k > r + j) f.v[j] = 0.f;
+      if (tri == 2 && k < r + j) f.v[j] = 0.f;
+    }
+  }
+  return f;
+}
+
+template <bool TRANS>
+__device__ __forceinline__ void commit(float (*s)[SP], const Frag& f, int tid) {
+  if (!TRANS) {
+    const int r = tid >> 2, k = (tid & 3) * 4;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) s[r][k + j] = f.v[j];
+  } else {
+    const int k = tid >> 4, r = (tid & 15) * 4;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) s[r + j][k] = f.v[j];
+  }
+}
+
+struct Operand {
+  const float* base;
+  uint32_t ld;
+  int r0;      // first logical row of the 64-row tile
+  int rmax;    // rows >= rmax read as zero
+  int tri;
+};
+
+// acc[i][j] += OpA[64 x K] * OpB[64 x K]^T over k in [k0, k1), k0/k1 multiples of 16.
+template <bool TA, bool TB>
+__device__ __forceinline__ void tile_gemm(v4f (&acc)[2][2], const Operand& A, const Operand& B, int k0, int k1,
+                                          float (*sA)[SP], float (*sB)[SP], int tid) {
+  const int wave = tid >> 6, lane = tid & 63;
+  const int wy = wave >> 1, wx = wave & 1;
+  const int m = lane & 15, kk = lane >> 4;
+  if (k0 >= k1) return;
+  Frag fa = fetch<TA>(A.base, A.ld, A.r0, k0, A.rmax, A.tri, tid);
+  Frag fb = fetch<TB>(B.base, B.ld, B.r0, k0, B.rmax, B.tri, tid);
+  for (int k = k0; k < k1; k += KS) {
+    __syncthreads();
+    commit<TA>(sA, fa, tid);
+    commit<TB>(sB, fb, tid);
+    __syncthreads();
+    if (k + KS < k1) {
+      fa = fetch<TA>(A.base, A.ld, A.r0, k + KS, A.rmax, A.tri, tid);
+      fb = fetch<TB>(B.base, B.ld, B.r0, k + KS, B.rmax, B.tri, tid);
+    }
+#pragma unroll
+    for (int ks = 0; ks < KS / 4; ++ks) {
+      const float a0 = sA[wy * 32 + m][4 * ks + kk];
+      const float a1 = sA[wy * 32 + 16 + m][4 * ks + kk];
+      const float b0 = sB[wx * 32 + m][4 * ks + kk];
+      const float b1 = sB[wx * 32 + 16 + m][4 * ks + kk];
+      acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b0, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b1, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b0, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1, acc[1][1], 0, 0, 0);
+    }
+  }
+}
+
+__device__ __forceinline__ void zero_acc(v4f (&acc)[2][2]) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = (v4f){0.f, 0.f, 0.f, 0.f};
+}
+
+// visit every accumulator element with its (row, col) inside the 64 x 64 tile
+template <class F>
+__device__ __forceinline__ void for_each_acc(v4f (&acc)[2][2], int tid, F f) {
+  const int wave = tid >> 6, lane = tid & 63;
+  const int wy = wave >> 1, wx = wave & 1;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        f(wy * 32 + 16 * i + 4 * (lane >> 4) + v, wx * 32 + 16 * j + (lane & 15), acc[i][j][v]);
+}
+
+// ---------------------------------------------------------------------------
+// Cholesky, step k
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_potrf_update(const ClusterInfo* __restrict__ cl, const float* __restrict__ Kd,
+                                                      float* __restrict__ Lf, float* __restrict__ G, int k,
+                                                      PcgState* __restrict__ st) {
+  __shared__ float sA[TILE][SP];
+  __shared__ float sB[TILE][SP];
+  __shared__ float sT[TILE][TILE + 1];
+  __shared__ float sI[TILE][TILE + 1];
+  const ClusterInfo c = cl[blockIdx.y];
+  const int mt = k + (int)blockIdx.x;
+  if (mt >= (int)c.nt) return;
+  const int tid = threadIdx.x;
+  const int b = (int)c.b;
+  const float* A = Kd + c.koff;
+  float* L = Lf + c.koff;
+  v4f acc[2][2];
+  zero_acc(acc);
+  Operand oa{L, c.ld, mt * TILE, b, 0};
+  Operand ob{L, c.ld, k * TILE, b, 0};
+  tile_gemm<false, false>(acc, oa, ob, 0, k * TILE, sA, sB, tid);
+  const uint64_t tile_off = (uint64_t)(mt * TILE) * c.ld + (uint64_t)k * TILE;
+  if (mt != k) {
+    for_each_acc(acc, tid, [&](int r, int q, float v) {
+      L[tile_off + (uint64_t)r * c.ld + q] = A[tile_off + (uint64_t)r * c.ld + q] - v;
+    });
+    return;
+  }
+  // ---- diagonal tile: factor in LDS; rows/cols past the cluster end behave as identity ----
+  const int valid = min(TILE, b - k * TILE);
+  for_each_acc(acc, tid, [&](int r, int q, float v) {
+    float x = A[tile_off + (uint64_t)r * c.ld + q] - v;
+    if (r >= valid || q >= valid) x = (r == q) ? 1.f : 0.f;
+    sT[r][q] = x;
+  });
+  __syncthreads();
+  bool bad = false;
+  for (int j = 0; j < TILE; ++j) {
+    float dj = sT[j][j];
+    if (!(dj > 0.f) || !(dj < INFINITY)) { bad = true; dj = 1.f; }
+    const float sj = sqrtf(dj);
+    const float inv = 1.f / sj;
+    __syncthreads();                       // everyone has read the pivot
+    if (tid > j && tid < TILE) sT[tid][j] *= inv;
+    if (tid == j) sT[j][j] = sj;
+    __syncthreads();
+    const int i = tid >> 2;                // trailing update, row i, columns j < cc <= i
+    if (i > j) {
+      const float lij = sT[i][j];
+      for (int cc = j + 1 + (tid & 3); cc <= i; cc += 4) sT[i][cc] = fmaf(-lij, sT[cc][j], sT[i][cc]);
+    }
+    __syncthreads();
+  }
+  if (bad && tid == 0) atomicMin(&st->bad_cluster, (int)blockIdx.y);
+  // ---- inverse of the lower-triangular tile, one column per thread ----
+  if (tid < TILE) {
+    const int cc = tid;
+    for (int i = 0; i < cc; ++i) sI[i][cc] = 0.f;
+    sI[cc][cc] = 1.f / sT[cc][cc];
+    for (int i = cc + 1; i < TILE; ++i) {
+      float s = 0.f;
+      for (int j = cc; j < i; ++j) s = fmaf(sT[i][j], sI[j][cc], s);
+      sI[i][cc] = -s / sT[i][i];
+    }
+  }
+  __syncthreads();
+  float* Y = G + c.koff;
+  for (int idx = tid; idx < TILE * TILE; idx += 256) {
+    const int r = idx >> 6, q = idx & 63;
+    L[tile_off + (uint64_t)r * c.ld + q] = (q <= r) ? sT[r][q] : 0.f;
+    Y[tile_off + (uint64_t)r * c.ld + q] = (q <= r) ? sI[r][q] : 0.f;
+  }
+}
+
+// tiles below the diagonal: L[m,k] <- L[m,k] * inv(L[k,k])^T
+__global__ __launch_bounds__(256) void k_potrf_trsm(const ClusterInfo* __restrict__ cl, float* __restrict__ Lf,
+                                                    const float* __restrict__ G, int k) {
+  __shared__ float sA[TILE][SP];
+  __shared__ float sB[TILE][SP];
+  const ClusterInfo c = cl[blockIdx.y];
+  const int mt = k + 1 + (int)blockIdx.x;
+  if (mt >= (int)c.nt) return;
+  const int tid = threadIdx.x;
+  float* L = Lf + c.koff;
+  const float* Y = G + c.koff;
+  v4f acc[2][2];
+  zero_acc(acc);
+  Operand oa{L, c.ld, mt * TILE, (int)c.b, 0};
+  Operand ob{Y, c.ld, k * TILE, (int)c.ld, 1};          // Y_kk[c][j], lower triangular
+  tile_gemm<false, false>(acc, oa, ob, k * TILE, (k + 1) * TILE, sA, sB, tid);
+  __syncthreads();
+  const uint64_t tile_off = (uint64_t)(mt * TILE) * c.ld + (uint64_t)k * TILE;
+  for_each_acc(acc, tid, [&](int r, int q, float v) { L[tile_off + (uint64_t)r * c.ld + q] = v; });
+}
+
+// ---------------------------------------------------------------------------
+// triangular inverse, one tree level (half = tiles per child)
+// ---------------------------------------------------------------------------
+// stage 1: T = L21 * Y11, stored transposed in the mirror block (upper triangle of G)
+__global__ __launch_bounds__(256) void k_trtri_stage1(const ClusterInfo* __restrict__ cl, const float* __restrict__ Lf,
+                                                      float* __restrict__ G, int half) {
+  __shared__ float sA[TILE][SP];
+  __shared__ float sB[TILE][SP];
+  __shared__ float sT[TILE][TILE + 1];
+  const ClusterInfo c = cl[blockIdx.z];
+  const int start = (int)blockIdx.y * 2 * half, mid = start + half;
+  const int tm = mid + (int)blockIdx.x / half, tn = start + (int)blockIdx.x % half;
+  if (mid >= (int)c.nt || tm >= (int)c.nt) return;
+  const int tid = threadIdx.x;
+  const float* L = Lf + c.koff;
+  float* Y = G + c.koff;
+  v4f acc[2][2];
+  zero_acc(acc);
+  Operand oa{L, c.ld, tm * TILE, (int)c.b, 0};          // L21[m][k]
+  Operand ob{Y, c.ld, tn * TILE, (int)c.ld, 2};         // OpB[n][k] = Y11[k][n], nonzero for k >= n
+  tile_gemm<false, true>(acc, oa, ob, tn * TILE, mid * TILE, sA, sB, tid);
+  for_each_acc(acc, tid, [&](int r, int q, float v) { sT[r][q] = v; });
+  __syncthreads();
+  // mirror block: rows = columns of T (tile tn), columns = rows of T (tile tm)
+  const uint64_t off = (uint64_t)(tn * TILE) * c.ld + (uint64_t)tm * TILE;
+  for (int idx = tid; idx < TILE * TILE; idx += 256) {
+    const int q = idx >> 6, r = idx & 63;
+    Y[off + (uint64_t)q * c.ld + r] = sT[r][q];
+  }
+}
+
+// stage 2: Y21 = -Y22 * T
+__global__ __launch_bounds__(256) void k_trtri_stage2(const ClusterInfo* __restrict__ cl, float* __restrict__ G,
+                                                      int half) {
+  __shared__ float sA[TILE][SP];
+  __shared__ float sB[TILE][SP];
+  const ClusterInfo c = cl[blockIdx.z];
+  const int start = (int)blockIdx.y * 2 * half, mid = start + half;
+  const int tm = mid + (int)blockIdx.x / half, tn = start + (int)blockIdx.x % half;
+  if (mid >= (int)c.nt || tm >= (int)c.nt) return;
+  const int tid = threadIdx.x;
+  float* Y = G + c.koff;
+  v4f acc[2][2];
+  zero_acc(acc);
+  Operand oa{Y, c.ld, tm * TILE, (int)c.b, 1};          // Y22[m][k], nonzero for k <= m
+  Operand ob{Y, c.ld, tn * TILE, (int)c.ld, 0};         // OpB[n][k] = T[k][n], read from the mirror block
+  tile_gemm<false, false>(acc, oa, ob, mid * TILE, (tm + 1) * TILE, sA, sB, tid);
+  const uint64_t off = (uint64_t)(tm * TILE) * c.ld + (uint64_t)tn * TILE;
+  for_each_acc(acc, tid, [&](int r, int q, float v) { Y[off + (uint64_t)r * c.ld + q] = -v; });
+}
+
+// upper triangle <- transpose of the lower triangle (tile list of the assembly kernels)
+__global__ __launch_bounds__(256) void k_mirror(const ClusterInfo* __restrict__ cl, const uint64_t* __restrict__ tiles,
+                                                float* __restrict__ G) {
+  __shared__ float sT[TILE][TILE + 1];
+  const uint64_t t = tiles[blockIdx.x];
+  const int ci = (int)(t >> 32), tr = (int)((t >> 16) & 0xffff), tc = (int)(t & 0xffff);
+  const ClusterInfo c = cl[ci];
+  float* Y = G + c.koff;
+  const int tid = threadIdx.x;
+  const uint64_t src = (uint64_t)(tr * TILE) * c.ld + (uint64_t)tc * TILE;
+  const uint64_t dst = (uint64_t)(tc * TILE) * c.ld + (uint64_t)tr * TILE;
+  for (int idx = tid; idx < TILE * TILE; idx += 256) {
+    const int r = idx >> 6, q = idx & 63;
+    sT[r][q] = Y[src + (uint64_t)r * c.ld + q];
+  }
+  __syncthreads();
+  for (int idx = tid; idx < TILE * TILE; idx += 256) {
+    const int r = idx >> 6, q = idx & 63;      // element (r, q) of the destination tile
+    if (tr != tc || q > r) Y[dst + (uint64_t)r * c.ld + q] = sT[q][r];
+  }
+}
+
+// log det of the preconditioner of one cluster from the stored inverse diagonal
+__global__ __launch_bounds__(256) void k_logdet(const ClusterInfo* __restrict__ cl, const float* __restrict__ G,
+                                                double* __restrict__ out) {
+  __shared__ double red[256];
+  const ClusterInfo c = cl[blockIdx.x];
+  const float* Y = G + c.koff;
+  double s = 0.0;
+  for (uint32_t p = threadIdx.x; p < c.b; p += 256) s += log((double)Y[(uint64_t)p * c.ld + p]);
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[blockIdx.x] = -2.0 * red[0];
+}
+
+__global__ void k_reset_bad(PcgState* st) { st->bad_cluster = INT_MAX; }
+
+// V = [0 | Z] (n x T) from the probes (n x t)
+__global__ void k_probes_to_block(const float* __restrict__ Z, float* __restrict__ V, int64_t n, int t) {
+  const int T = t + 1;
+  const int64_t total = n * T;
+  for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t p = idx / T;
+    const int col = (int)(idx - p * T);
+    V[idx] = col == 0 ? 0.f : Z[p * t + col - 1];
+  }
+}
+
+__global__ void k_set_col0(float* __restrict__ B, const float* __restrict__ y, int64_t n, int T) {
+  for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < n; p += (int64_t)gridDim.x * blockDim.x)
+    B[p * T] = y[p];
+}
+
+int launch_factor(nugpr_ctx* c, hipStream_t s) {
+  const Layout& L = c->L;
+  hipLaunchKernelGGL(k_reset_bad, dim3(1), dim3(1), 0, s, c->d_state);
+  for (int k = 0; k < L.ntmax; ++k) {
+    hipLaunchKernelGGL(k_potrf_update, dim3(L.ntmax - k, L.nc), dim3(256), 0, s, c->d_cl, c->Kd, c->Lf, c->G, k,
+                       c->d_state);
+    if (k + 1 < L.ntmax)
+      hipLaunchKernelGGL(k_potrf_trsm, dim3(L.ntmax - k - 1, L.nc), dim3(256), 0, s, c->d_cl, c->Lf, c->G, k);
+  }
+  for (int half = 1; half < L.ntmax; half *= 2) {
+    const int nodes = (L.ntmax + 2 * half - 1) / (2 * half);
+    dim3 grid(half * half, nodes, L.nc);
+    hipLaunchKernelGGL(k_trtri_stage1, grid, dim3(256), 0, s, c->d_cl, c->Lf, c->G, half);
+    hipLaunchKernelGGL(k_trtri_stage2, grid, dim3(256), 0, s, c->d_cl, c->G, half);
+  }
+  hipLaunchKernelGGL(k_mirror, dim3((unsigned)L.n_diag_tiles), dim3(256), 0, s, c->d_cl, c->d_tiles, c->G);
+  hipLaunchKernelGGL(k_logdet, dim3(L.nc), dim3(256), 0, s, c->d_cl, c->G, c->d_logdet);
+  NUGPR_HIP(hipGetLastError());
+  // right-hand sides B = [y | L Z]
+  if (L.t > 0) {
+    hipLaunchKernelGGL(k_probes_to_block, dim3(1024), dim3(256), 0, s, c->probes, c->Vv, (int64_t)L.n, L.t);
+    StripPort p0{};
+    p0.A = c->Lf; p0.in = c->Vv; p0.out = c->Bv; p0.nin = 1;
+    int rc = launch_strip(c->tab_lowL, p0, p0, L.T, s);
+    if (rc) return rc;
+  }
+  hipLaunchKernelGGL(k_set_col0, dim3(1024), dim3(256), 0, s, c->Bv, c->y, (int64_t)L.n, L.T);
+  NUGPR_HIP(hipGetLastError());
+  return NUGPR_OK;
+}
+
+}  // namespace nugpr

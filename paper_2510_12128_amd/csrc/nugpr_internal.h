@@ -1,0 +1,185 @@
+// Internal declarations shared by the HIP translation units of libnugpr.
+// gfx950 only; wave64.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "nugpr.h"
+
+namespace nugpr {
+
+constexpr int TILE = 64;        // rows per strip / edge of the square tiles
+constexpr int MAX_COLS = 33;    // widest vector block (1 + 32 probes)
+constexpr int MAX_D = 64;
+constexpr int MAX_ITER_CAP = 4096;
+
+// ---------------------------------------------------------------------------
+// per-cluster geometry (device copy lives in the workspace)
+// ---------------------------------------------------------------------------
+struct ClusterInfo {
+  uint64_t koff;    // element offset of this cluster's b x ld block in Kd / Lf / G
+  uint64_t wtoff;   // element offset of this cluster's r x ld block in Wt
+  uint32_t row0;    // first point of the cluster
+  uint32_t b;       // points in the cluster
+  uint32_t ld;      // leading dimension of its square blocks: b rounded up to 64
+  uint32_t nt;      // number of 64-wide tiles per side: ld / 64
+};
+
+// ---------------------------------------------------------------------------
+// strip GEMM work item: out[64 rows] (+)= A[64 rows, c_begin:c_end] * in[c_begin:c_end]
+// ---------------------------------------------------------------------------
+struct StripItem {
+  uint64_t a_off;        // element offset (within the port's matrix) of strip row 0, column 0
+  uint32_t lda;
+  uint32_t nrows;        // valid rows of the strip, 1..64
+  uint32_t c_begin;      // first column, multiple of 64
+  uint32_t c_end;        // one past the last valid column
+  uint32_t in_row0;      // vector-block row matching column 0
+  uint32_t out_row0;     // vector-block row of strip row 0
+  uint32_t row_in_block; // index of strip row 0 inside its square block (diagonal position)
+  uint16_t out_part;     // which partial-output slab this item writes
+  uint8_t port;          // 0 / 1: which (matrix, in, out) triple of the launch
+  uint8_t mode;          // 0 full, 1 lower triangle (col <= row), 2 upper triangle (col >= row)
+  float diag_add;        // 1 for square diagonal blocks: out += port.diag_add * in[row]; else 0
+  uint32_t pad_;
+};
+static_assert(sizeof(StripItem) == 48, "StripItem layout");
+
+struct StripPort {
+  const float* A;            // matrix base
+  const float* in;           // input vector block(s)
+  float* out;                // output vector block(s)
+  uint64_t in_part_stride;   // elements between the nin input slabs (summed on load)
+  uint64_t out_part_stride;  // elements between output slabs
+  int32_t nin;
+  int32_t accumulate;        // out += result instead of out = result
+  float diag_add;            // scalar added on the diagonal of items that ask for it
+  int32_t pad_;
+};
+
+struct StripArgs {
+  StripPort port[2];
+  const StripItem* items;
+  int32_t T;                 // columns of the vector blocks (row stride)
+  uint32_t magicT;           // floor(2^32 / T) + 1, for division by T
+};
+
+struct StripTable {
+  StripItem* dev = nullptr;
+  int count = 0;
+};
+
+// ---------------------------------------------------------------------------
+// device-side PCG scalars (all double), one slot per column
+// ---------------------------------------------------------------------------
+struct PcgState {
+  double rho[MAX_COLS];
+  double rho0[MAX_COLS];     // <r_0, M^-1 r_0>: squared norm of the Lanczos start vector
+  double bnorm2[MAX_COLS];
+  double alpha[MAX_COLS];
+  double beta[MAX_COLS];
+  int32_t active[MAX_COLS];
+  int32_t iters[MAX_COLS];
+  int32_t converged[MAX_COLS];
+  int32_t n_active;
+  int32_t indefinite;
+  int32_t bad_cluster;    // Cholesky: lowest failing cluster index, or INT_MAX
+  int32_t pad_;
+};
+
+// host-visible mirror (pinned)
+struct HostFlags {
+  int32_t n_active;
+  int32_t indefinite;
+  int32_t bad_cluster;
+  int32_t pad_;
+};
+
+struct Layout {
+  // geometry
+  int64_t n = 0;
+  int d = 0, nc = 0, r = 0, t = 0, T = 0, p = 0;
+  int ncr = 0, ldc = 0, ldw = 0;
+  int ntmax = 0;
+  int nsS = 1, nsP = 1;
+  std::vector<ClusterInfo> cl;
+  uint64_t kd_elems = 0, wt_elems = 0;
+  // byte offsets into the workspace
+  size_t o_cl = 0, o_Kd = 0, o_Lf = 0, o_G = 0, o_C = 0, o_Wd = 0, o_Wt = 0, o_reps = 0;
+  size_t o_B = 0, o_X = 0, o_R = 0, o_Z = 0, o_D = 0, o_Q = 0, o_V = 0;
+  size_t o_Spart = 0, o_Ppart = 0, o_dot = 0, o_state = 0, o_alog = 0, o_blog = 0;
+  size_t o_theta = 0, o_logdet = 0, o_tiles = 0, o_items = 0;
+  size_t items_bytes = 0;
+  int n_dot_blocks = 0;
+  int max_iter = 0;
+  uint64_t n_diag_tiles = 0, n_c_tiles = 0;
+  size_t total = 0;
+};
+
+}  // namespace nugpr
+
+struct nugpr_ctx {
+  nugpr::Layout L;
+  nugpr_params params;
+  char* ws = nullptr;
+  const float* X = nullptr;
+  const float* y = nullptr;
+  const float* probes = nullptr;
+  // device views into the workspace
+  nugpr::ClusterInfo* d_cl = nullptr;
+  float *Kd = nullptr, *Lf = nullptr, *G = nullptr, *C = nullptr, *Wd = nullptr, *Wt = nullptr, *reps = nullptr;
+  float *Bv = nullptr, *Xv = nullptr, *Rv = nullptr, *Zv = nullptr, *Dv = nullptr, *Qv = nullptr, *Vv = nullptr;
+  float *Spart = nullptr, *Ppart = nullptr;
+  double *dotpart = nullptr, *alog = nullptr, *blog = nullptr, *d_theta = nullptr, *d_logdet = nullptr;
+  nugpr::PcgState* d_state = nullptr;
+  uint64_t* d_tiles = nullptr;       // packed (cluster, tile row, tile col) list for assembly
+  nugpr::StripTable tab_WtD, tab_KC, tab_WP, tab_lowG, tab_upG, tab_lowL;
+  nugpr::HostFlags* h_flags = nullptr;   // pinned
+  double* h_buf = nullptr;               // pinned scratch for small device->host reads
+  size_t h_buf_doubles = 0;
+  float diag_residual = 0.f;             // (alpha + sigma^2) - float(alpha + sigma^2)
+  bool built = false, factored = false;
+  double logdetM = 0.0;
+};
+
+namespace nugpr {
+
+// error plumbing ------------------------------------------------------------
+void set_error(const std::string& msg);
+const char* last_error_cstr();
+int hip_fail(hipError_t e, const char* what);
+#define NUGPR_HIP(call)                                         \
+  do {                                                          \
+    hipError_t e__ = (call);                                    \
+    if (e__ != hipSuccess) return ::nugpr::hip_fail(e__, #call); \
+  } while (0)
+
+// layout.cpp ----------------------------------------------------------------
+int plan_layout(const nugpr_problem* pb, uint32_t flags, Layout& L);
+
+// build_blocks.hip ----------------------------------------------------------
+int launch_setup(nugpr_ctx* c, const float* user_reps, const float* user_W, hipStream_t s);
+int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s);
+int launch_export(nugpr_ctx* c, int what, int index, float* dst, int64_t ld, hipStream_t s);
+
+// strip_gemm.hip ------------------------------------------------------------
+int launch_strip(const StripTable& tab, const StripPort& p0, const StripPort& p1, int T, hipStream_t s);
+
+// factor.hip ----------------------------------------------------------------
+int launch_factor(nugpr_ctx* c, hipStream_t s);
+
+// pcg.hip ---------------------------------------------------------------------
+int run_matvec(nugpr_ctx* c, const float* D, float* Q, int T, hipStream_t s);
+int run_precond(nugpr_ctx* c, const float* R, float* Z, int T, hipStream_t s);
+int run_pcg(nugpr_ctx* c, const float* B, float* X, int T, int32_t* iters, double* alpha, double* beta,
+            int* max_it_used, hipStream_t s);
+int run_dot_col(nugpr_ctx* c, const float* A, const float* B, int T, double* out_host, hipStream_t s);
+
+// slq.cpp ---------------------------------------------------------------------
+// e_1^T log(T) e_1 for the k x k Lanczos matrix built from CG coefficients.
+int slq_e1_log_e1(const double* alpha, const double* beta, int stride, int k, double* out);
+
+}  // namespace nugpr

@@ -1,0 +1,306 @@
+// Batched preconditioned CG (Sections 3.1-3.2; the vector operations of Tables 1-2) and
+// the two operator applications it alternates: the block-low-rank product K' D and the
+// block-Jacobi preconditioner M^-1 R.
+//
+// All T columns advance in lock step.  Vector blocks are n x T row-major fp32; every
+// reduction that feeds a CG coefficient (the paper's batched dot products) is accumulated
+// in fp64 in a fixed order: per-workgroup partial sums, then one small kernel that adds
+// them, computes alpha / beta per column and updates the convergence mask on the device.
+// The host reads back one 16-byte flag record per iteration (O(1) traffic, Section 4).
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+
+#include "nugpr_internal.h"
+
+namespace nugpr {
+
+// ---------------------------------------------------------------------------
+// per-column dot products: partial[which][block][col] = sum over the block's rows
+// ---------------------------------------------------------------------------
+template <int NP>
+__global__ __launch_bounds__(256) void k_dot(const float* __restrict__ A0, const float* __restrict__ B0,
+                                             const float* __restrict__ A1, const float* __restrict__ B1,
+                                             int64_t n, int T, double* __restrict__ partial) {
+  __shared__ double red[NP][256];
+  const int rpp = 256 / T;                      // rows per pass
+  const int tid = threadIdx.x;
+  const int myrow = tid / T, col = tid - myrow * T;
+  const bool live = myrow < rpp;
+  const int64_t rows_per_block = (n + gridDim.x - 1) / gridDim.x;
+  const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
+  const int64_t r1 = r0 + rows_per_block < n ? r0 + rows_per_block : n;
+  double s0 = 0.0, s1 = 0.0;
+  if (live) {
+    for (int64_t r = r0 + myrow; r < r1; r += rpp) {
+      const int64_t idx = r * T + col;
+      s0 += (double)A0[idx] * (double)B0[idx];
+      if (NP > 1) s1 += (double)A1[idx] * (double)B1[idx];
+    }
+  }
+  red[0][tid] = s0;
+  if (NP > 1) red[NP - 1][tid] = s1;
+  __syncthreads();
+  if (tid < T) {
+    for (int w = 0; w < NP; ++w) {
+      double s = 0.0;
+      for (int k = 0; k < rpp; ++k) s += red[w][k * T + tid];
+      partial[((int64_t)w * gridDim.x + blockIdx.x) * MAX_COLS + tid] = s;
+    }
+  }
+}
+
+__device__ __forceinline__ double sum_partials(const double* __restrict__ partial, int nblocks, int col,
+                                               double* red, int tid) {
+  // 256 threads cooperate on one column at a time, fixed order
+  double s = 0.0;
+  for (int b = tid; b < nblocks; b += 256) s += partial[(int64_t)b * MAX_COLS + col];
+  red[tid] = s;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if (tid < w) red[tid] += red[tid + w];
+    __syncthreads();
+  }
+  const double r = red[0];
+  __syncthreads();
+  return r;
+}
+
+// start of a solve: ||b||^2 and rho_0 = <r_0, z_0>
+__global__ __launch_bounds__(256) void k_pcg_begin(PcgState* __restrict__ st, const double* __restrict__ partial,
+                                                   int nblocks, int T) {
+  __shared__ double red[256];
+  const int tid = threadIdx.x;
+  int n_active = 0;
+  for (int c = 0; c < T; ++c) {
+    const double bb = sum_partials(partial, nblocks, c, red, tid);
+    const double rz = sum_partials(partial + (int64_t)nblocks * MAX_COLS, nblocks, c, red, tid);
+    const bool act = bb > 0.0 && rz == rz;
+    if (tid == 0) {
+      st->bnorm2[c] = bb;
+      st->rho[c] = rz;
+      st->rho0[c] = rz;
+      st->alpha[c] = 0.0;
+      st->beta[c] = 0.0;
+      st->active[c] = act ? 1 : 0;
+      st->iters[c] = 0;
+      st->converged[c] = (bb == 0.0) ? 1 : 0;
+    }
+    n_active += act ? 1 : 0;
+  }
+  if (tid == 0) { st->n_active = n_active; st->indefinite = 0; }
+}
+
+// alpha_c = rho_c / <d, K'd>_c for the active columns
+__global__ __launch_bounds__(256) void k_pcg_alpha(PcgState* __restrict__ st, const double* __restrict__ partial,
+                                                   int nblocks, int T, int iter, double* __restrict__ alog) {
+  __shared__ double red[256];
+  const int tid = threadIdx.x;
+  for (int c = 0; c < T; ++c) {
+    const double dq = sum_partials(partial, nblocks, c, red, tid);
+    if (tid == 0) {
+      double a = 0.0;
+      if (st->active[c]) {
+        if (dq > 0.0) a = st->rho[c] / dq;
+        else { st->indefinite = 1; st->active[c] = 0; st->n_active -= 1; }   // <d, K'd> <= 0 (or NaN)
+      }
+      st->alpha[c] = a;
+      alog[(int64_t)iter * MAX_COLS + c] = a;
+    }
+  }
+}
+
+// after the update: stop test on ||r||, then beta_c = <r, z>_new / rho_c
+__global__ __launch_bounds__(256) void k_pcg_beta(PcgState* __restrict__ st, const double* __restrict__ partial,
+                                                  int nblocks, int T, int iter, double tol2,
+                                                  double* __restrict__ blog) {
+  __shared__ double red[256];
+  const int tid = threadIdx.x;
+  for (int c = 0; c < T; ++c) {
+    const double rr = sum_partials(partial, nblocks, c, red, tid);
+    const double rz = sum_partials(partial + (int64_t)nblocks * MAX_COLS, nblocks, c, red, tid);
+    if (tid == 0) {
+      double bta = 0.0;
+      if (st->active[c]) {
+        st->iters[c] = iter + 1;
+        if (rr <= tol2 * st->bnorm2[c]) {
+          st->active[c] = 0;
+          st->converged[c] = 1;
+          st->n_active -= 1;
+        } else if (!(rz > 0.0)) {            // preconditioned residual lost positivity (or NaN)
+          st->active[c] = 0;
+          st->indefinite = 1;
+          st->n_active -= 1;
+        } else {
+          bta = rz / st->rho[c];
+          st->rho[c] = rz;
+        }
+      }
+      st->beta[c] = bta;
+      blog[(int64_t)iter * MAX_COLS + c] = bta;
+    }
+  }
+}
+
+// X += D diag(alpha); R -= Q diag(alpha)
+__global__ __launch_bounds__(256) void k_update_xr(float* __restrict__ X, float* __restrict__ R,
+                                                   const float* __restrict__ D, const float* __restrict__ Q,
+                                                   const PcgState* __restrict__ st, int64_t n, int T) {
+  const int rpp = 256 / T;
+  const int tid = threadIdx.x;
+  const int myrow = tid / T, col = tid - myrow * T;
+  if (myrow >= rpp) return;
+  // alpha stays in fp64: rounding it to fp32 would scale the whole step coherently
+  const double a = st->alpha[col];
+  for (int64_t r = (int64_t)blockIdx.x * rpp + myrow; r < n; r += (int64_t)gridDim.x * rpp) {
+    const int64_t idx = r * T + col;
+    X[idx] = (float)fma(a, (double)D[idx], (double)X[idx]);
+    R[idx] = (float)fma(-a, (double)Q[idx], (double)R[idx]);
+  }
+}
+
+// D = Z + D diag(beta) for active columns, 0 for stopped ones
+__global__ __launch_bounds__(256) void k_update_d(float* __restrict__ D, const float* __restrict__ Z,
+                                                  const PcgState* __restrict__ st, int64_t n, int T) {
+  const int rpp = 256 / T;
+  const int tid = threadIdx.x;
+  const int myrow = tid / T, col = tid - myrow * T;
+  if (myrow >= rpp) return;
+  const double bta = st->beta[col];
+  const bool act = st->active[col] != 0;
+  for (int64_t r = (int64_t)blockIdx.x * rpp + myrow; r < n; r += (int64_t)gridDim.x * rpp) {
+    const int64_t idx = r * T + col;
+    D[idx] = act ? (float)fma(bta, (double)D[idx], (double)Z[idx]) : 0.f;
+  }
+}
+
+__global__ void k_copy_flags(const PcgState* __restrict__ st, HostFlags* __restrict__ out) {
+  out->n_active = st->n_active;
+  out->indefinite = st->indefinite;
+  out->bad_cluster = st->bad_cluster;
+}
+
+// ---------------------------------------------------------------------------
+// operator applications
+// ---------------------------------------------------------------------------
+int run_matvec(nugpr_ctx* c, const float* D, float* Q, int T, hipStream_t s) {
+  const Layout& L = c->L;
+  int rc;
+  const uint64_t spart = (uint64_t)L.ncr * T, ppart = (uint64_t)L.ncr * T;
+  // S_j = W_j^T D_j, split over column slabs of W_j^T
+  StripPort s0{};
+  s0.A = c->Wt; s0.in = D; s0.out = c->Spart; s0.nin = 1; s0.out_part_stride = spart;
+  if ((rc = launch_strip(c->tab_WtD, s0, s0, T, s))) return rc;
+  // Q_i = K_ii D_i   and   P = C_offdiag S (column slabs), one launch
+  StripPort k0{}, k1{};
+  k0.A = c->Kd; k0.in = D; k0.out = Q; k0.nin = 1; k0.diag_add = c->diag_residual;
+  k1.A = c->C; k1.in = c->Spart; k1.nin = L.nsS; k1.in_part_stride = spart; k1.out = c->Ppart;
+  k1.out_part_stride = ppart;
+  if ((rc = launch_strip(c->tab_KC, k0, k1, T, s))) return rc;
+  // Q_i += W_i P_i
+  StripPort w0{};
+  w0.A = c->Wd; w0.in = c->Ppart; w0.nin = L.nsP; w0.in_part_stride = ppart; w0.out = Q; w0.accumulate = 1;
+  return launch_strip(c->tab_WP, w0, w0, T, s);
+}
+
+int run_precond(nugpr_ctx* c, const float* R, float* Z, int T, hipStream_t s) {
+  int rc;
+  StripPort a{};
+  a.A = c->G; a.in = R; a.out = c->Vv; a.nin = 1;
+  if ((rc = launch_strip(c->tab_lowG, a, a, T, s))) return rc;
+  StripPort b{};
+  b.A = c->G; b.in = c->Vv; b.out = Z; b.nin = 1;
+  return launch_strip(c->tab_upG, b, b, T, s);
+}
+
+static int elementwise_grid(int64_t n, int T) {
+  const int rpp = 256 / T;
+  int64_t g = (n + rpp - 1) / rpp;
+  return (int)std::min<int64_t>(g, 4096);
+}
+
+int run_dot_col(nugpr_ctx* c, const float* A, const float* B, int T, double* out_host, hipStream_t s) {
+  const Layout& L = c->L;
+  const int nb = L.n_dot_blocks;
+  hipLaunchKernelGGL((k_dot<1>), dim3(nb), dim3(256), 0, s, A, B, A, B, (int64_t)L.n, T, c->dotpart);
+  NUGPR_HIP(hipGetLastError());
+  // small: add the partials on the host in block order
+  NUGPR_HIP(hipMemcpyAsync(c->h_buf, c->dotpart, (size_t)nb * MAX_COLS * sizeof(double), hipMemcpyDeviceToHost, s));
+  NUGPR_HIP(hipStreamSynchronize(s));
+  for (int col = 0; col < T; ++col) {
+    double acc = 0.0;
+    for (int b = 0; b < nb; ++b) acc += c->h_buf[(size_t)b * MAX_COLS + col];
+    out_host[col] = acc;
+  }
+  return NUGPR_OK;
+}
+
+int run_pcg(nugpr_ctx* c, const float* B, float* X, int T, int32_t* iters, double* alpha, double* beta,
+            int* max_it_used, hipStream_t s) {
+  const Layout& L = c->L;
+  const int64_t n = L.n;
+  const size_t bytes = (size_t)n * T * sizeof(float);
+  const int nb = L.n_dot_blocks;
+  const int eg = elementwise_grid(n, T);
+  const double tol2 = c->params.tol * c->params.tol;
+  const int max_iter = c->params.max_iter;
+  int rc;
+  float *R = c->Rv, *Z = c->Zv, *D = c->Dv, *Q = c->Qv;
+  NUGPR_HIP(hipMemsetAsync(X, 0, bytes, s));
+  NUGPR_HIP(hipMemcpyAsync(R, B, bytes, hipMemcpyDeviceToDevice, s));
+  NUGPR_HIP(hipMemsetAsync(c->alog, 0, (size_t)max_iter * MAX_COLS * sizeof(double), s));
+  NUGPR_HIP(hipMemsetAsync(c->blog, 0, (size_t)max_iter * MAX_COLS * sizeof(double), s));
+  if ((rc = run_precond(c, R, Z, T, s))) return rc;
+  NUGPR_HIP(hipMemcpyAsync(D, Z, bytes, hipMemcpyDeviceToDevice, s));
+  hipLaunchKernelGGL((k_dot<2>), dim3(nb), dim3(256), 0, s, R, R, R, Z, n, T, c->dotpart);
+  hipLaunchKernelGGL(k_pcg_begin, dim3(1), dim3(256), 0, s, c->d_state, c->dotpart, nb, T);
+  NUGPR_HIP(hipGetLastError());
+  int it = 0;
+  bool indefinite = false;
+  c->h_flags->n_active = 1;
+  hipLaunchKernelGGL(k_copy_flags, dim3(1), dim3(1), 0, s, c->d_state, c->h_flags);
+  NUGPR_HIP(hipStreamSynchronize(s));
+  while (it < max_iter && c->h_flags->n_active > 0) {
+    if ((rc = run_matvec(c, D, Q, T, s))) return rc;
+    hipLaunchKernelGGL((k_dot<1>), dim3(nb), dim3(256), 0, s, D, Q, D, Q, n, T, c->dotpart);
+    hipLaunchKernelGGL(k_pcg_alpha, dim3(1), dim3(256), 0, s, c->d_state, c->dotpart, nb, T, it, c->alog);
+    hipLaunchKernelGGL(k_update_xr, dim3(eg), dim3(256), 0, s, X, R, D, Q, c->d_state, n, T);
+    if ((rc = run_precond(c, R, Z, T, s))) return rc;
+    hipLaunchKernelGGL((k_dot<2>), dim3(nb), dim3(256), 0, s, R, R, R, Z, n, T, c->dotpart);
+    hipLaunchKernelGGL(k_pcg_beta, dim3(1), dim3(256), 0, s, c->d_state, c->dotpart, nb, T, it, tol2, c->blog);
+    hipLaunchKernelGGL(k_update_d, dim3(eg), dim3(256), 0, s, D, Z, c->d_state, n, T);
+    hipLaunchKernelGGL(k_copy_flags, dim3(1), dim3(1), 0, s, c->d_state, c->h_flags);
+    NUGPR_HIP(hipGetLastError());
+    NUGPR_HIP(hipStreamSynchronize(s));
+    ++it;
+    if (c->h_flags->indefinite) indefinite = true;
+  }
+  // per-column records
+  PcgState* hs = reinterpret_cast<PcgState*>(c->h_buf);
+  NUGPR_HIP(hipMemcpyAsync(hs, c->d_state, sizeof(PcgState), hipMemcpyDeviceToHost, s));
+  NUGPR_HIP(hipStreamSynchronize(s));
+  bool all_conv = true;
+  int mx = 0;
+  for (int col = 0; col < T; ++col) {
+    if (iters) iters[col] = hs->iters[col];
+    mx = std::max(mx, hs->iters[col]);
+    if (!hs->converged[col]) all_conv = false;
+  }
+  if (max_it_used) *max_it_used = mx;
+  if (alpha || beta) {
+    double* ha = c->h_buf;
+    const size_t cnt = (size_t)max_iter * MAX_COLS;
+    NUGPR_HIP(hipMemcpyAsync(ha, c->alog, cnt * sizeof(double), hipMemcpyDeviceToHost, s));
+    NUGPR_HIP(hipMemcpyAsync(ha + cnt, c->blog, cnt * sizeof(double), hipMemcpyDeviceToHost, s));
+    NUGPR_HIP(hipStreamSynchronize(s));
+    for (int j = 0; j < max_iter; ++j)
+      for (int col = 0; col < T; ++col) {
+        if (alpha) alpha[(size_t)j * T + col] = ha[(size_t)j * MAX_COLS + col];
+        if (beta) beta[(size_t)j * T + col] = ha[cnt + (size_t)j * MAX_COLS + col];
+      }
+  }
+  if (indefinite) return NUGPR_INDEFINITE;
+  return all_conv ? NUGPR_OK : NUGPR_NOT_CONVERGED;
+}
+
+}  // namespace nugpr
