@@ -60,7 +60,11 @@ enum {
 };
 
 enum {
-  NUGPR_ISOTROPIC = 1u         /* one tied lengthscale: theta has 3 entries */
+  NUGPR_ISOTROPIC = 1u,        /* one tied lengthscale: theta has 3 entries */
+  NUGPR_ACC_FP32 = 2u          /* operator applications on fp32 vector blocks with fp32 matrix-core
+                                  accumulation (faster).  Default: fp64 vector blocks and fp64
+                                  matrix-core accumulation over the same fp32 stored matrices, which
+                                  keeps accumulation rounding out of the finite-difference gradient. */
 };
 
 /* Problem description (Section 2.1 notation; Section 3.3 for representatives). */
@@ -91,7 +95,7 @@ typedef struct {
   double fd_step;      /* h of the central differences on log(theta)                   */
   double lr;           /* Adam learning rate (paper: 0.05)                             */
   double beta1, beta2, eps;  /* Adam moments / epsilon (0 selects 0.9, 0.999, 1e-8)    */
-  uint32_t flags;      /* NUGPR_ISOTROPIC or 0                                         */
+  uint32_t flags;      /* NUGPR_ISOTROPIC | NUGPR_ACC_FP32, or 0                       */
 } nugpr_params;
 
 /* Result of one loss evaluation, eq. (loss function): nll = (quad + logdet + n log 2pi)/2. */

@@ -131,6 +131,7 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   if (!c) { set_error("out of host memory"); return NUGPR_ERR_INVALID; }
   c->L = L;
   c->params = *prm;
+  c->acc64 = (prm->flags & NUGPR_ACC_FP32) == 0;
   if (c->params.beta1 == 0.0) c->params.beta1 = 0.9;
   if (c->params.beta2 == 0.0) c->params.beta2 = 0.999;
   if (c->params.eps == 0.0) c->params.eps = 1e-8;
@@ -145,15 +146,16 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   c->Wd = reinterpret_cast<float*>(w + L.o_Wd);
   c->Wt = reinterpret_cast<float*>(w + L.o_Wt);
   c->reps = reinterpret_cast<float*>(w + L.o_reps);
-  c->Bv = reinterpret_cast<float*>(w + L.o_B);
-  c->Xv = reinterpret_cast<float*>(w + L.o_X);
-  c->Rv = reinterpret_cast<float*>(w + L.o_R);
-  c->Zv = reinterpret_cast<float*>(w + L.o_Z);
-  c->Dv = reinterpret_cast<float*>(w + L.o_D);
-  c->Qv = reinterpret_cast<float*>(w + L.o_Q);
-  c->Vv = reinterpret_cast<float*>(w + L.o_V);
-  c->Spart = reinterpret_cast<float*>(w + L.o_Spart);
-  c->Ppart = reinterpret_cast<float*>(w + L.o_Ppart);
+  c->Bv = w + L.o_B;
+  c->Xv = w + L.o_X;
+  c->Rv = w + L.o_R;
+  c->Zv = w + L.o_Z;
+  c->Dv = w + L.o_D;
+  c->Qv = w + L.o_Q;
+  c->Vv = w + L.o_V;
+  c->Uv = w + L.o_U;
+  c->Spart = w + L.o_Spart;
+  c->Ppart = w + L.o_Ppart;
   c->dotpart = reinterpret_cast<double*>(w + L.o_dot);
   c->d_state = reinterpret_cast<PcgState*>(w + L.o_state);
   c->alog = reinterpret_cast<double*>(w + L.o_alog);
@@ -238,14 +240,24 @@ int nugpr_matvec(nugpr_ctx* c, const float* D, float* Q, int32_t ncols, void* st
   int rc = check_block_args(c, D, Q, ncols);
   if (rc) return rc;
   if (!c->built) { set_error("matvec needs build_blocks first"); return NUGPR_ERR_STATE; }
-  return run_matvec(c, D, Q, ncols, as_stream(stream));
+  hipStream_t s = as_stream(stream);
+  if (!c->acc64) return run_matvec(c, D, Q, ncols, s);
+  const int64_t cnt = c->L.n * ncols;
+  if ((rc = to_internal(c, D, c->Dv, cnt, s))) return rc;
+  if ((rc = run_matvec(c, c->Dv, c->Qv, ncols, s))) return rc;
+  return from_internal(c, c->Qv, Q, cnt, s);
 }
 
 int nugpr_precond_apply(nugpr_ctx* c, const float* R, float* Z, int32_t ncols, void* stream) {
   int rc = check_block_args(c, R, Z, ncols);
   if (rc) return rc;
   if (!c->factored) { set_error("precond_apply needs precond_factor first"); return NUGPR_ERR_STATE; }
-  return run_precond(c, R, Z, ncols, as_stream(stream));
+  hipStream_t s = as_stream(stream);
+  if (!c->acc64) return run_precond(c, R, Z, ncols, s);
+  const int64_t cnt = c->L.n * ncols;
+  if ((rc = to_internal(c, R, c->Rv, cnt, s))) return rc;
+  if ((rc = run_precond(c, c->Rv, c->Zv, ncols, s))) return rc;
+  return from_internal(c, c->Zv, Z, cnt, s);
 }
 
 int nugpr_pcg_solve(nugpr_ctx* c, const float* B, float* Xout, int32_t ncols, int32_t* iters, double* alpha,
@@ -253,7 +265,15 @@ int nugpr_pcg_solve(nugpr_ctx* c, const float* B, float* Xout, int32_t ncols, in
   int rc = check_block_args(c, B, Xout, ncols);
   if (rc) return rc;
   if (!c->built || !c->factored) { set_error("pcg_solve needs build_blocks and precond_factor first"); return NUGPR_ERR_STATE; }
-  return run_pcg(c, B, Xout, ncols, iters, alpha, beta, nullptr, as_stream(stream));
+  hipStream_t s = as_stream(stream);
+  if (!c->acc64) return run_pcg(c, B, Xout, ncols, iters, alpha, beta, nullptr, s);
+  const int64_t cnt = c->L.n * ncols;
+  if ((rc = to_internal(c, B, c->Uv, cnt, s))) return rc;
+  const int status = run_pcg(c, c->Uv, c->Xv, ncols, iters, alpha, beta, nullptr, s);
+  if (status < 0) return status;
+  if ((rc = from_internal(c, c->Xv, Xout, cnt, s))) return rc;
+  NUGPR_HIP(hipStreamSynchronize(s));
+  return status;
 }
 
 int nugpr_mll(nugpr_ctx* c, const double* theta, nugpr_mll_result* res, void* stream) {

@@ -1,17 +1,19 @@
 // Block assembly (Section 2.1 kernel, K_diag of Section 3.2, representative-point
 // coupling of Section 3.3) and the theta-independent setup (representatives, basis W).
 //
-// The covariance entries are written in fp32, but every scalar that multiplies ALL
-// entries alike -- the per-dimension weights 1/(2 ell_k^2), the output scale alpha and
-// the diagonal alpha + sigma^2 -- is carried as an fp32 (hi, lo) pair so that its
-// rounding does not move between the two evaluations of a central difference (a
-// rounding of 6e-8 in a scalar is amplified by 1/h = 1000 in the gradient).  The part of
-// alpha + sigma^2 that fp32 cannot hold is kept as a scalar and added by the matrix-
-// vector product (StripPort::diag_add).
+// Entries are STORED in fp32 but COMPUTED in fp64 and rounded once.  The loss is
+// differenced over hyperparameter steps of 1e-3, and each probe's quadratic form
+// z^T log(.) z weighs the entry errors by the (large) entries of L^-T z, so an entry error
+// of a few fp32 ulps -- what an fp32 distance accumulation followed by the hardware exp
+// gives -- shows up as 1e-4-level noise in the gradient.  On CDNA the fp64 vector FMA
+// runs at the rate of the unpacked fp32 FMA, so the exact form costs no more than an fp32
+// (hi, lo) split would: per pair and dimension one subtract, one multiply, one FMA.
 //
 // Squared distances use the direct difference form sum_k w_k (x_pk - x_qk)^2 on the
 // vector ALUs; the |x|^2 + |x'|^2 - 2 x.x' contraction would put this on the matrix
-// cores but cancels catastrophically in fp32.
+// cores but cancels catastrophically.  The part of alpha + sigma^2 that the fp32 diagonal
+// cannot hold is kept as a scalar and added by the matrix-vector product
+// (StripPort::diag_add).
 #include <cmath>
 #include <vector>
 
@@ -20,54 +22,67 @@
 namespace nugpr {
 
 struct PairArgs {
-  float w_hi[MAX_D];
-  float w_lo[MAX_D];
-  float a_hi, a_lo;
-  float diag_val;
+  double w[MAX_D];      // log2(e) / (2 ell_k^2)
+  double alpha;
+  float diag_val;       // float(alpha + sigma^2)
   int32_t d;
 };
 
-// 64x64 tile of alpha * exp2(-sum_k w_k (xr_k - xc_k)^2); thread (ty, tx) holds a 4x4 patch.
-// sXr / sXc: coordinates of the 64 row / column points, layout [k][64].
-__device__ __forceinline__ void pair_tile(const PairArgs& a, const float (*sXr)[TILE], const float (*sXc)[TILE],
+// 2^(-a) for a >= 0 in fp64: a = n + f, |f| <= 1/2, 2^-f by its Taylor series in f ln 2
+// (degree 10: relative error < 1e-13), scaled by 2^-n.
+__device__ __forceinline__ double exp2_neg(double a) {
+  const double n = rint(a);
+  const double g = (n - a) * 0.69314718055994530942;      // -f ln 2, |g| <= 0.3466
+  double p = 1.0 / 3628800.0;
+  p = fma(p, g, 1.0 / 362880.0);
+  p = fma(p, g, 1.0 / 40320.0);
+  p = fma(p, g, 1.0 / 5040.0);
+  p = fma(p, g, 1.0 / 720.0);
+  p = fma(p, g, 1.0 / 120.0);
+  p = fma(p, g, 1.0 / 24.0);
+  p = fma(p, g, 1.0 / 6.0);
+  p = fma(p, g, 0.5);
+  p = fma(p, g, 1.0);
+  p = fma(p, g, 1.0);
+  const int e = n > 2000.0 ? -2000 : -(int)n;
+  return ldexp(p, e);
+}
+
+// 64x64 tile of alpha * 2^(-sum_k w_k (xr_k - xc_k)^2); thread (ty, tx) holds a 4x4 patch.
+// sXr / sXc: coordinates of the 64 row / column points widened to fp64, layout [k][64].
+__device__ __forceinline__ void pair_tile(const PairArgs& a, const double (*sXr)[TILE], const double (*sXc)[TILE],
                                           int ty, int tx, float (&val)[4][4]) {
-  float hi[4][4], lo[4][4];
+  double acc[4][4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) { hi[i][j] = 0.f; lo[i][j] = 0.f; }
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
   for (int k = 0; k < a.d; ++k) {
-    const float4 xr = *reinterpret_cast<const float4*>(&sXr[k][4 * ty]);
-    const float4 xc = *reinterpret_cast<const float4*>(&sXc[k][4 * tx]);
-    const float wh = a.w_hi[k], wl = a.w_lo[k];
-    const float r_[4] = {xr.x, xr.y, xr.z, xr.w};
-    const float c_[4] = {xc.x, xc.y, xc.z, xc.w};
+    const double w = a.w[k];
+    double r_[4], c_[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { r_[i] = sXr[k][4 * ty + i]; c_[i] = sXc[k][4 * tx + i]; }
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const float df = r_[i] - c_[j];
-        const float t = df * df;
-        hi[i][j] = fmaf(wh, t, hi[i][j]);
-        lo[i][j] = fmaf(wl, t, lo[i][j]);
+        const double df = r_[i] - c_[j];
+        acc[i][j] = fma(w, df * df, acc[i][j]);
       }
   }
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const float e = __builtin_amdgcn_exp2f(-(hi[i][j] + lo[i][j]));
-      val[i][j] = fmaf(a.a_lo, e, a.a_hi * e);
-    }
+    for (int j = 0; j < 4; ++j) val[i][j] = (float)(a.alpha * exp2_neg(acc[i][j]));
 }
 
 __device__ __forceinline__ void load_points(const float* __restrict__ P, int d, int first, int valid,
-                                            float (*sX)[TILE], int tid) {
+                                            double (*sX)[TILE], int tid) {
   // sX[k][p] = P[(first + p) * d + k] for p < valid, else 0
   const int total = TILE * d;
   for (int idx = tid; idx < total; idx += 256) {
     const int p = idx / d, k = idx - p * d;
-    sX[k][p] = p < valid ? P[(uint64_t)(first + p) * d + k] : 0.f;
+    sX[k][p] = p < valid ? (double)P[(uint64_t)(first + p) * d + k] : 0.0;
   }
 }
 
@@ -106,12 +121,19 @@ __device__ __forceinline__ void store_tile(float* __restrict__ out, uint32_t ld,
   }
 }
 
+// dynamic LDS: two [d][64] fp64 coordinate panels, reused as a 64 x 65 fp32 transpose buffer
+__host__ __device__ inline size_t pair_lds_bytes(int d) {
+  const size_t panels = (size_t)2 * d * TILE * sizeof(double);
+  const size_t transp = (size_t)TILE * (TILE + 1) * sizeof(float);
+  return panels > transp ? panels : transp;
+}
+
 __global__ __launch_bounds__(256) void k_build_diag(const PairArgs a, const ClusterInfo* __restrict__ cl,
                                                     const uint64_t* __restrict__ tiles,
                                                     const float* __restrict__ X, float* __restrict__ Kd) {
-  __shared__ __attribute__((aligned(16))) float sX[2][MAX_D][TILE];
-  float(*sXr)[TILE] = sX[0];
-  float(*sXc)[TILE] = sX[1];
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  double(*sXr)[TILE] = reinterpret_cast<double(*)[TILE]>(lds_raw);
+  double(*sXc)[TILE] = sXr + a.d;
   const uint64_t t = tiles[blockIdx.x];
   const int ci = (int)(t >> 32), tr = (int)((t >> 16) & 0xffff), tc = (int)(t & 0xffff);
   const ClusterInfo c = cl[ci];
@@ -123,7 +145,7 @@ __global__ __launch_bounds__(256) void k_build_diag(const PairArgs a, const Clus
   __syncthreads();
   float val[4][4];
   pair_tile(a, sXr, sXc, ty, tx, val);
-  float(*sT)[TILE + 1] = reinterpret_cast<float(*)[TILE + 1]>(&sX[0][0][0]);   // 64*65 floats, reused after the tile is in registers
+  float(*sT)[TILE + 1] = reinterpret_cast<float(*)[TILE + 1]>(lds_raw);   // reused once the tile is in registers
   const float dv = a.diag_val;
   store_tile(Kd + c.koff, c.ld, p0, q0, tr != tc, val, sT, ty, tx, tid,
              [b](int p, int q) { return p < b && q < b; },
@@ -133,9 +155,9 @@ __global__ __launch_bounds__(256) void k_build_diag(const PairArgs a, const Clus
 __global__ __launch_bounds__(256) void k_build_coupling(const PairArgs a, const uint64_t* __restrict__ tiles,
                                                         const float* __restrict__ reps, float* __restrict__ C,
                                                         int ncr, int r, uint32_t ldc) {
-  __shared__ __attribute__((aligned(16))) float sX[2][MAX_D][TILE];
-  float(*sXr)[TILE] = sX[0];
-  float(*sXc)[TILE] = sX[1];
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  double(*sXr)[TILE] = reinterpret_cast<double(*)[TILE]>(lds_raw);
+  double(*sXc)[TILE] = sXr + a.d;
   const uint64_t t = tiles[blockIdx.x];
   const int tr = (int)((t >> 16) & 0xffff), tc = (int)(t & 0xffff);
   const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
@@ -145,7 +167,7 @@ __global__ __launch_bounds__(256) void k_build_coupling(const PairArgs a, const 
   __syncthreads();
   float val[4][4];
   pair_tile(a, sXr, sXc, ty, tx, val);
-  float(*sT)[TILE + 1] = reinterpret_cast<float(*)[TILE + 1]>(&sX[0][0][0]);
+  float(*sT)[TILE + 1] = reinterpret_cast<float(*)[TILE + 1]>(lds_raw);
   // only blocks between DIFFERENT clusters enter K' (eq. (odsplit)): same-cluster entries are 0
   store_tile(C, ldc, p0, q0, tr != tc, val, sT, ty, tx, tid,
              [ncr, r](int p, int q) { return p < ncr && q < ncr && (p / r) != (q / r); },
@@ -211,13 +233,14 @@ __global__ void k_fill(float* __restrict__ p, uint64_t n, float v) {
 }
 
 // dense export with optional lower-triangle mask
-__global__ void k_export(const float* __restrict__ src, uint64_t lds, float* __restrict__ dst, int64_t ldd,
+template <typename ST>
+__global__ void k_export(const ST* __restrict__ src, uint64_t lds, float* __restrict__ dst, int64_t ldd,
                          int rows, int cols, int lower_only) {
   const int64_t total = (int64_t)rows * cols;
   for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
        idx += (int64_t)gridDim.x * blockDim.x) {
     const int p = (int)(idx / cols), q = (int)(idx - (int64_t)p * cols);
-    float v = src[(uint64_t)p * lds + q];
+    float v = (float)src[(uint64_t)p * lds + q];
     if (lower_only && q > p) v = 0.f;
     dst[(int64_t)p * ldd + q] = v;
   }
@@ -263,20 +286,18 @@ int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s) {
   const double alpha = theta[L.p - 2], sigma2 = theta[L.p - 1];
   PairArgs a;
   const double half_log2e = 0.5 * 1.4426950408889634074;
-  for (int k = 0; k < MAX_D; ++k) { a.w_hi[k] = 0.f; a.w_lo[k] = 0.f; }
+  for (int k = 0; k < MAX_D; ++k) a.w[k] = 0.0;
   for (int k = 0; k < L.d; ++k) {
     const double ell = iso ? theta[0] : theta[k];
-    const double w = half_log2e / (ell * ell);
-    a.w_hi[k] = (float)w;
-    a.w_lo[k] = (float)(w - (double)a.w_hi[k]);
+    a.w[k] = half_log2e / (ell * ell);
   }
-  a.a_hi = (float)alpha;
-  a.a_lo = (float)(alpha - (double)a.a_hi);
+  a.alpha = alpha;
   a.diag_val = (float)(alpha + sigma2);
   a.d = L.d;
   c->diag_residual = (float)((alpha + sigma2) - (double)a.diag_val);
-  hipLaunchKernelGGL(k_build_diag, dim3((unsigned)L.n_diag_tiles), dim3(256), 0, s, a, c->d_cl, c->d_tiles, c->X, c->Kd);
-  hipLaunchKernelGGL(k_build_coupling, dim3((unsigned)L.n_c_tiles), dim3(256), 0, s, a, c->d_tiles + L.n_diag_tiles,
+  const size_t lds = pair_lds_bytes(L.d);
+  hipLaunchKernelGGL(k_build_diag, dim3((unsigned)L.n_diag_tiles), dim3(256), lds, s, a, c->d_cl, c->d_tiles, c->X, c->Kd);
+  hipLaunchKernelGGL(k_build_coupling, dim3((unsigned)L.n_c_tiles), dim3(256), lds, s, a, c->d_tiles + L.n_diag_tiles,
                      c->reps, c->C, L.ncr, L.r, (uint32_t)L.ldc);
   NUGPR_HIP(hipGetLastError());
   c->built = true;
@@ -303,12 +324,16 @@ int launch_export(nugpr_ctx* c, int what, int index, float* dst, int64_t ld, hip
     src = c->Wd + (uint64_t)L.cl[index].row0 * L.ldw; lds = L.ldw; rows = (int)L.cl[index].b; cols = L.r;
   } else if (what == 5) {
     if (!c->factored) { set_error("nothing stored yet"); return NUGPR_ERR_STATE; }
-    src = c->Bv; lds = L.T; rows = (int)L.n; cols = L.T;
+    src = nullptr; lds = L.T; rows = (int)L.n; cols = L.T;
   } else if (what == 6) {
     src = c->reps; lds = L.d; rows = L.ncr; cols = L.d;
   } else { set_error("unknown export selector"); return NUGPR_ERR_INVALID; }
   if (ld < cols) { set_error("ld smaller than the number of columns"); return NUGPR_ERR_INVALID; }
-  hipLaunchKernelGGL(k_export, dim3(2048), dim3(256), 0, s, src, lds, dst, ld, rows, cols, lower);
+  if (what == 5 && c->acc64)
+    hipLaunchKernelGGL((k_export<double>), dim3(2048), dim3(256), 0, s, (const double*)c->Bv, lds, dst, ld, rows, cols, lower);
+  else
+    hipLaunchKernelGGL((k_export<float>), dim3(2048), dim3(256), 0, s, what == 5 ? (const float*)c->Bv : src, lds, dst, ld,
+                       rows, cols, lower);
   NUGPR_HIP(hipGetLastError());
   NUGPR_HIP(hipStreamSynchronize(s));
   return NUGPR_OK;

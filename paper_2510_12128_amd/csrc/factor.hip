@@ -329,20 +329,22 @@ __global__ __launch_bounds__(256) void k_logdet(const ClusterInfo* __restrict__ 
 __global__ void k_reset_bad(PcgState* st) { st->bad_cluster = INT_MAX; }
 
 // V = [0 | Z] (n x T) from the probes (n x t)
-__global__ void k_probes_to_block(const float* __restrict__ Z, float* __restrict__ V, int64_t n, int t) {
+template <typename VT>
+__global__ void k_probes_to_block(const float* __restrict__ Z, VT* __restrict__ V, int64_t n, int t) {
   const int T = t + 1;
   const int64_t total = n * T;
   for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
        idx += (int64_t)gridDim.x * blockDim.x) {
     const int64_t p = idx / T;
     const int col = (int)(idx - p * T);
-    V[idx] = col == 0 ? 0.f : Z[p * t + col - 1];
+    V[idx] = col == 0 ? (VT)0 : (VT)Z[p * t + col - 1];
   }
 }
 
-__global__ void k_set_col0(float* __restrict__ B, const float* __restrict__ y, int64_t n, int T) {
+template <typename VT>
+__global__ void k_set_col0(VT* __restrict__ B, const float* __restrict__ y, int64_t n, int T) {
   for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < n; p += (int64_t)gridDim.x * blockDim.x)
-    B[p * T] = y[p];
+    B[p * T] = (VT)y[p];
 }
 
 int launch_factor(nugpr_ctx* c, hipStream_t s) {
@@ -365,13 +367,17 @@ int launch_factor(nugpr_ctx* c, hipStream_t s) {
   NUGPR_HIP(hipGetLastError());
   // right-hand sides B = [y | L Z]
   if (L.t > 0) {
-    hipLaunchKernelGGL(k_probes_to_block, dim3(1024), dim3(256), 0, s, c->probes, c->Vv, (int64_t)L.n, L.t);
+    if (c->acc64)
+      hipLaunchKernelGGL((k_probes_to_block<double>), dim3(1024), dim3(256), 0, s, c->probes, (double*)c->Vv, (int64_t)L.n, L.t);
+    else
+      hipLaunchKernelGGL((k_probes_to_block<float>), dim3(1024), dim3(256), 0, s, c->probes, (float*)c->Vv, (int64_t)L.n, L.t);
     StripPort p0{};
     p0.A = c->Lf; p0.in = c->Vv; p0.out = c->Bv; p0.nin = 1;
-    int rc = launch_strip(c->tab_lowL, p0, p0, L.T, s);
+    int rc = launch_strip(c->tab_lowL, p0, p0, L.T, c->acc64, s);
     if (rc) return rc;
   }
-  hipLaunchKernelGGL(k_set_col0, dim3(1024), dim3(256), 0, s, c->Bv, c->y, (int64_t)L.n, L.T);
+  if (c->acc64) hipLaunchKernelGGL((k_set_col0<double>), dim3(1024), dim3(256), 0, s, (double*)c->Bv, c->y, (int64_t)L.n, L.T);
+  else hipLaunchKernelGGL((k_set_col0<float>), dim3(1024), dim3(256), 0, s, (float*)c->Bv, c->y, (int64_t)L.n, L.T);
   NUGPR_HIP(hipGetLastError());
   return NUGPR_OK;
 }

@@ -83,7 +83,7 @@ int plan_layout(const nugpr_problem* pb, uint32_t flags, Layout& L) {
 
   size_t cur = 0;
   const size_t f = sizeof(float);
-  const size_t vec = (size_t)L.n * L.T * f;
+  const size_t vec = (size_t)L.n * L.T * sizeof(double);      // fp64 vector blocks (fp32 mode uses half)
   L.o_cl = take(cur, sizeof(ClusterInfo) * L.nc);
   L.o_Kd = take(cur, L.kd_elems * f);
   L.o_Lf = take(cur, L.kd_elems * f);
@@ -99,8 +99,9 @@ int plan_layout(const nugpr_problem* pb, uint32_t flags, Layout& L) {
   L.o_D = take(cur, vec);
   L.o_Q = take(cur, vec);
   L.o_V = take(cur, vec);
-  L.o_Spart = take(cur, (size_t)L.nsS * L.ncr * L.T * f);
-  L.o_Ppart = take(cur, (size_t)L.nsP * L.ncr * L.T * f);
+  L.o_U = take(cur, vec);
+  L.o_Spart = take(cur, (size_t)L.nsS * L.ncr * L.T * sizeof(double));
+  L.o_Ppart = take(cur, (size_t)L.nsP * L.ncr * L.T * sizeof(double));
   L.o_dot = take(cur, (size_t)2 * L.n_dot_blocks * MAX_COLS * sizeof(double));
   L.o_state = take(cur, sizeof(PcgState));
   L.o_alog = take(cur, (size_t)L.max_iter * MAX_COLS * sizeof(double));

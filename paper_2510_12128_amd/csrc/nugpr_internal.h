@@ -49,9 +49,9 @@ struct StripItem {
 static_assert(sizeof(StripItem) == 48, "StripItem layout");
 
 struct StripPort {
-  const float* A;            // matrix base
-  const float* in;           // input vector block(s)
-  float* out;                // output vector block(s)
+  const float* A;            // matrix base (always fp32)
+  const void* in;            // input vector block(s), fp32 or fp64 by the arithmetic mode
+  void* out;                 // output vector block(s), same type
   uint64_t in_part_stride;   // elements between the nin input slabs (summed on load)
   uint64_t out_part_stride;  // elements between output slabs
   int32_t nin;
@@ -109,7 +109,7 @@ struct Layout {
   uint64_t kd_elems = 0, wt_elems = 0;
   // byte offsets into the workspace
   size_t o_cl = 0, o_Kd = 0, o_Lf = 0, o_G = 0, o_C = 0, o_Wd = 0, o_Wt = 0, o_reps = 0;
-  size_t o_B = 0, o_X = 0, o_R = 0, o_Z = 0, o_D = 0, o_Q = 0, o_V = 0;
+  size_t o_B = 0, o_X = 0, o_R = 0, o_Z = 0, o_D = 0, o_Q = 0, o_V = 0, o_U = 0;
   size_t o_Spart = 0, o_Ppart = 0, o_dot = 0, o_state = 0, o_alog = 0, o_blog = 0;
   size_t o_theta = 0, o_logdet = 0, o_tiles = 0, o_items = 0;
   size_t items_bytes = 0;
@@ -131,8 +131,11 @@ struct nugpr_ctx {
   // device views into the workspace
   nugpr::ClusterInfo* d_cl = nullptr;
   float *Kd = nullptr, *Lf = nullptr, *G = nullptr, *C = nullptr, *Wd = nullptr, *Wt = nullptr, *reps = nullptr;
-  float *Bv = nullptr, *Xv = nullptr, *Rv = nullptr, *Zv = nullptr, *Dv = nullptr, *Qv = nullptr, *Vv = nullptr;
-  float *Spart = nullptr, *Ppart = nullptr;
+  // vector blocks: fp64 when acc64, else fp32 (sized for fp64 either way)
+  void *Bv = nullptr, *Xv = nullptr, *Rv = nullptr, *Zv = nullptr, *Dv = nullptr, *Qv = nullptr, *Vv = nullptr,
+       *Uv = nullptr;
+  void *Spart = nullptr, *Ppart = nullptr;
+  bool acc64 = true;                     // arithmetic mode of the operator applications
   double *dotpart = nullptr, *alog = nullptr, *blog = nullptr, *d_theta = nullptr, *d_logdet = nullptr;
   nugpr::PcgState* d_state = nullptr;
   uint64_t* d_tiles = nullptr;       // packed (cluster, tile row, tile col) list for assembly
@@ -166,17 +169,21 @@ int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s);
 int launch_export(nugpr_ctx* c, int what, int index, float* dst, int64_t ld, hipStream_t s);
 
 // strip_gemm.hip ------------------------------------------------------------
-int launch_strip(const StripTable& tab, const StripPort& p0, const StripPort& p1, int T, hipStream_t s);
+int launch_strip(const StripTable& tab, const StripPort& p0, const StripPort& p1, int T, bool acc64,
+                 hipStream_t s);
 
 // factor.hip ----------------------------------------------------------------
 int launch_factor(nugpr_ctx* c, hipStream_t s);
 
 // pcg.hip ---------------------------------------------------------------------
-int run_matvec(nugpr_ctx* c, const float* D, float* Q, int T, hipStream_t s);
-int run_precond(nugpr_ctx* c, const float* R, float* Z, int T, hipStream_t s);
-int run_pcg(nugpr_ctx* c, const float* B, float* X, int T, int32_t* iters, double* alpha, double* beta,
+// (vector blocks are the context's internal type: fp64 when acc64, else fp32)
+int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s);
+int run_precond(nugpr_ctx* c, const void* R, void* Z, int T, hipStream_t s);
+int run_pcg(nugpr_ctx* c, const void* B, void* X, int T, int32_t* iters, double* alpha, double* beta,
             int* max_it_used, hipStream_t s);
-int run_dot_col(nugpr_ctx* c, const float* A, const float* B, int T, double* out_host, hipStream_t s);
+int run_dot_col(nugpr_ctx* c, const void* A, const void* B, int T, double* out_host, hipStream_t s);
+int to_internal(nugpr_ctx* c, const float* src, void* dst, int64_t count, hipStream_t s);
+int from_internal(nugpr_ctx* c, const void* src, float* dst, int64_t count, hipStream_t s);
 
 // slq.cpp ---------------------------------------------------------------------
 // e_1^T log(T) e_1 for the k x k Lanczos matrix built from CG coefficients.

@@ -2,11 +2,12 @@
 // the two operator applications it alternates: the block-low-rank product K' D and the
 // block-Jacobi preconditioner M^-1 R.
 //
-// All T columns advance in lock step.  Vector blocks are n x T row-major fp32; every
-// reduction that feeds a CG coefficient (the paper's batched dot products) is accumulated
-// in fp64 in a fixed order: per-workgroup partial sums, then one small kernel that adds
-// them, computes alpha / beta per column and updates the convergence mask on the device.
-// The host reads back one 16-byte flag record per iteration (O(1) traffic, Section 4).
+// All T columns advance in lock step.  Vector blocks are n x T row-major, fp64 or fp32
+// according to the context's arithmetic mode (VT below); every reduction that feeds a CG
+// coefficient (the paper's batched dot products) is accumulated in fp64 in a fixed order:
+// per-workgroup partial sums, then one small kernel that adds them, computes alpha / beta
+// per column and updates the convergence mask on the device.  The host reads back one
+// 16-byte flag record per iteration (O(1) traffic, Section 4).
 #include <algorithm>
 #include <cmath>
 #include <cstring>
@@ -18,9 +19,9 @@ namespace nugpr {
 // ---------------------------------------------------------------------------
 // per-column dot products: partial[which][block][col] = sum over the block's rows
 // ---------------------------------------------------------------------------
-template <int NP>
-__global__ __launch_bounds__(256) void k_dot(const float* __restrict__ A0, const float* __restrict__ B0,
-                                             const float* __restrict__ A1, const float* __restrict__ B1,
+template <int NP, typename VT>
+__global__ __launch_bounds__(256) void k_dot(const VT* __restrict__ A0, const VT* __restrict__ B0,
+                                             const VT* __restrict__ A1, const VT* __restrict__ B1,
                                              int64_t n, int T, double* __restrict__ partial) {
   __shared__ double red[NP][256];
   const int rpp = 256 / T;                      // rows per pass
@@ -34,8 +35,8 @@ __global__ __launch_bounds__(256) void k_dot(const float* __restrict__ A0, const
   if (live) {
     for (int64_t r = r0 + myrow; r < r1; r += rpp) {
       const int64_t idx = r * T + col;
-      s0 += (double)A0[idx] * (double)B0[idx];
-      if (NP > 1) s1 += (double)A1[idx] * (double)B1[idx];
+      s0 = fma((double)A0[idx], (double)B0[idx], s0);
+      if (NP > 1) s1 = fma((double)A1[idx], (double)B1[idx], s1);
     }
   }
   red[0][tid] = s0;
@@ -142,25 +143,27 @@ __global__ __launch_bounds__(256) void k_pcg_beta(PcgState* __restrict__ st, con
   }
 }
 
-// X += D diag(alpha); R -= Q diag(alpha)
-__global__ __launch_bounds__(256) void k_update_xr(float* __restrict__ X, float* __restrict__ R,
-                                                   const float* __restrict__ D, const float* __restrict__ Q,
+// X += D diag(alpha); R -= Q diag(alpha)   (alpha stays in fp64: rounding it to fp32 would
+// scale the whole step coherently)
+template <typename VT>
+__global__ __launch_bounds__(256) void k_update_xr(VT* __restrict__ X, VT* __restrict__ R,
+                                                   const VT* __restrict__ D, const VT* __restrict__ Q,
                                                    const PcgState* __restrict__ st, int64_t n, int T) {
   const int rpp = 256 / T;
   const int tid = threadIdx.x;
   const int myrow = tid / T, col = tid - myrow * T;
   if (myrow >= rpp) return;
-  // alpha stays in fp64: rounding it to fp32 would scale the whole step coherently
   const double a = st->alpha[col];
   for (int64_t r = (int64_t)blockIdx.x * rpp + myrow; r < n; r += (int64_t)gridDim.x * rpp) {
     const int64_t idx = r * T + col;
-    X[idx] = (float)fma(a, (double)D[idx], (double)X[idx]);
-    R[idx] = (float)fma(-a, (double)Q[idx], (double)R[idx]);
+    X[idx] = (VT)fma(a, (double)D[idx], (double)X[idx]);
+    R[idx] = (VT)fma(-a, (double)Q[idx], (double)R[idx]);
   }
 }
 
 // D = Z + D diag(beta) for active columns, 0 for stopped ones
-__global__ __launch_bounds__(256) void k_update_d(float* __restrict__ D, const float* __restrict__ Z,
+template <typename VT>
+__global__ __launch_bounds__(256) void k_update_d(VT* __restrict__ D, const VT* __restrict__ Z,
                                                   const PcgState* __restrict__ st, int64_t n, int T) {
   const int rpp = 256 / T;
   const int tid = threadIdx.x;
@@ -170,7 +173,7 @@ __global__ __launch_bounds__(256) void k_update_d(float* __restrict__ D, const f
   const bool act = st->active[col] != 0;
   for (int64_t r = (int64_t)blockIdx.x * rpp + myrow; r < n; r += (int64_t)gridDim.x * rpp) {
     const int64_t idx = r * T + col;
-    D[idx] = act ? (float)fma(bta, (double)D[idx], (double)Z[idx]) : 0.f;
+    D[idx] = act ? (VT)fma(bta, (double)D[idx], (double)Z[idx]) : (VT)0;
   }
 }
 
@@ -180,37 +183,57 @@ __global__ void k_copy_flags(const PcgState* __restrict__ st, HostFlags* __restr
   out->bad_cluster = st->bad_cluster;
 }
 
+template <typename SRC, typename DST>
+__global__ void k_convert(const SRC* __restrict__ src, DST* __restrict__ dst, int64_t count) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x)
+    dst[i] = (DST)src[i];
+}
+
+int to_internal(nugpr_ctx* c, const float* src, void* dst, int64_t count, hipStream_t s) {
+  if (c->acc64) hipLaunchKernelGGL((k_convert<float, double>), dim3(1024), dim3(256), 0, s, src, (double*)dst, count);
+  else NUGPR_HIP(hipMemcpyAsync(dst, src, (size_t)count * sizeof(float), hipMemcpyDeviceToDevice, s));
+  NUGPR_HIP(hipGetLastError());
+  return NUGPR_OK;
+}
+
+int from_internal(nugpr_ctx* c, const void* src, float* dst, int64_t count, hipStream_t s) {
+  if (c->acc64) hipLaunchKernelGGL((k_convert<double, float>), dim3(1024), dim3(256), 0, s, (const double*)src, dst, count);
+  else NUGPR_HIP(hipMemcpyAsync(dst, src, (size_t)count * sizeof(float), hipMemcpyDeviceToDevice, s));
+  NUGPR_HIP(hipGetLastError());
+  return NUGPR_OK;
+}
+
 // ---------------------------------------------------------------------------
-// operator applications
+// operator applications on internal vector blocks
 // ---------------------------------------------------------------------------
-int run_matvec(nugpr_ctx* c, const float* D, float* Q, int T, hipStream_t s) {
+int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s) {
   const Layout& L = c->L;
   int rc;
   const uint64_t spart = (uint64_t)L.ncr * T, ppart = (uint64_t)L.ncr * T;
   // S_j = W_j^T D_j, split over column slabs of W_j^T
   StripPort s0{};
   s0.A = c->Wt; s0.in = D; s0.out = c->Spart; s0.nin = 1; s0.out_part_stride = spart;
-  if ((rc = launch_strip(c->tab_WtD, s0, s0, T, s))) return rc;
+  if ((rc = launch_strip(c->tab_WtD, s0, s0, T, c->acc64, s))) return rc;
   // Q_i = K_ii D_i   and   P = C_offdiag S (column slabs), one launch
   StripPort k0{}, k1{};
   k0.A = c->Kd; k0.in = D; k0.out = Q; k0.nin = 1; k0.diag_add = c->diag_residual;
   k1.A = c->C; k1.in = c->Spart; k1.nin = L.nsS; k1.in_part_stride = spart; k1.out = c->Ppart;
   k1.out_part_stride = ppart;
-  if ((rc = launch_strip(c->tab_KC, k0, k1, T, s))) return rc;
+  if ((rc = launch_strip(c->tab_KC, k0, k1, T, c->acc64, s))) return rc;
   // Q_i += W_i P_i
   StripPort w0{};
   w0.A = c->Wd; w0.in = c->Ppart; w0.nin = L.nsP; w0.in_part_stride = ppart; w0.out = Q; w0.accumulate = 1;
-  return launch_strip(c->tab_WP, w0, w0, T, s);
+  return launch_strip(c->tab_WP, w0, w0, T, c->acc64, s);
 }
 
-int run_precond(nugpr_ctx* c, const float* R, float* Z, int T, hipStream_t s) {
+int run_precond(nugpr_ctx* c, const void* R, void* Z, int T, hipStream_t s) {
   int rc;
   StripPort a{};
   a.A = c->G; a.in = R; a.out = c->Vv; a.nin = 1;
-  if ((rc = launch_strip(c->tab_lowG, a, a, T, s))) return rc;
+  if ((rc = launch_strip(c->tab_lowG, a, a, T, c->acc64, s))) return rc;
   StripPort b{};
   b.A = c->G; b.in = c->Vv; b.out = Z; b.nin = 1;
-  return launch_strip(c->tab_upG, b, b, T, s);
+  return launch_strip(c->tab_upG, b, b, T, c->acc64, s);
 }
 
 static int elementwise_grid(int64_t n, int T) {
@@ -219,10 +242,11 @@ static int elementwise_grid(int64_t n, int T) {
   return (int)std::min<int64_t>(g, 4096);
 }
 
-int run_dot_col(nugpr_ctx* c, const float* A, const float* B, int T, double* out_host, hipStream_t s) {
+template <typename VT>
+static int dot_col_t(nugpr_ctx* c, const VT* A, const VT* B, int T, double* out_host, hipStream_t s) {
   const Layout& L = c->L;
   const int nb = L.n_dot_blocks;
-  hipLaunchKernelGGL((k_dot<1>), dim3(nb), dim3(256), 0, s, A, B, A, B, (int64_t)L.n, T, c->dotpart);
+  hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, A, B, A, B, (int64_t)L.n, T, c->dotpart);
   NUGPR_HIP(hipGetLastError());
   // small: add the partials on the host in block order
   NUGPR_HIP(hipMemcpyAsync(c->h_buf, c->dotpart, (size_t)nb * MAX_COLS * sizeof(double), hipMemcpyDeviceToHost, s));
@@ -235,24 +259,30 @@ int run_dot_col(nugpr_ctx* c, const float* A, const float* B, int T, double* out
   return NUGPR_OK;
 }
 
-int run_pcg(nugpr_ctx* c, const float* B, float* X, int T, int32_t* iters, double* alpha, double* beta,
-            int* max_it_used, hipStream_t s) {
+int run_dot_col(nugpr_ctx* c, const void* A, const void* B, int T, double* out_host, hipStream_t s) {
+  if (c->acc64) return dot_col_t<double>(c, (const double*)A, (const double*)B, T, out_host, s);
+  return dot_col_t<float>(c, (const float*)A, (const float*)B, T, out_host, s);
+}
+
+template <typename VT>
+static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double* alpha, double* beta,
+                 int* max_it_used, hipStream_t s) {
   const Layout& L = c->L;
   const int64_t n = L.n;
-  const size_t bytes = (size_t)n * T * sizeof(float);
+  const size_t bytes = (size_t)n * T * sizeof(VT);
   const int nb = L.n_dot_blocks;
   const int eg = elementwise_grid(n, T);
   const double tol2 = c->params.tol * c->params.tol;
   const int max_iter = c->params.max_iter;
   int rc;
-  float *R = c->Rv, *Z = c->Zv, *D = c->Dv, *Q = c->Qv;
+  VT *R = (VT*)c->Rv, *Z = (VT*)c->Zv, *D = (VT*)c->Dv, *Q = (VT*)c->Qv;
   NUGPR_HIP(hipMemsetAsync(X, 0, bytes, s));
   NUGPR_HIP(hipMemcpyAsync(R, B, bytes, hipMemcpyDeviceToDevice, s));
   NUGPR_HIP(hipMemsetAsync(c->alog, 0, (size_t)max_iter * MAX_COLS * sizeof(double), s));
   NUGPR_HIP(hipMemsetAsync(c->blog, 0, (size_t)max_iter * MAX_COLS * sizeof(double), s));
   if ((rc = run_precond(c, R, Z, T, s))) return rc;
   NUGPR_HIP(hipMemcpyAsync(D, Z, bytes, hipMemcpyDeviceToDevice, s));
-  hipLaunchKernelGGL((k_dot<2>), dim3(nb), dim3(256), 0, s, R, R, R, Z, n, T, c->dotpart);
+  hipLaunchKernelGGL((k_dot<2, VT>), dim3(nb), dim3(256), 0, s, R, R, R, Z, n, T, c->dotpart);
   hipLaunchKernelGGL(k_pcg_begin, dim3(1), dim3(256), 0, s, c->d_state, c->dotpart, nb, T);
   NUGPR_HIP(hipGetLastError());
   int it = 0;
@@ -262,13 +292,13 @@ int run_pcg(nugpr_ctx* c, const float* B, float* X, int T, int32_t* iters, doubl
   NUGPR_HIP(hipStreamSynchronize(s));
   while (it < max_iter && c->h_flags->n_active > 0) {
     if ((rc = run_matvec(c, D, Q, T, s))) return rc;
-    hipLaunchKernelGGL((k_dot<1>), dim3(nb), dim3(256), 0, s, D, Q, D, Q, n, T, c->dotpart);
+    hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, D, Q, D, Q, n, T, c->dotpart);
     hipLaunchKernelGGL(k_pcg_alpha, dim3(1), dim3(256), 0, s, c->d_state, c->dotpart, nb, T, it, c->alog);
-    hipLaunchKernelGGL(k_update_xr, dim3(eg), dim3(256), 0, s, X, R, D, Q, c->d_state, n, T);
+    hipLaunchKernelGGL((k_update_xr<VT>), dim3(eg), dim3(256), 0, s, X, R, D, Q, c->d_state, n, T);
     if ((rc = run_precond(c, R, Z, T, s))) return rc;
-    hipLaunchKernelGGL((k_dot<2>), dim3(nb), dim3(256), 0, s, R, R, R, Z, n, T, c->dotpart);
+    hipLaunchKernelGGL((k_dot<2, VT>), dim3(nb), dim3(256), 0, s, R, R, R, Z, n, T, c->dotpart);
     hipLaunchKernelGGL(k_pcg_beta, dim3(1), dim3(256), 0, s, c->d_state, c->dotpart, nb, T, it, tol2, c->blog);
-    hipLaunchKernelGGL(k_update_d, dim3(eg), dim3(256), 0, s, D, Z, c->d_state, n, T);
+    hipLaunchKernelGGL((k_update_d<VT>), dim3(eg), dim3(256), 0, s, D, Z, c->d_state, n, T);
     hipLaunchKernelGGL(k_copy_flags, dim3(1), dim3(1), 0, s, c->d_state, c->h_flags);
     NUGPR_HIP(hipGetLastError());
     NUGPR_HIP(hipStreamSynchronize(s));
@@ -301,6 +331,12 @@ int run_pcg(nugpr_ctx* c, const float* B, float* X, int T, int32_t* iters, doubl
   }
   if (indefinite) return NUGPR_INDEFINITE;
   return all_conv ? NUGPR_OK : NUGPR_NOT_CONVERGED;
+}
+
+int run_pcg(nugpr_ctx* c, const void* B, void* X, int T, int32_t* iters, double* alpha, double* beta,
+            int* max_it_used, hipStream_t s) {
+  if (c->acc64) return pcg_t<double>(c, (const double*)B, (double*)X, T, iters, alpha, beta, max_it_used, s);
+  return pcg_t<float>(c, (const float*)B, (float*)X, T, iters, alpha, beta, max_it_used, s);
 }
 
 }  // namespace nugpr

