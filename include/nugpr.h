@@ -186,6 +186,19 @@ int nugpr_export(nugpr_ctx* ctx, int32_t what, int32_t index, float* dst /*DEVIC
 /* Number of hyperparameters p the context expects in theta / log_theta. */
 int32_t nugpr_num_hyper(const nugpr_ctx* ctx);
 
+/* Live timing of the dominant kernel (the launch that streams K_diag and C once per
+ * product, inside nugpr_matvec and every PCG iteration).  After
+ * nugpr_profile_enable(ctx, 1) each such launch is bracketed by HIP events on the stream
+ * it runs on (at most 2048 launches are kept; later ones go untimed).
+ * nugpr_profile_read synchronises `stream`, returns the summed kernel time in
+ * milliseconds and the number of timed launches, and resets the counters.
+ * nugpr_profile_bytes returns the bytes one such launch moves at `ncols` columns:
+ * the stored matrices it streams (4 * (sum b_i^2 + (n_c r)^2)) plus the vector blocks
+ * it reads and writes in the context's arithmetic mode. */
+int nugpr_profile_enable(nugpr_ctx* ctx, int32_t on);
+int nugpr_profile_read(nugpr_ctx* ctx, double* total_ms /*HOST*/, int32_t* launches /*HOST*/, void* stream);
+double nugpr_profile_bytes(const nugpr_ctx* ctx, int32_t ncols);
+
 #ifdef __cplusplus
 }
 #endif

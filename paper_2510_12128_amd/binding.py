@@ -90,6 +90,12 @@ def load_library():
     lib.nugpr_export.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_int64, vp]
     lib.nugpr_num_hyper.restype = C.c_int32
     lib.nugpr_num_hyper.argtypes = [vp]
+    lib.nugpr_profile_enable.restype = C.c_int
+    lib.nugpr_profile_enable.argtypes = [vp, C.c_int32]
+    lib.nugpr_profile_read.restype = C.c_int
+    lib.nugpr_profile_read.argtypes = [vp, dp, ip, vp]
+    lib.nugpr_profile_bytes.restype = C.c_double
+    lib.nugpr_profile_bytes.argtypes = [vp, C.c_int32]
     _LIB = lib
     return lib
 
@@ -235,6 +241,25 @@ class Context:
         code = _check(self.lib.nugpr_train_step(self.handle, _dptr(phi), _dptr(m), _dptr(v), C.byref(st),
                                                 C.byref(nll0), _dptr(g), self._stream()))
         return dict(code=code, log_theta=phi, adam_m=m, adam_v=v, step=st.value, nll0=nll0.value, grad=g)
+
+    def nugpr_matvec_into(self, D, Q):
+        """nugpr_matvec on caller-held device tensors (no allocation; used for timing)."""
+        return _check(self.lib.nugpr_matvec(self.handle, D.data_ptr(), Q.data_ptr(), D.shape[1], self._stream()))
+
+    def nugpr_precond_apply_into(self, R, Z):
+        return _check(self.lib.nugpr_precond_apply(self.handle, R.data_ptr(), Z.data_ptr(), R.shape[1],
+                                                   self._stream()))
+
+    def nugpr_profile_enable(self, on=True):
+        return _check(self.lib.nugpr_profile_enable(self.handle, 1 if on else 0))
+
+    def nugpr_profile_read(self):
+        ms, cnt = C.c_double(), C.c_int32()
+        _check(self.lib.nugpr_profile_read(self.handle, C.byref(ms), C.byref(cnt), self._stream()))
+        return ms.value, cnt.value
+
+    def nugpr_profile_bytes(self, ncols):
+        return float(self.lib.nugpr_profile_bytes(self.handle, int(ncols)))
 
     def nugpr_export(self, what, index=0):
         if what in (EXPORT_K, EXPORT_L, EXPORT_LINV):

@@ -195,8 +195,53 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   return NUGPR_OK;
 }
 
+int nugpr_profile_enable(nugpr_ctx* c, int32_t on) {
+  if (!c) { set_error("ctx is null"); return NUGPR_ERR_INVALID; }
+  if (on && c->prof_ev.empty()) {
+    c->prof_ev.resize(2 * 2048);
+    for (size_t i = 0; i < c->prof_ev.size(); ++i) {
+      hipError_t e = hipEventCreate(&c->prof_ev[i]);
+      if (e != hipSuccess) {
+        for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(c->prof_ev[j]);
+        c->prof_ev.clear();
+        return hip_fail(e, "hipEventCreate");
+      }
+    }
+  }
+  c->prof_on = on != 0;
+  c->prof_used = 0;
+  return NUGPR_OK;
+}
+
+int nugpr_profile_read(nugpr_ctx* c, double* total_ms, int32_t* launches, void* stream) {
+  if (!c || !total_ms || !launches) { set_error("null argument"); return NUGPR_ERR_INVALID; }
+  NUGPR_HIP(hipStreamSynchronize(as_stream(stream)));
+  double acc = 0.0;
+  for (int i = 0; i < c->prof_used; ++i) {
+    float ms = 0.f;
+    NUGPR_HIP(hipEventElapsedTime(&ms, c->prof_ev[2 * i], c->prof_ev[2 * i + 1]));
+    acc += ms;
+  }
+  *total_ms = acc;
+  *launches = c->prof_used;
+  c->prof_used = 0;
+  return NUGPR_OK;
+}
+
+double nugpr_profile_bytes(const nugpr_ctx* c, int32_t ncols) {
+  if (!c || ncols < 1) return 0.0;
+  const Layout& L = c->L;
+  double entries = (double)L.ncr * (double)L.ncr;
+  for (const auto& ci : L.cl) entries += (double)ci.b * (double)ci.b;
+  const double vs = c->acc64 ? 8.0 : 4.0;
+  // reads D and the S slabs, writes Q and the P slabs
+  const double vec = vs * ncols * (2.0 * (double)L.n + (double)L.ncr * (L.nsS + L.nsP));
+  return 4.0 * entries + vec;
+}
+
 int nugpr_destroy(nugpr_ctx* c) {
   if (!c) return NUGPR_OK;
+  for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
   if (c->h_flags) (void)hipHostFree(c->h_flags);
   if (c->h_buf) (void)hipHostFree(c->h_buf);
   delete c;

@@ -140,6 +140,10 @@ struct nugpr_ctx {
   nugpr::PcgState* d_state = nullptr;
   uint64_t* d_tiles = nullptr;       // packed (cluster, tile row, tile col) list for assembly
   nugpr::StripTable tab_WtD, tab_KC, tab_WP, tab_lowG, tab_upG, tab_lowL;
+  // optional event timing of the K_diag / C streaming launch
+  bool prof_on = false;
+  std::vector<hipEvent_t> prof_ev;       // start/stop pairs
+  int prof_used = 0;                     // pairs recorded since the last read
   nugpr::HostFlags* h_flags = nullptr;   // pinned
   double* h_buf = nullptr;               // pinned scratch for small device->host reads
   size_t h_buf_doubles = 0;
@@ -171,6 +175,9 @@ int launch_export(nugpr_ctx* c, int what, int index, float* dst, int64_t ld, hip
 // strip_gemm.hip ------------------------------------------------------------
 int launch_strip(const StripTable& tab, const StripPort& p0, const StripPort& p1, int T, bool acc64,
                  hipStream_t s);
+
+int launch_sum_parts(const void* in, void* out, int64_t count, int parts, uint64_t stride, bool acc64,
+                     hipStream_t s);
 
 // factor.hip ----------------------------------------------------------------
 int launch_factor(nugpr_ctx* c, hipStream_t s);

@@ -210,19 +210,26 @@ int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s) {
   const Layout& L = c->L;
   int rc;
   const uint64_t spart = (uint64_t)L.ncr * T, ppart = (uint64_t)L.ncr * T;
-  // S_j = W_j^T D_j, split over column slabs of W_j^T
+  // S_j = W_j^T D_j, computed in column slabs of W_j^T that are then added up
   StripPort s0{};
   s0.A = c->Wt; s0.in = D; s0.out = c->Spart; s0.nin = 1; s0.out_part_stride = spart;
   if ((rc = launch_strip(c->tab_WtD, s0, s0, T, c->acc64, s))) return rc;
+  if (L.nsS > 1 && (rc = launch_sum_parts(c->Spart, c->Spart, (int64_t)spart, L.nsS, spart, c->acc64, s))) return rc;
   // Q_i = K_ii D_i   and   P = C_offdiag S (column slabs), one launch
   StripPort k0{}, k1{};
   k0.A = c->Kd; k0.in = D; k0.out = Q; k0.nin = 1; k0.diag_add = c->diag_residual;
-  k1.A = c->C; k1.in = c->Spart; k1.nin = L.nsS; k1.in_part_stride = spart; k1.out = c->Ppart;
-  k1.out_part_stride = ppart;
+  k1.A = c->C; k1.in = c->Spart; k1.nin = 1; k1.out = c->Ppart; k1.out_part_stride = ppart;
+  const bool timed = c->prof_on && (size_t)(2 * c->prof_used + 1) < c->prof_ev.size();
+  if (timed) NUGPR_HIP(hipEventRecord(c->prof_ev[2 * c->prof_used], s));
   if ((rc = launch_strip(c->tab_KC, k0, k1, T, c->acc64, s))) return rc;
+  if (timed) {
+    NUGPR_HIP(hipEventRecord(c->prof_ev[2 * c->prof_used + 1], s));
+    c->prof_used += 1;
+  }
+  if (L.nsP > 1 && (rc = launch_sum_parts(c->Ppart, c->Ppart, (int64_t)ppart, L.nsP, ppart, c->acc64, s))) return rc;
   // Q_i += W_i P_i
   StripPort w0{};
-  w0.A = c->Wd; w0.in = c->Ppart; w0.nin = L.nsP; w0.in_part_stride = ppart; w0.out = Q; w0.accumulate = 1;
+  w0.A = c->Wd; w0.in = c->Ppart; w0.nin = 1; w0.out = Q; w0.accumulate = 1;
   return launch_strip(c->tab_WP, w0, w0, T, c->acc64, s);
 }
 

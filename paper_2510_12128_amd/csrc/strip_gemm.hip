@@ -9,16 +9,18 @@
 //   tril(L_i) Z_i                                        -- probe right-hand sides
 //
 // Design (gfx950, wave64): a workgroup of 4 waves owns a strip of 64 matrix rows,
-// each wave 16 of them, and walks along the rows so every matrix element is read
-// from HBM exactly once, with 16-byte loads, for all T columns.  Lane (m, kg) of a
-// wave loads float4 A[row m][c + 16 s + 4 kg ..]; the four components feed four
-// 16x16x4 MFMAs, whose contraction index is the kg of the lane, so the column
+// each wave 16 of them, and walks along the rows in chunks of 64 columns so every
+// matrix element is read from HBM exactly once, with 16-byte loads, for all T columns.
+// Lane (m, kg) of a wave loads float4 A[row m][c + 16 s + 4 kg ..]; the four components
+// feed four 16x16x4 MFMAs, whose contraction index is the kg of the lane, so the column
 // permutation inside a 16-column group is absorbed by reading the matching rows of
 // the vector block from LDS (stored as 4-vectors over 4 consecutive rows).
 // Columns 1..T-1 (the probes) go through the matrix cores in groups of 16; column 0
 // (y) rides on the vector ALUs from the same registers, so T = 17 costs one MFMA
-// group, not two.  The vector block chunk is double-buffered in LDS, the matrix
-// chunk is prefetched one stage ahead in registers.
+// group, not two.  The vector block chunk is double-buffered in LDS.  The matrix
+// chunk lives in ONE register set: slot s is reloaded with the next chunk's data right
+// after it has been consumed, so each load has a full chunk period to land while few
+// registers are live, and occupancy hides the rest of the HBM latency.
 //
 // Two arithmetic modes, same data movement:
 //   ACC64 = true   vector blocks are fp64; the fp32 matrix entries are widened in
@@ -30,6 +32,7 @@
 // The CG coefficients and the SLQ estimate are Rayleigh quotients of these products
 // scaled by n, so rounding in the running sums enters the loss at first order; the fp64
 // mode removes it, the fp32 mode keeps it near sqrt(b) * 1e-7 per output entry.
+#include <algorithm>
 #include <type_traits>
 
 #include "nugpr_internal.h"
@@ -52,11 +55,13 @@ __device__ __forceinline__ int acc_row(int lane, int i) {
   return ACC64 ? (lane >> 4) + 4 * i : 4 * (lane >> 4) + i;
 }
 
-template <int NG, int CHUNK, bool ACC64>
+constexpr int CHUNK = 64;              // columns per pipeline stage
+constexpr int NL = CHUNK / 16;         // float4 loads per lane per chunk
+
+template <int NG, bool ACC64>
 __global__ __launch_bounds__(256) void k_strip(const StripArgs a) {
   typedef typename VecT<ACC64>::type VT;
   typedef typename std::conditional<ACC64, Quad64, Quad32>::type QuadT;
-  constexpr int NL = CHUNK / 16;                 // float4 loads per lane per chunk
   constexpr int NCOLM = NG > 0 ? 16 * NG : 1;    // columns handled by the matrix cores
   constexpr int NE = (CHUNK * (16 * NG + 1) + 255) / 256;   // staged vector elements per thread
   constexpr int NGA = NG > 0 ? NG : 1;
@@ -71,14 +76,18 @@ __global__ __launch_bounds__(256) void k_strip(const StripArgs a) {
   const int wave = tid >> 6, lane = tid & 63;
   const int m = lane & 15, kg = lane >> 4;
   const int nrows = (int)it.nrows;
-  const int lda = (int)it.lda;
   const int lr = wave * 16 + m;                               // local row this lane loads
   const int lrc = lr < nrows ? lr : nrows - 1;
-  const float* __restrict__ Arow = pt.A + it.a_off + (uint64_t)lrc * (uint64_t)lda;
-  const int diag = (int)it.row_in_block + lr;                 // diagonal column of that row
-  const int mode = it.mode;
+  const float* __restrict__ Arow = pt.A + it.a_off + (uint64_t)lrc * (uint64_t)it.lda + 4 * kg;
   const int c_begin = (int)it.c_begin, c_end = (int)it.c_end;
   const int nchunks = c_end > c_begin ? (c_end - c_begin + CHUNK - 1) / CHUNK : 0;
+  // columns this lane's row keeps: [q_lo, q_hi)
+  const int diag = (int)it.row_in_block + lr;
+  const int q_lo = it.mode == 2 ? diag : c_begin;
+  const int q_hi = it.mode == 1 ? (diag + 1 < c_end ? diag + 1 : c_end) : c_end;
+  // chunks that may hold dropped elements: the last one, and the one with the diagonal tile
+  const int mask_from = it.mode == 1 ? (int)it.row_in_block : c_end - (c_end - c_begin) % CHUNK;
+  const int mask_upto = it.mode == 2 ? (int)it.row_in_block + TILE : c_begin;
 
   // zero the LDS once: the padding columns of the MFMA operand are never written again
   {
@@ -87,7 +96,6 @@ __global__ __launch_bounds__(256) void k_strip(const StripArgs a) {
   }
   __syncthreads();
 
-  // accumulators
   v4f acc32[NGA][4];       // fp32 mode: four chains per group, restarted every chunk
   v4d acc64[NGA][2];       // fp64 mode: two chains per group (hides the MFMA issue latency)
   double dacc[NGA][4];     // fp32 mode: fp64 running sums
@@ -101,54 +109,74 @@ __global__ __launch_bounds__(256) void k_strip(const StripArgs a) {
     acc64[g][1] = (v4d){0.0, 0.0, 0.0, 0.0};
   }
 
-  // staging slots of this thread: flat element e of the chunk's (CHUNK x T) slab
+  // staging: thread `tid` moves flat elements e = tid + 256 k of the chunk's contiguous
+  // (CHUNK x T) slab; rows past the item's last column are staged as zero
   const int nelem = CHUNK * T;
-  int e_q[NE], e_col[NE];
-#pragma unroll
-  for (int k = 0; k < NE; ++k) {
-    int e = tid + 256 * k;
-    int q = (T == 1) ? e : (int)__umulhi((uint32_t)e, a.magicT);
-    e_q[k] = e < nelem ? q : -1;
-    e_col[k] = e - q * T;
-  }
-
-  auto load_A = [&](int c, float4 (&reg)[NL]) {
-#pragma unroll
-    for (int s = 0; s < NL; ++s) {
-      int col = c + 16 * s + 4 * kg;
-      if (col < lda) reg[s] = *reinterpret_cast<const float4*>(Arow + col);
-      else reg[s] = make_float4(0.f, 0.f, 0.f, 0.f);
-    }
-  };
   auto load_in = [&](int c, VT (&reg)[NE]) {
+    const VT* __restrict__ src = vin + (uint64_t)(it.in_row0 + (uint32_t)c) * (uint64_t)T;
+    const int lim = min(nelem, (c_end - c) * T);
 #pragma unroll
     for (int k = 0; k < NE; ++k) {
-      VT v = (VT)0;
-      int q = e_q[k];
-      if (q >= 0 && c + q < c_end) {
-        uint64_t idx = (uint64_t)(it.in_row0 + (uint32_t)(c + q)) * (uint64_t)T + (uint32_t)e_col[k];
-        v = vin[idx];
-        for (int part = 1; part < pt.nin; ++part) v += vin[idx + (uint64_t)part * pt.in_part_stride];
-      }
-      reg[k] = v;
+      const int e = tid + 256 * k;
+      reg[k] = e < lim ? src[e] : (VT)0;
     }
   };
   auto store_in = [&](int buf, const VT (&reg)[NE]) {
 #pragma unroll
     for (int k = 0; k < NE; ++k) {
-      int q = e_q[k];
-      if (q >= 0) {
-        int col = e_col[k];
+      const int e = tid + 256 * k;
+      if (e < nelem) {
+        const int q = (T == 1) ? e : (int)__umulhi((uint32_t)e, a.magicT);
+        const int col = e - q * T;
         if (col == 0) reinterpret_cast<VT*>(&sY[buf][q >> 2])[q & 3] = reg[k];
         else if (NG > 0) reinterpret_cast<VT*>(&sB[buf][(q >> 2) * NCOLM + (col - 1)])[q & 3] = reg[k];
       }
     }
   };
 
-  float4 areg[NL], anext[NL];
+  // one 16-column step: 4 MFMAs per column group + the y column on the vector ALUs
+  auto step = [&](const float4 av, int buf, int s) {
+    if constexpr (ACC64) {
+      const double ax = (double)av.x, ay = (double)av.y, az = (double)av.z, aw = (double)av.w;
+      if (NG > 0) {
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+          const Quad64 bv = sB[buf][(4 * s + kg) * NCOLM + 16 * g + m];
+          acc64[g][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(ax, bv.x, acc64[g][0], 0, 0, 0);
+          acc64[g][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(ay, bv.y, acc64[g][1], 0, 0, 0);
+          acc64[g][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(az, bv.z, acc64[g][0], 0, 0, 0);
+          acc64[g][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(aw, bv.w, acc64[g][1], 0, 0, 0);
+        }
+      }
+      const Quad64 yv = sY[buf][4 * s + kg];
+      daccy = fma(ax, yv.x, daccy);
+      daccy = fma(ay, yv.y, daccy);
+      daccy = fma(az, yv.z, daccy);
+      daccy = fma(aw, yv.w, daccy);
+    } else {
+      if (NG > 0) {
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+          const Quad32 bv = sB[buf][(4 * s + kg) * NCOLM + 16 * g + m];
+          acc32[g][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.x, bv.x, acc32[g][0], 0, 0, 0);
+          acc32[g][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.y, bv.y, acc32[g][1], 0, 0, 0);
+          acc32[g][2] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.z, bv.z, acc32[g][2], 0, 0, 0);
+          acc32[g][3] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.w, bv.w, acc32[g][3], 0, 0, 0);
+        }
+      }
+      const Quad32 yv = sY[buf][4 * s + kg];
+      accy32[0] = fmaf(av.x, yv.x, accy32[0]);
+      accy32[1] = fmaf(av.y, yv.y, accy32[1]);
+      accy32[2] = fmaf(av.z, yv.z, accy32[2]);
+      accy32[3] = fmaf(av.w, yv.w, accy32[3]);
+    }
+  };
+
+  float4 areg[NL];
   VT inreg[NE];
   if (nchunks > 0) {
-    load_A(c_begin, areg);
+#pragma unroll
+    for (int s = 0; s < NL; ++s) areg[s] = *reinterpret_cast<const float4*>(Arow + c_begin + 16 * s);
     load_in(c_begin, inreg);
     store_in(0, inreg);
   }
@@ -158,68 +186,31 @@ __global__ __launch_bounds__(256) void k_strip(const StripArgs a) {
     const int c = c_begin + ch * CHUNK;
     const int buf = ch & 1;
     const bool more = ch + 1 < nchunks;
-    if (more) {
-      load_A(c + CHUNK, anext);
-      load_in(c + CHUNK, inreg);
-    }
-    // elements outside the item's column range or on the wrong side of the diagonal are dropped
-    const bool need_mask = (c + CHUNK > c_end) || (mode == 1 && c + CHUNK > (int)it.row_in_block) ||
-                           (mode == 2 && c < (int)it.row_in_block + TILE);
-    if (need_mask) {
+    const int cn = more ? c + CHUNK : c;       // the last chunk re-reads itself instead of branching
+    load_in(cn, inreg);
+    const float* __restrict__ An = Arow + cn;
+    if (c >= mask_from || c < mask_upto) {
+      // chunk with elements outside the item's column range or on the wrong side of the diagonal
 #pragma unroll
       for (int s = 0; s < NL; ++s) {
-        int q0 = c + 16 * s + 4 * kg;
-        float* v = reinterpret_cast<float*>(&areg[s]);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          int q = q0 + j;
-          bool ok = q < c_end;
-          if (mode == 1) ok = ok && (q <= diag);
-          if (mode == 2) ok = ok && (q >= diag);
-          v[j] = ok ? v[j] : 0.f;
-        }
-      }
-    }
-    if constexpr (ACC64) {
-#pragma unroll
-      for (int s = 0; s < NL; ++s) {
-        const double ax = (double)areg[s].x, ay = (double)areg[s].y, az = (double)areg[s].z, aw = (double)areg[s].w;
-        if (NG > 0) {
-#pragma unroll
-          for (int g = 0; g < NG; ++g) {
-            const Quad64 bv = sB[buf][(4 * s + kg) * NCOLM + 16 * g + m];
-            acc64[g][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(ax, bv.x, acc64[g][0], 0, 0, 0);
-            acc64[g][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(ay, bv.y, acc64[g][1], 0, 0, 0);
-            acc64[g][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(az, bv.z, acc64[g][0], 0, 0, 0);
-            acc64[g][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(aw, bv.w, acc64[g][1], 0, 0, 0);
-          }
-        }
-        const Quad64 yv = sY[buf][4 * s + kg];
-        daccy = fma(ax, yv.x, daccy);
-        daccy = fma(ay, yv.y, daccy);
-        daccy = fma(az, yv.z, daccy);
-        daccy = fma(aw, yv.w, daccy);
+        float4 av = areg[s];
+        areg[s] = *reinterpret_cast<const float4*>(An + 16 * s);
+        const int q0 = c + 16 * s + 4 * kg;
+        av.x = (q0 + 0 >= q_lo && q0 + 0 < q_hi) ? av.x : 0.f;
+        av.y = (q0 + 1 >= q_lo && q0 + 1 < q_hi) ? av.y : 0.f;
+        av.z = (q0 + 2 >= q_lo && q0 + 2 < q_hi) ? av.z : 0.f;
+        av.w = (q0 + 3 >= q_lo && q0 + 3 < q_hi) ? av.w : 0.f;
+        step(av, buf, s);
       }
     } else {
 #pragma unroll
       for (int s = 0; s < NL; ++s) {
         const float4 av = areg[s];
-        if (NG > 0) {
-#pragma unroll
-          for (int g = 0; g < NG; ++g) {
-            const Quad32 bv = sB[buf][(4 * s + kg) * NCOLM + 16 * g + m];
-            acc32[g][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.x, bv.x, acc32[g][0], 0, 0, 0);
-            acc32[g][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.y, bv.y, acc32[g][1], 0, 0, 0);
-            acc32[g][2] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.z, bv.z, acc32[g][2], 0, 0, 0);
-            acc32[g][3] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.w, bv.w, acc32[g][3], 0, 0, 0);
-          }
-        }
-        const Quad32 yv = sY[buf][4 * s + kg];
-        accy32[0] = fmaf(av.x, yv.x, accy32[0]);
-        accy32[1] = fmaf(av.y, yv.y, accy32[1]);
-        accy32[2] = fmaf(av.z, yv.z, accy32[2]);
-        accy32[3] = fmaf(av.w, yv.w, accy32[3]);
+        areg[s] = *reinterpret_cast<const float4*>(An + 16 * s);
+        step(av, buf, s);
       }
+    }
+    if constexpr (!ACC64) {
       // fold this chunk's short chains into the fp64 sums and restart them
       if (NG > 0) {
 #pragma unroll
@@ -235,11 +226,7 @@ __global__ __launch_bounds__(256) void k_strip(const StripArgs a) {
       daccy += ((double)accy32[0] + (double)accy32[1]) + ((double)accy32[2] + (double)accy32[3]);
       accy32[0] = accy32[1] = accy32[2] = accy32[3] = 0.f;
     }
-    if (more) {
-      store_in(buf ^ 1, inreg);
-#pragma unroll
-      for (int s = 0; s < NL; ++s) areg[s] = anext[s];
-    }
+    store_in(buf ^ 1, inreg);
     __syncthreads();
   }
 
@@ -275,28 +262,42 @@ __global__ __launch_bounds__(256) void k_strip(const StripArgs a) {
   }
 }
 
-static int g_chunk = 0;
+// out[i] = sum over `parts` slabs of in[part * stride + i]  (fixed order: deterministic)
+template <typename VT>
+__global__ void k_sum_parts(const VT* __restrict__ in, VT* __restrict__ out, int64_t count, int parts,
+                            uint64_t stride) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x) {
+    VT s = in[i];
+    for (int p = 1; p < parts; ++p) s += in[(uint64_t)p * stride + i];
+    out[i] = s;
+  }
+}
+
+int launch_sum_parts(const void* in, void* out, int64_t count, int parts, uint64_t stride, bool acc64,
+                     hipStream_t s) {
+  const int grid = (int)std::min<int64_t>((count + 255) / 256, 2048);
+  if (acc64)
+    hipLaunchKernelGGL((k_sum_parts<double>), dim3(grid), dim3(256), 0, s, (const double*)in, (double*)out, count,
+                       parts, stride);
+  else
+    hipLaunchKernelGGL((k_sum_parts<float>), dim3(grid), dim3(256), 0, s, (const float*)in, (float*)out, count,
+                       parts, stride);
+  NUGPR_HIP(hipGetLastError());
+  return NUGPR_OK;
+}
 
 template <bool ACC64>
-static void launch_typed(int ng, int chunk, dim3 grid, hipStream_t s, const StripArgs& a) {
+static void launch_typed(int ng, dim3 grid, hipStream_t s, const StripArgs& a) {
   dim3 block(256);
-#define LAUNCH(NGV, CH) hipLaunchKernelGGL((k_strip<NGV, CH, ACC64>), grid, block, 0, s, a)
-  if (chunk == 64) {
-    if (ng == 0) LAUNCH(0, 64); else if (ng == 1) LAUNCH(1, 64); else LAUNCH(2, 64);
-  } else {
-    if (ng == 0) LAUNCH(0, 128); else if (ng == 1) LAUNCH(1, 128); else LAUNCH(2, 128);
-  }
-#undef LAUNCH
+  if (ng == 0) hipLaunchKernelGGL((k_strip<0, ACC64>), grid, block, 0, s, a);
+  else if (ng == 1) hipLaunchKernelGGL((k_strip<1, ACC64>), grid, block, 0, s, a);
+  else hipLaunchKernelGGL((k_strip<2, ACC64>), grid, block, 0, s, a);
 }
 
 int launch_strip(const StripTable& tab, const StripPort& p0, const StripPort& p1, int T, bool acc64,
                  hipStream_t s) {
   if (tab.count == 0) return NUGPR_OK;
   if (T < 1 || T > MAX_COLS) { set_error("vector block wider than 33 columns"); return NUGPR_ERR_INVALID; }
-  if (g_chunk == 0) {
-    const char* e = getenv("NUGPR_STRIP_CHUNK");
-    g_chunk = (e && atoi(e) == 64) ? 64 : 128;
-  }
   StripArgs a;
   a.port[0] = p0;
   a.port[1] = p1;
@@ -304,11 +305,8 @@ int launch_strip(const StripTable& tab, const StripPort& p0, const StripPort& p1
   a.T = T;
   a.magicT = T == 1 ? 0u : (uint32_t)((1ull << 32) / (uint64_t)T + 1ull);
   const int ng = (T - 1 + 15) / 16;
-  // the fp64 mode keeps twice the bytes per staged vector element in LDS: use the short chunk
-  // for the widest blocks so that several workgroups still fit on a compute unit
-  const int chunk = (acc64 && ng == 2) ? 64 : g_chunk;
-  if (acc64) launch_typed<true>(ng, chunk, dim3(tab.count), s, a);
-  else launch_typed<false>(ng, chunk, dim3(tab.count), s, a);
+  if (acc64) launch_typed<true>(ng, dim3(tab.count), s, a);
+  else launch_typed<false>(ng, dim3(tab.count), s, a);
   NUGPR_HIP(hipGetLastError());
   return NUGPR_OK;
 }
