@@ -60,6 +60,9 @@ def main():
                     help="arithmetic of the operator applications over the fp32 stored matrices")
     ap.add_argument("--cpu-clusters", type=int, default=8, help="clusters in the CPU-oracle sample (0 = skip)")
     ap.add_argument("--kv-reps", type=int, default=20)
+    ap.add_argument("--copy-probe-gib", type=float, default=0.0,
+                    help="also run a plain copy kernel of this many GiB three times (reference dispatch for "
+                         "scaling hardware HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one process, one device); --gpus N with N > 1 is not "
@@ -73,8 +76,17 @@ def main():
         sys.exit(1)
     from paper_2510_12128_amd import Context, inputs
 
-    w = inputs.make_config(args.config)
     dev = torch.device("cuda:0")
+    if args.copy_probe_gib > 0:
+        from paper_2510_12128_amd.binding import nugpr_copy_probe
+        nb = int(args.copy_probe_gib * (1 << 30)) // 16 * 16
+        src = torch.ones(nb // 4, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            nugpr_copy_probe(dst, src)
+        torch.cuda.synchronize(dev)
+        del src, dst
+    w = inputs.make_config(args.config)
     ctx = Context(w.X, w.y, w.offsets, w.probes, w.rank, tol=w.tol, max_iter=w.max_iter, fd_step=w.fd_step,
                   lr=w.lr, isotropic=w.isotropic, device=dev, acc_fp32=(args.acc == "fp32"))
     p, T = ctx.p, ctx.T

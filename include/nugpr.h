@@ -199,6 +199,11 @@ int nugpr_profile_enable(nugpr_ctx* ctx, int32_t on);
 int nugpr_profile_read(nugpr_ctx* ctx, double* total_ms /*HOST*/, int32_t* launches /*HOST*/, void* stream);
 double nugpr_profile_bytes(const nugpr_ctx* ctx, int32_t ncols);
 
+/* A plain device-to-device copy kernel of `bytes` bytes (16-byte loads/stores, both
+ * DEVICE pointers 16-byte aligned, bytes a multiple of 16): the known-size dispatch
+ * against which hardware HBM byte counters are scaled.  Does not synchronise. */
+int nugpr_copy_probe(void* dst /*DEVICE*/, const void* src /*DEVICE*/, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -96,6 +96,8 @@ def load_library():
     lib.nugpr_profile_read.argtypes = [vp, dp, ip, vp]
     lib.nugpr_profile_bytes.restype = C.c_double
     lib.nugpr_profile_bytes.argtypes = [vp, C.c_int32]
+    lib.nugpr_copy_probe.restype = C.c_int
+    lib.nugpr_copy_probe.argtypes = [vp, vp, C.c_size_t, vp]
     _LIB = lib
     return lib
 
@@ -108,6 +110,15 @@ def _check(code):
     if code < 0:
         raise NugprError(code, load_library().nugpr_last_error_string().decode())
     return code
+
+
+def nugpr_copy_probe(dst, src, stream=None):
+    """Plain copy kernel between two equally sized CUDA tensors (counter calibration)."""
+    import torch
+    lib = load_library()
+    nbytes = src.numel() * src.element_size()
+    st = C.c_void_p(torch.cuda.current_stream(src.device).cuda_stream if stream is None else stream)
+    return _check(lib.nugpr_copy_probe(dst.data_ptr(), src.data_ptr(), nbytes, st))
 
 
 class Context:

@@ -13,6 +13,12 @@ using namespace nugpr;
 
 namespace {
 
+// plain 16-byte grid-stride copy: the known-size reference the HBM byte counters are scaled by
+__global__ void k_copy16(const float4* __restrict__ src, float4* __restrict__ dst, size_t count) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
 hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 // ---- strip work tables ------------------------------------------------------
@@ -192,6 +198,17 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   e = hipStreamSynchronize(s);
   if (e != hipSuccess) return fail(hip_fail(e, "sync after setup"));
   *out = c;
+  return NUGPR_OK;
+}
+
+int nugpr_copy_probe(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src || (bytes & 15u) || ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15u)) {
+    set_error("copy_probe needs 16-byte aligned buffers and a multiple of 16 bytes");
+    return NUGPR_ERR_INVALID;
+  }
+  hipLaunchKernelGGL(k_copy16, dim3(8192), dim3(256), 0, as_stream(stream), static_cast<const float4*>(src),
+                     static_cast<float4*>(dst), bytes / 16);
+  NUGPR_HIP(hipGetLastError());
   return NUGPR_OK;
 }
 
