@@ -107,7 +107,8 @@ int plan_layout(const nugpr_problem* pb, uint32_t flags, Layout& L) {
   L.o_alog = take(cur, (size_t)L.max_iter * MAX_COLS * sizeof(double));
   L.o_blog = take(cur, (size_t)L.max_iter * MAX_COLS * sizeof(double));
   L.o_logdet = take(cur, (size_t)L.nc * sizeof(double));
-  L.o_tiles = take(cur, (L.n_diag_tiles + L.n_c_tiles) * sizeof(uint64_t));
+  // tile list of the diagonal blocks (mirroring) + row-panel work items of the two assembly launches
+  L.o_tiles = take(cur, (2 * L.n_diag_tiles + L.n_c_tiles) * sizeof(uint64_t));
   // strip tables: exact item counts
   size_t items = 0;
   for (auto& c : L.cl) {

@@ -84,6 +84,7 @@ struct PcgState {
   int32_t active[MAX_COLS];
   int32_t iters[MAX_COLS];
   int32_t converged[MAX_COLS];
+  int32_t indef[MAX_COLS];      // column met <d, K'd> <= 0
   int32_t n_active;
   int32_t indefinite;
   int32_t bad_cluster;    // Cholesky: lowest failing cluster index, or INT_MAX
@@ -138,7 +139,10 @@ struct nugpr_ctx {
   bool acc64 = true;                     // arithmetic mode of the operator applications
   double *dotpart = nullptr, *alog = nullptr, *blog = nullptr, *d_theta = nullptr, *d_logdet = nullptr;
   nugpr::PcgState* d_state = nullptr;
-  uint64_t* d_tiles = nullptr;       // packed (cluster, tile row, tile col) list for assembly
+  uint64_t* d_tiles = nullptr;       // packed (cluster, tile row, tile col) list of the diagonal blocks
+  uint64_t* d_pan_diag = nullptr;    // row-panel work items of the K_ii assembly
+  uint64_t* d_pan_c = nullptr;       // row-panel work items of the coupling assembly
+  int n_pan_diag = 0, n_pan_c = 0;
   nugpr::StripTable tab_WtD, tab_KC, tab_WP, tab_lowG, tab_upG, tab_lowL;
   // optional event timing of the K_diag / C streaming launch
   bool prof_on = false;

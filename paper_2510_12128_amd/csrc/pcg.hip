@@ -67,79 +67,85 @@ __device__ __forceinline__ double sum_partials(const double* __restrict__ partia
   return r;
 }
 
+// The three scalar kernels run one workgroup per column (grid = T); the cross-column
+// bookkeeping (how many columns are still active, did any meet negative curvature) is
+// gathered by k_copy_flags, which runs after them on the same stream.
+
 // start of a solve: ||b||^2 and rho_0 = <r_0, z_0>
 __global__ __launch_bounds__(256) void k_pcg_begin(PcgState* __restrict__ st, const double* __restrict__ partial,
-                                                   int nblocks, int T) {
+                                                   int nblocks) {
   __shared__ double red[256];
-  const int tid = threadIdx.x;
-  int n_active = 0;
-  for (int c = 0; c < T; ++c) {
-    const double bb = sum_partials(partial, nblocks, c, red, tid);
-    const double rz = sum_partials(partial + (int64_t)nblocks * MAX_COLS, nblocks, c, red, tid);
+  const int tid = threadIdx.x, c = blockIdx.x;
+  const double bb = sum_partials(partial, nblocks, c, red, tid);
+  const double rz = sum_partials(partial + (int64_t)nblocks * MAX_COLS, nblocks, c, red, tid);
+  if (tid == 0) {
     const bool act = bb > 0.0 && rz == rz;
-    if (tid == 0) {
-      st->bnorm2[c] = bb;
-      st->rho[c] = rz;
-      st->rho0[c] = rz;
-      st->alpha[c] = 0.0;
-      st->beta[c] = 0.0;
-      st->active[c] = act ? 1 : 0;
-      st->iters[c] = 0;
-      st->converged[c] = (bb == 0.0) ? 1 : 0;
-    }
-    n_active += act ? 1 : 0;
+    st->bnorm2[c] = bb;
+    st->rho[c] = rz;
+    st->rho0[c] = rz;
+    st->alpha[c] = 0.0;
+    st->beta[c] = 0.0;
+    st->active[c] = act ? 1 : 0;
+    st->iters[c] = 0;
+    st->converged[c] = (bb == 0.0) ? 1 : 0;
+    st->indef[c] = 0;
   }
-  if (tid == 0) { st->n_active = n_active; st->indefinite = 0; }
 }
 
 // alpha_c = rho_c / <d, K'd>_c for the active columns
 __global__ __launch_bounds__(256) void k_pcg_alpha(PcgState* __restrict__ st, const double* __restrict__ partial,
-                                                   int nblocks, int T, int iter, double* __restrict__ alog) {
+                                                   int nblocks, int iter, double* __restrict__ alog) {
   __shared__ double red[256];
-  const int tid = threadIdx.x;
-  for (int c = 0; c < T; ++c) {
-    const double dq = sum_partials(partial, nblocks, c, red, tid);
-    if (tid == 0) {
-      double a = 0.0;
-      if (st->active[c]) {
-        if (dq > 0.0) a = st->rho[c] / dq;
-        else { st->indefinite = 1; st->active[c] = 0; st->n_active -= 1; }   // <d, K'd> <= 0 (or NaN)
-      }
-      st->alpha[c] = a;
-      alog[(int64_t)iter * MAX_COLS + c] = a;
+  const int tid = threadIdx.x, c = blockIdx.x;
+  const double dq = sum_partials(partial, nblocks, c, red, tid);
+  if (tid == 0) {
+    double a = 0.0;
+    if (st->active[c]) {
+      if (dq > 0.0) a = st->rho[c] / dq;
+      else { st->indef[c] = 1; st->active[c] = 0; }      // <d, K'd> <= 0 (or NaN)
+    }
+    st->alpha[c] = a;
+    alog[(int64_t)iter * MAX_COLS + c] = a;
+  }
+}
+
+// after the update: stop test on ||r_c|| (columns that meet it are frozen)
+__global__ __launch_bounds__(256) void k_pcg_check(PcgState* __restrict__ st, const double* __restrict__ partial,
+                                                   int nblocks, int iter, double tol2) {
+  __shared__ double red[256];
+  const int tid = threadIdx.x, c = blockIdx.x;
+  const double rr = sum_partials(partial, nblocks, c, red, tid);
+  if (tid == 0 && st->active[c]) {
+    st->iters[c] = iter + 1;
+    if (rr <= tol2 * st->bnorm2[c]) {
+      st->active[c] = 0;
+      st->converged[c] = 1;
+    } else if (!(rr == rr)) {                // NaN residual: stop this column
+      st->active[c] = 0;
+      st->indef[c] = 1;
     }
   }
 }
 
-// after the update: stop test on ||r||, then beta_c = <r, z>_new / rho_c
+// beta_c = <r, z>_new / rho_c for the columns that go on
 __global__ __launch_bounds__(256) void k_pcg_beta(PcgState* __restrict__ st, const double* __restrict__ partial,
-                                                  int nblocks, int T, int iter, double tol2,
-                                                  double* __restrict__ blog) {
+                                                  int nblocks, int iter, double* __restrict__ blog) {
   __shared__ double red[256];
-  const int tid = threadIdx.x;
-  for (int c = 0; c < T; ++c) {
-    const double rr = sum_partials(partial, nblocks, c, red, tid);
-    const double rz = sum_partials(partial + (int64_t)nblocks * MAX_COLS, nblocks, c, red, tid);
-    if (tid == 0) {
-      double bta = 0.0;
-      if (st->active[c]) {
-        st->iters[c] = iter + 1;
-        if (rr <= tol2 * st->bnorm2[c]) {
-          st->active[c] = 0;
-          st->converged[c] = 1;
-          st->n_active -= 1;
-        } else if (!(rz > 0.0)) {            // preconditioned residual lost positivity (or NaN)
-          st->active[c] = 0;
-          st->indefinite = 1;
-          st->n_active -= 1;
-        } else {
-          bta = rz / st->rho[c];
-          st->rho[c] = rz;
-        }
+  const int tid = threadIdx.x, c = blockIdx.x;
+  const double rz = sum_partials(partial, nblocks, c, red, tid);
+  if (tid == 0) {
+    double bta = 0.0;
+    if (st->active[c]) {
+      if (!(rz > 0.0)) {                     // preconditioned residual lost positivity (or NaN)
+        st->active[c] = 0;
+        st->indef[c] = 1;
+      } else {
+        bta = rz / st->rho[c];
+        st->rho[c] = rz;
       }
-      st->beta[c] = bta;
-      blog[(int64_t)iter * MAX_COLS + c] = bta;
     }
+    st->beta[c] = bta;
+    blog[(int64_t)iter * MAX_COLS + c] = bta;
   }
 }
 
@@ -177,9 +183,13 @@ __global__ __launch_bounds__(256) void k_update_d(VT* __restrict__ D, const VT* 
   }
 }
 
-__global__ void k_copy_flags(const PcgState* __restrict__ st, HostFlags* __restrict__ out) {
-  out->n_active = st->n_active;
-  out->indefinite = st->indefinite;
+__global__ void k_copy_flags(PcgState* __restrict__ st, HostFlags* __restrict__ out, int T) {
+  int n_active = 0, indef = 0;
+  for (int c = 0; c < T; ++c) { n_active += st->active[c]; indef |= st->indef[c]; }
+  st->n_active = n_active;
+  st->indefinite = indef;
+  out->n_active = n_active;
+  out->indefinite = indef;
   out->bad_cluster = st->bad_cluster;
 }
 
@@ -290,27 +300,32 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
   if ((rc = run_precond(c, R, Z, T, s))) return rc;
   NUGPR_HIP(hipMemcpyAsync(D, Z, bytes, hipMemcpyDeviceToDevice, s));
   hipLaunchKernelGGL((k_dot<2, VT>), dim3(nb), dim3(256), 0, s, R, R, R, Z, n, T, c->dotpart);
-  hipLaunchKernelGGL(k_pcg_begin, dim3(1), dim3(256), 0, s, c->d_state, c->dotpart, nb, T);
+  hipLaunchKernelGGL(k_pcg_begin, dim3(T), dim3(256), 0, s, c->d_state, c->dotpart, nb);
   NUGPR_HIP(hipGetLastError());
   int it = 0;
   bool indefinite = false;
   c->h_flags->n_active = 1;
-  hipLaunchKernelGGL(k_copy_flags, dim3(1), dim3(1), 0, s, c->d_state, c->h_flags);
+  hipLaunchKernelGGL(k_copy_flags, dim3(1), dim3(1), 0, s, c->d_state, c->h_flags, T);
   NUGPR_HIP(hipStreamSynchronize(s));
   while (it < max_iter && c->h_flags->n_active > 0) {
     if ((rc = run_matvec(c, D, Q, T, s))) return rc;
     hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, D, Q, D, Q, n, T, c->dotpart);
-    hipLaunchKernelGGL(k_pcg_alpha, dim3(1), dim3(256), 0, s, c->d_state, c->dotpart, nb, T, it, c->alog);
+    hipLaunchKernelGGL(k_pcg_alpha, dim3(T), dim3(256), 0, s, c->d_state, c->dotpart, nb, it, c->alog);
     hipLaunchKernelGGL((k_update_xr<VT>), dim3(eg), dim3(256), 0, s, X, R, D, Q, c->d_state, n, T);
-    if ((rc = run_precond(c, R, Z, T, s))) return rc;
-    hipLaunchKernelGGL((k_dot<2, VT>), dim3(nb), dim3(256), 0, s, R, R, R, Z, n, T, c->dotpart);
-    hipLaunchKernelGGL(k_pcg_beta, dim3(1), dim3(256), 0, s, c->d_state, c->dotpart, nb, T, it, tol2, c->blog);
-    hipLaunchKernelGGL((k_update_d<VT>), dim3(eg), dim3(256), 0, s, D, Z, c->d_state, n, T);
-    hipLaunchKernelGGL(k_copy_flags, dim3(1), dim3(1), 0, s, c->d_state, c->h_flags);
+    // stop test first: when every column has converged the preconditioner apply is not needed
+    hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, R, R, R, R, n, T, c->dotpart);
+    hipLaunchKernelGGL(k_pcg_check, dim3(T), dim3(256), 0, s, c->d_state, c->dotpart, nb, it, tol2);
+    hipLaunchKernelGGL(k_copy_flags, dim3(1), dim3(1), 0, s, c->d_state, c->h_flags, T);
     NUGPR_HIP(hipGetLastError());
     NUGPR_HIP(hipStreamSynchronize(s));
-    ++it;
+    const int j = it++;
     if (c->h_flags->indefinite) indefinite = true;
+    if (c->h_flags->n_active == 0 || it >= max_iter) break;
+    if ((rc = run_precond(c, R, Z, T, s))) return rc;
+    hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, R, Z, R, Z, n, T, c->dotpart);
+    hipLaunchKernelGGL(k_pcg_beta, dim3(T), dim3(256), 0, s, c->d_state, c->dotpart, nb, j, c->blog);
+    hipLaunchKernelGGL((k_update_d<VT>), dim3(eg), dim3(256), 0, s, D, Z, c->d_state, n, T);
+    NUGPR_HIP(hipGetLastError());
   }
   // per-column records
   PcgState* hs = reinterpret_cast<PcgState*>(c->h_buf);
@@ -322,6 +337,7 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
     if (iters) iters[col] = hs->iters[col];
     mx = std::max(mx, hs->iters[col]);
     if (!hs->converged[col]) all_conv = false;
+    if (hs->indef[col]) indefinite = true;
   }
   if (max_it_used) *max_it_used = mx;
   if (alpha || beta) {
