@@ -24,6 +24,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 
+# HBM bytes per launch of the dominant kernel from the two rocprofv3 --pmc runs summarised in
+# profiles/k_strip_C4_*_hbm_traffic.md (FETCH_SIZE + WRITE_SIZE, scaled by the copy probe).
+# Counter runs are separate from this program, so the figure is quoted, not measured live.
+MEASURED_TRAFFIC_BYTES = {("C4", "fp64"): 3.646e9}
+
 
 def cpu_baseline(w, n_sample_clusters):
     """The fp64 oracle, as it stands, on the first clusters of the same workload:
@@ -181,7 +186,8 @@ def main():
         "mll_iters": res["max_iters_used"],
         "roofline": {"bound": "hbm", "kernel": "k_strip (K_diag.D and C.S in one launch)",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, args.acc)),
                      "bytes_per_launch": dom_bytes, "avg_ms": dom_avg_ms, "launches_timed": dom_launches},
     }
     if args.cpu_clusters > 0:
