@@ -152,6 +152,10 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   c->Wd = reinterpret_cast<float*>(w + L.o_Wd);
   c->Wt = reinterpret_cast<float*>(w + L.o_Wt);
   c->reps = reinterpret_cast<float*>(w + L.o_reps);
+  c->Xs = reinterpret_cast<double*>(w + L.o_Xs);
+  c->Xn = reinterpret_cast<double*>(w + L.o_Xn);
+  c->Rs = reinterpret_cast<double*>(w + L.o_Rs);
+  c->Rn = reinterpret_cast<double*>(w + L.o_Rn);
   c->Bv = w + L.o_B;
   c->Xv = w + L.o_X;
   c->Rv = w + L.o_R;

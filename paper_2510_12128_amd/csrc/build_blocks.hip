@@ -14,8 +14,20 @@
 // exponential (a degree-9 polynomial after range reduction) on the vector ALUs.
 // The part of alpha + sigma^2 that the fp32 diagonal cannot hold is kept as a scalar and
 // added by the matrix-vector product (StripPort::diag_add).
+//
+// Two kernels per assembly:
+//   k_scale_points  writes the scaled coordinates once, in fp64, in the order the matrix
+//                   cores read their operands (groups of 16 points, coordinate-major inside a
+//                   group), and the squared norms;
+//   k_build_panel   one work item = a run of 64 x 64 tiles of one tile row.  Each wave owns a
+//                   16-column slice of every tile and works on its own: operands come
+//                   straight from the scaled array (512-byte contiguous loads, served by
+//                   L2), the result is transposed through a wave-private LDS staging area
+//                   and written twice (the tile and its mirror image) with 16-byte stores.
+//                   No workgroup barrier inside the tile loop.
 #include <algorithm>
 #include <cmath>
+#include <type_traits>
 #include <vector>
 
 #include "nugpr_internal.h"
@@ -24,10 +36,8 @@ namespace nugpr {
 
 typedef double v4d __attribute__((ext_vector_type(4)));
 
-struct PairArgs {
+struct ScaleArgs {
   double sw[MAX_D];     // sqrt(log2(e) / (2 ell_k^2)): coordinate scale per dimension
-  double alpha;
-  float diag_val;       // float(alpha + sigma^2)
   int32_t d;
 };
 
@@ -50,171 +60,220 @@ __device__ __forceinline__ double exp2_neg(double a) {
   return ldexp(p, e);
 }
 
-// LDS layout (dynamic): two [kd][64] fp64 panels of scaled coordinates (kd = d rounded up to
-// 4, the padding rows zero), two [64] fp64 squared norms, and a 64 x 65 fp32 staging tile.
 __host__ __device__ inline int pair_kd(int d) { return (d + 3) & ~3; }
-__host__ __device__ inline size_t pair_lds_bytes(int d) {
-  return (size_t)2 * pair_kd(d) * TILE * sizeof(double) + 2 * TILE * sizeof(double) +
-         (size_t)TILE * (TILE + 1) * sizeof(float);
-}
-constexpr int MAX_PT = MAX_D / 4;     // coordinates one thread holds for one 64-point panel
 
-// Thread t holds coordinates k = (t % 4) + 4 e, e < kd / 4, of point t / 4 of a 64-point panel.
-__device__ __forceinline__ void fetch_points(const float* __restrict__ P, int d, int kd, int first, int valid,
-                                             int tid, float (&reg)[MAX_PT]) {
-  const int p = tid >> 2, sub = tid & 3;
-#pragma unroll
-  for (int e = 0; e < MAX_PT; ++e) {
-    const int k = sub + 4 * e;
-    reg[e] = (e * 4 < kd && p < valid && k < d) ? P[(uint64_t)(first + p) * d + k] : 0.f;
+// Scaled coordinates of the point with padded row number pr live at
+//   S[((pr / 16) * kd + k) * 16 + pr % 16],  k < kd = d rounded up to 4 (padding zero),
+// so the 64 lanes (m = lane % 16, kk = lane / 16) of a wave read the operand of MFMA step ks
+// for the 16 points of a group as ONE contiguous 512-byte run: element (4 ks + kk) * 16 + m.
+// Four threads share a point (coordinates k = sub + 4 e); rows past the end of a cluster are
+// written as zeros.  grid.y = cluster (or 0 for the representatives), 64 points per block.
+__global__ __launch_bounds__(256) void k_scale_points(const ScaleArgs a, const ClusterInfo* __restrict__ cl,
+                                                      const float* __restrict__ P, double* __restrict__ S,
+                                                      double* __restrict__ N, int single_total, int single_ld) {
+  uint32_t first, total, ld, prow;
+  if (cl) {
+    const ClusterInfo c = cl[blockIdx.y];
+    first = c.row0; total = c.b; ld = c.ld; prow = c.prow;
+  } else {
+    first = 0; total = (uint32_t)single_total; ld = (uint32_t)single_ld; prow = 0;
   }
-}
-
-// sX[k][p] = sw[k] * x_pk (zero in the padding), sN[p] = sum_k sX[k][p]^2
-__device__ __forceinline__ void commit_points(const PairArgs& a, int kd, const float (&reg)[MAX_PT],
-                                              double (*sX)[TILE], double* sN, int tid) {
-  const int p = tid >> 2, sub = tid & 3;
+  const uint32_t pl = blockIdx.x * 64 + (threadIdx.x >> 2);
+  if (pl >= ld) return;                       // whole groups of four threads leave together
+  const int sub = threadIdx.x & 3, d = a.d, kd = pair_kd(d);
+  const uint32_t pr = prow + pl;
+  double* __restrict__ dst = S + ((uint64_t)(pr >> 4) * kd) * 16 + (pr & 15);
   double nrm = 0.0;
-#pragma unroll
-  for (int e = 0; e < MAX_PT; ++e) {
-    if (e * 4 < kd) {
-      const int k = sub + 4 * e;
-      const double v = a.sw[k] * (double)reg[e];
-      sX[k][p] = v;
-      nrm = fma(v, v, nrm);
-    }
+  for (int k = sub; k < kd; k += 4) {
+    const double v = (pl < total && k < d) ? a.sw[k] * (double)P[(uint64_t)(first + pl) * d + k] : 0.0;
+    dst[(uint64_t)k * 16] = v;
+    nrm = fma(v, v, nrm);
   }
   nrm += __shfl_xor(nrm, 1);
   nrm += __shfl_xor(nrm, 2);
-  if (sub == 0) sN[p] = nrm;
+  if (sub == 0) N[pr] = nrm;
 }
 
-// 64 x 64 tile of alpha * 2^(-|u_r - v_c|^2): wave w owns rows 16w..16w+15; val[tj][i] is the
-// entry at row 16w + (lane/16) + 4i, column 16 tj + lane%16 (the f64 16x16x4 accumulator layout).
-__device__ __forceinline__ void pair_tile(const PairArgs& a, const double (*sXr)[TILE], const double (*sXc)[TILE],
-                                          const double* sNr, const double* sNc, int wave, int lane,
-                                          float (&val)[4][4]) {
-  v4d acc[4];
-#pragma unroll
-  for (int tj = 0; tj < 4; ++tj) acc[tj] = (v4d){0.0, 0.0, 0.0, 0.0};
-  const int m = lane & 15, kk = lane >> 4;
-  const int kd = pair_kd(a.d);
-  for (int ks = 0; ks < kd; ks += 4) {
-    const double av = sXr[ks + kk][16 * wave + m];
-#pragma unroll
-    for (int tj = 0; tj < 4; ++tj) {
-      const double bv = sXc[ks + kk][16 * tj + m];
-      acc[tj] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc[tj], 0, 0, 0);
-    }
-  }
-#pragma unroll
-  for (int tj = 0; tj < 4; ++tj) {
-    const double nc = sNc[16 * tj + m];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const double nr = sNr[16 * wave + kk + 4 * i];
-      const double arg = fma(-2.0, acc[tj][i], nr + nc);
-      val[tj][i] = (float)(a.alpha * exp2_neg(arg));
-    }
-  }
-}
+struct PanelArgs {
+  double alpha;
+  float diag_val;       // float(alpha + sigma^2)
+  int32_t kd;           // coordinates per point in the scaled array (multiple of 4)
+};
 
-// Writes the staged tile (and its mirror image when off the diagonal of the tile grid) with
-// 16-byte stores.  keep(p, q) decides which entries are stored as computed (the others
-// become 0); diag(p, v) replaces diagonal entries.
-template <class Keep, class DiagVal>
-__device__ __forceinline__ void store_tile(float* __restrict__ out, uint32_t ld, int p0, int q0, bool mirror,
-                                           const float (*sT)[TILE + 1], int tid, Keep keep, DiagVal diag) {
-  const int r = tid >> 2, c0 = (tid & 3) * 16;     // this thread writes 16 consecutive entries of one row
-  {
-    const int p = p0 + r;
-#pragma unroll
-    for (int j4 = 0; j4 < 4; ++j4) {
-      float v[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int q = q0 + c0 + 4 * j4 + j;
-        float x = keep(p, q) ? sT[r][c0 + 4 * j4 + j] : 0.f;
-        if (p == q) x = diag(p, x);
-        v[j] = x;
-      }
-      *reinterpret_cast<float4*>(out + (uint64_t)p * ld + q0 + c0 + 4 * j4) = make_float4(v[0], v[1], v[2], v[3]);
-    }
-  }
-  if (mirror) {
-    const int q = q0 + r;                          // row of the mirrored tile
-#pragma unroll
-    for (int j4 = 0; j4 < 4; ++j4) {
-      float v[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int p = p0 + c0 + 4 * j4 + j;
-        v[j] = keep(p, q) ? sT[c0 + 4 * j4 + j][r] : 0.f;
-      }
-      *reinterpret_cast<float4*>(out + (uint64_t)q * ld + p0 + c0 + 4 * j4) = make_float4(v[0], v[1], v[2], v[3]);
-    }
-  }
-}
+constexpr int ST_LD = 17;      // row stride of the staging area (floats)
+constexpr int MAX_ITEM_TILES = 16;   // tiles per work item
 
 // One work item = tile row `tr` of one square symmetric matrix (a cluster's K_ii, or the
-// coupling C) and the run of tile columns tc0..tc1-1 (<= tr): the row panel's coordinates
-// are staged once, the column panels stream through with the next one prefetched in
-// registers while the current tile is computed, staged and written (with its mirror).
+// coupling C) and the run of tile columns tc0..tc1-1 (<= tr).
 // item = cluster << 48 | tr << 32 | tc0 << 16 | tc1.
-template <bool COUPLING>
-__global__ __launch_bounds__(256) void k_build_panel(const PairArgs a, const ClusterInfo* __restrict__ cl,
-                                                     const uint64_t* __restrict__ items,
-                                                     const float* __restrict__ P, float* __restrict__ out_base,
-                                                     int ncr, int r, uint32_t ldc) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  const int d = a.d, kd = pair_kd(d);
-  double(*sXr)[TILE] = reinterpret_cast<double(*)[TILE]>(lds_raw);
-  double(*sXc)[TILE] = sXr + kd;
-  double* sNr = reinterpret_cast<double*>(sXc + kd);
-  double* sNc = sNr + TILE;
-  float(*sT)[TILE + 1] = reinterpret_cast<float(*)[TILE + 1]>(sNc + TILE);
+// Wave w computes columns 16 w .. 16 w + 15 of every tile: four 16 x 16 accumulators (one
+// per 16-row group), the row operands of the item held in registers (NKS > 0) and the
+// column operand of the next tile loaded while the current one is exponentiated and stored.
+// NKS = kd / 4 when positive; NKS = 0 handles any kd and re-reads the row operands per tile.
+template <bool COUPLING, int NKS>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
+void k_build_panel(const PanelArgs a, const ClusterInfo* __restrict__ cl, const uint64_t* __restrict__ items,
+                   const double* __restrict__ S, const double* __restrict__ N, float* __restrict__ out_base,
+                   int ncr, int r, uint32_t ldc) {
+  __shared__ double sNr[TILE];
+  __shared__ double sNc[MAX_ITEM_TILES * TILE];      // column norms of every tile of the item
+  __shared__ float sT[4][TILE * ST_LD];
 
   const uint64_t it = items[blockIdx.x];
   const int ci = (int)(it >> 48), tr = (int)((it >> 32) & 0xffff), tc0 = (int)((it >> 16) & 0xffff),
             tc1 = (int)(it & 0xffff);
-  int first, total;
-  uint32_t ld;
+  int total;
+  uint32_t ld, prow;
   float* out;
   if (COUPLING) {
-    first = 0; total = ncr; ld = ldc; out = out_base;
+    total = ncr; ld = ldc; out = out_base; prow = 0;
   } else {
     const ClusterInfo c = cl[ci];
-    first = (int)c.row0; total = (int)c.b; ld = c.ld; out = out_base + c.koff;
+    total = (int)c.b; ld = c.ld; out = out_base + c.koff; prow = c.prow;
   }
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int m = lane & 15, kk = lane >> 4;
+  const int kd = a.kd, nks = NKS > 0 ? NKS : kd / 4;
   const int p0 = tr * TILE;
-  float reg[MAX_PT];
-  fetch_points(P, d, kd, first + p0, min(TILE, total - p0), tid, reg);
-  commit_points(a, kd, reg, sXr, sNr, tid);
-  fetch_points(P, d, kd, first + tc0 * TILE, min(TILE, total - tc0 * TILE), tid, reg);
-  const float dv = a.diag_val;
-  for (int tc = tc0; tc < tc1; ++tc) {
-    const int q0 = tc * TILE;
-    commit_points(a, kd, reg, sXc, sNc, tid);
-    __syncthreads();
-    if (tc + 1 < tc1) fetch_points(P, d, kd, first + q0 + TILE, min(TILE, total - q0 - TILE), tid, reg);
-    float val[4][4];
-    pair_tile(a, sXr, sXc, sNr, sNc, wave, lane, val);
+  const uint64_t gstride = (uint64_t)kd * 16;                 // doubles per group of 16 points
+  const int lofs = kk * 16 + m;                               // this lane's element of a 4-coordinate step
+  const double* __restrict__ Srow = S + (uint64_t)((prow + p0) >> 4) * gstride + lofs;
+
+  if (tid < TILE) sNr[tid] = N[prow + p0 + tid];
+  for (int i = tid; i < (tc1 - tc0) * TILE; i += 256) sNc[i] = N[prow + (uint32_t)tc0 * TILE + i];
+  constexpr int NA = NKS > 0 ? NKS : 1;
+  double av[4][NA];
+  if (NKS > 0) {
 #pragma unroll
-    for (int tj = 0; tj < 4; ++tj)
+    for (int ti = 0; ti < 4; ++ti)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) sT[16 * wave + (lane >> 4) + 4 * i][16 * tj + (lane & 15)] = val[tj][i];
-    __syncthreads();
-    if (COUPLING) {
-      // only blocks between DIFFERENT clusters enter K' (eq. (odsplit)): same-cluster entries are 0
-      store_tile(out, ld, p0, q0, tr != tc, sT, tid,
-                 [total, r](int p, int q) { return p < total && q < total && (p / r) != (q / r); },
-                 [](int, float v) { return v; });
-    } else {
-      store_tile(out, ld, p0, q0, tr != tc, sT, tid,
-                 [total](int p, int q) { return p < total && q < total; },
-                 [total, dv](int p, float v) { return p < total ? dv : v; });
+      for (int ks = 0; ks < NKS; ++ks) av[ti][ks] = Srow[ti * gstride + ks * 64];
+  }
+  __syncthreads();
+
+  // Column operands of two tiles ahead live in two register sets: the loads of tile
+  // tc + 2 are issued before the stores of tile tc, and because the outstanding-operation
+  // counter retires in order, waiting for them later only drains stores that are two tiles old.
+  // A store takes several microseconds to be acknowledged; this keeps two tiles of stores per
+  // wave in flight instead of stalling on each.
+  double bv[2][NA];
+  const int tc_off = min(tc1, tr);            // tiles tc0 .. tc_off - 1 lie below the diagonal
+  auto load_cols = [&](auto set_c, int tc) {
+    constexpr int SET = decltype(set_c)::value;
+    const uint32_t q = prow + (uint32_t)tc * TILE + 16 * wave;
+    const double* __restrict__ Sc = S + (uint64_t)(q >> 4) * gstride + lofs;
+    if (NKS > 0) {
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) bv[SET][ks] = Sc[ks * 64];
     }
+  };
+  typedef std::integral_constant<int, 0> Set0;
+  typedef std::integral_constant<int, 1> Set1;
+  const int tc_last = tc1 - 1;                // prefetches past the item re-read its last tile
+  load_cols(Set0(), tc0);
+  load_cols(Set1(), min(tc0 + 1, tc_last));
+  // nothing is outstanding when the loop is entered: the compiler's count of outstanding
+  // operations at the loop head is the minimum over the ways in, and must not be the prologue's
+  __builtin_amdgcn_s_waitcnt(0x0F70);         // vmcnt(0)
+
+  float* __restrict__ sTw = &sT[wave][0];
+  const float dv = a.diag_val;
+  // One tile, with the operands of register set SET; DIAG marks the tile on the diagonal, which
+  // has no mirror image and no successor.
+  auto tile = [&](auto diag_c, auto set_c, const int tc) {
+    constexpr bool DIAG = decltype(diag_c)::value;
+    constexpr int SET = decltype(set_c)::value;
+    const int q0 = tc * TILE;
+    v4d acc[4];
+#pragma unroll
+    for (int ti = 0; ti < 4; ++ti) acc[ti] = (v4d){0.0, 0.0, 0.0, 0.0};
+    if (NKS > 0) {
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+        for (int ti = 0; ti < 4; ++ti)
+          acc[ti] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[ti][ks], bv[SET][ks], acc[ti], 0, 0, 0);
+    } else {
+      const double* __restrict__ Sc = S + (uint64_t)((prow + (uint32_t)q0 + 16 * wave) >> 4) * gstride + lofs;
+      for (int ks = 0; ks < nks; ++ks) {
+        const double b = Sc[ks * 64];
+#pragma unroll
+        for (int ti = 0; ti < 4; ++ti)
+          acc[ti] = __builtin_amdgcn_mfma_f64_16x16x4f64(Srow[ti * gstride + ks * 64], b, acc[ti], 0, 0, 0);
+      }
+    }
+    const double nc = sNc[(tc - tc0) * TILE + 16 * wave + m];
+    if (!DIAG) load_cols(set_c, min(tc + 2, tc_last));
+
+    // entry (row 16 ti + kk + 4 i, column 16 wave + m) of the tile, masked, into the staging area
+    const int q = q0 + 16 * wave + m;
+    // tiles that can hold dropped or replaced entries: on the diagonal, at the ragged end, or (coupling)
+    // overlapping a same-cluster block of r x r representatives (q0 <= p0 inside an item)
+    const bool edge = DIAG || p0 + TILE > total || q0 + TILE > total ||
+                      (COUPLING && (q0 + TILE - 1) / r >= p0 / r);
+#pragma unroll
+    for (int ti = 0; ti < 4; ++ti) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = 16 * ti + kk + 4 * i;
+        const double arg = fma(-2.0, acc[ti][i], sNr[row] + nc);
+        float x = (float)(a.alpha * exp2_neg(arg));
+        if (edge) {
+          const int p = p0 + row;
+          bool keep = p < total && q < total;
+          if (COUPLING) {
+            // only blocks between DIFFERENT clusters enter K' (eq. (odsplit)): same-cluster entries are 0
+            keep = keep && (p / r) != (q / r);
+            x = keep ? x : 0.f;
+          } else {
+            x = keep ? x : 0.f;
+            if (p == q && p < total) x = dv;
+          }
+        }
+        sTw[row * ST_LD + m] = x;
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // the tile itself: rows p0 + row, 64 bytes (this wave's 16 columns) per row
+    {
+      const int f = lane & 3;
+      float* __restrict__ o = out + (uint64_t)(p0 + (lane >> 2)) * ld + q0 + 16 * wave + 4 * f;
+      const float* __restrict__ t = sTw + (lane >> 2) * ST_LD + 4 * f;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float* tt = t + 16 * j * ST_LD;
+        *reinterpret_cast<float4*>(o + (uint64_t)(16 * j) * ld) = make_float4(tt[0], tt[1], tt[2], tt[3]);
+      }
+    }
+    // its mirror image: rows q0 + 16 wave + c, 256 bytes (64 columns starting at p0) per row
+    if (!DIAG) {
+      const int f = lane & 15;
+      float* __restrict__ o = out + (uint64_t)(q0 + 16 * wave + kk) * ld + p0 + 4 * f;
+      const float* __restrict__ t = sTw + (4 * f) * ST_LD + kk;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float* tt = t + 4 * j;
+        *reinterpret_cast<float4*>(o + (uint64_t)(4 * j) * ld) =
+            make_float4(tt[0], tt[ST_LD], tt[2 * ST_LD], tt[3 * ST_LD]);
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  };
+  // pairs of off-diagonal tiles (identical memory-operation counts every trip), then an odd
+  // one, then the diagonal tile, whose operands sit in the set its parity selects
+  int tc = tc0;
+  for (; tc + 1 < tc_off; tc += 2) {
+    tile(std::false_type(), Set0(), tc);
+    tile(std::false_type(), Set1(), tc + 1);
+  }
+  if (tc < tc_off) {
+    tile(std::false_type(), Set0(), tc);
+    if (tc1 > tr) tile(std::true_type(), Set1(), tr);
+  } else if (tc1 > tr) {
+    tile(std::true_type(), Set0(), tr);
   }
 }
 
@@ -299,7 +358,7 @@ int launch_setup(nugpr_ctx* c, const float* user_reps, const float* user_W, hipS
   for (int i = 0; i < L.nc; ++i)
     for (uint32_t tr = 0; tr < L.cl[i].nt; ++tr)
       for (uint32_t tc = 0; tc <= tr; ++tc) tiles.push_back(((uint64_t)i << 32) | ((uint64_t)tr << 16) | tc);
-  constexpr uint32_t MAXT = 16;          // tiles per work item
+  constexpr uint32_t MAXT = MAX_ITEM_TILES;
   auto panel_items = [&](uint32_t nt, uint64_t ci, std::vector<uint64_t>& v) {
     for (uint32_t tr = 0; tr < nt; ++tr)
       for (uint32_t t0 = 0; t0 <= tr; t0 += MAXT)
@@ -347,22 +406,38 @@ int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s) {
     if (!(theta[i] > 0.0) || !std::isfinite(theta[i])) { set_error("theta entries must be finite and > 0"); return NUGPR_ERR_INVALID; }
   const bool iso = (c->params.flags & NUGPR_ISOTROPIC) != 0;
   const double alpha = theta[L.p - 2], sigma2 = theta[L.p - 1];
-  PairArgs a;
+  ScaleArgs sa;
   const double half_log2e = 0.5 * 1.4426950408889634074;
-  for (int k = 0; k < MAX_D; ++k) a.sw[k] = 0.0;
+  for (int k = 0; k < MAX_D; ++k) sa.sw[k] = 0.0;
   for (int k = 0; k < L.d; ++k) {
     const double ell = iso ? theta[0] : theta[k];
-    a.sw[k] = std::sqrt(half_log2e) / ell;
+    sa.sw[k] = std::sqrt(half_log2e) / ell;
   }
+  sa.d = L.d;
+  PanelArgs a;
   a.alpha = alpha;
   a.diag_val = (float)(alpha + sigma2);
-  a.d = L.d;
+  a.kd = pair_kd(L.d);
   c->diag_residual = (float)((alpha + sigma2) - (double)a.diag_val);
-  const size_t lds = pair_lds_bytes(L.d);
-  hipLaunchKernelGGL((k_build_panel<false>), dim3((unsigned)c->n_pan_diag), dim3(256), lds, s, a, c->d_cl, c->d_pan_diag,
-                     c->X, c->Kd, 0, 1, 0u);
-  hipLaunchKernelGGL((k_build_panel<true>), dim3((unsigned)c->n_pan_c), dim3(256), lds, s, a, c->d_cl, c->d_pan_c,
-                     c->reps, c->C, L.ncr, L.r, (uint32_t)L.ldc);
+  hipLaunchKernelGGL(k_scale_points, dim3((unsigned)L.ntmax, (unsigned)L.nc), dim3(256), 0, s, sa, c->d_cl, c->X, c->Xs,
+                     c->Xn, 0, 0);
+  hipLaunchKernelGGL(k_scale_points, dim3((unsigned)(L.ldc / TILE), 1u), dim3(256), 0, s, sa,
+                     (const ClusterInfo*)nullptr, c->reps, c->Rs, c->Rn, L.ncr, L.ldc);
+  const dim3 gd((unsigned)c->n_pan_diag), gc((unsigned)c->n_pan_c), blk(256);
+#define NUGPR_PANELS(NKS)                                                                                          \
+  do {                                                                                                             \
+    hipLaunchKernelGGL((k_build_panel<false, NKS>), gd, blk, 0, s, a, c->d_cl, c->d_pan_diag, c->Xs, c->Xn, c->Kd, \
+                       0, 1, 0u);                                                                                  \
+    hipLaunchKernelGGL((k_build_panel<true, NKS>), gc, blk, 0, s, a, c->d_cl, c->d_pan_c, c->Rs, c->Rn, c->C,      \
+                       L.ncr, L.r, (uint32_t)L.ldc);                                                               \
+  } while (0)
+  switch (a.kd / 4) {        // the dimensions of the usual workloads get their own instantiation
+    case 1: NUGPR_PANELS(1); break;
+    case 2: NUGPR_PANELS(2); break;
+    case 5: NUGPR_PANELS(5); break;
+    default: NUGPR_PANELS(0); break;
+  }
+#undef NUGPR_PANELS
   NUGPR_HIP(hipGetLastError());
   c->built = true;
   return NUGPR_OK;

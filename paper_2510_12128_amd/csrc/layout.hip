@@ -45,7 +45,7 @@ int plan_layout(const nugpr_problem* pb, uint32_t flags, Layout& L) {
   L.ldc = (int)align_up(L.ncr, TILE);
   L.ldw = (int)align_up(L.r, TILE);
   L.cl.resize(L.nc);
-  uint64_t koff = 0, wtoff = 0;
+  uint64_t koff = 0, wtoff = 0, prow = 0;
   for (int i = 0; i < L.nc; ++i) {
     int64_t b = off[i + 1] - off[i];
     if (b < L.r) { set_error("a cluster is smaller than rank (or offsets not ascending)"); return NUGPR_ERR_INVALID; }
@@ -57,12 +57,17 @@ int plan_layout(const nugpr_problem* pb, uint32_t flags, Layout& L) {
     c.nt = c.ld / TILE;
     c.koff = koff;
     c.wtoff = wtoff;
+    c.prow = (uint32_t)prow;
+    c.pad_ = 0;
+    prow += c.ld;
     koff += (uint64_t)c.ld * c.ld;
     wtoff += (uint64_t)L.r * c.ld;
     L.ntmax = std::max<int>(L.ntmax, (int)c.nt);
     L.n_diag_tiles += (uint64_t)c.nt * (c.nt + 1) / 2;
   }
   L.kd_elems = koff;
+  L.rows_pad = prow;
+  if (prow > 0xffffffffull) { set_error("padded row count out of range"); return NUGPR_ERR_INVALID; }
   L.wt_elems = wtoff;
   {
     uint64_t ct = (uint64_t)L.ldc / TILE;
@@ -92,6 +97,13 @@ int plan_layout(const nugpr_problem* pb, uint32_t flags, Layout& L) {
   L.o_Wd = take(cur, (size_t)L.n * L.ldw * f);
   L.o_Wt = take(cur, L.wt_elems * f);
   L.o_reps = take(cur, (size_t)L.ncr * L.d * f);
+  {
+    const size_t kd = (size_t)((L.d + 3) & ~3);
+    L.o_Xs = take(cur, (size_t)L.rows_pad * kd * sizeof(double));
+    L.o_Xn = take(cur, (size_t)L.rows_pad * sizeof(double));
+    L.o_Rs = take(cur, (size_t)L.ldc * kd * sizeof(double));
+    L.o_Rn = take(cur, (size_t)L.ldc * sizeof(double));
+  }
   L.o_B = take(cur, vec);
   L.o_X = take(cur, vec);
   L.o_R = take(cur, vec);

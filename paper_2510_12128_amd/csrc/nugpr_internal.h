@@ -26,6 +26,8 @@ struct ClusterInfo {
   uint32_t b;       // points in the cluster
   uint32_t ld;      // leading dimension of its square blocks: b rounded up to 64
   uint32_t nt;      // number of 64-wide tiles per side: ld / 64
+  uint32_t prow;    // first row of the cluster in the padded row numbering (sum of ld of the clusters before it)
+  uint32_t pad_;
 };
 
 // ---------------------------------------------------------------------------
@@ -108,11 +110,13 @@ struct Layout {
   int nsS = 1, nsP = 1;
   std::vector<ClusterInfo> cl;
   uint64_t kd_elems = 0, wt_elems = 0;
+  uint64_t rows_pad = 0;      // sum of ld over the clusters
   // byte offsets into the workspace
   size_t o_cl = 0, o_Kd = 0, o_Lf = 0, o_G = 0, o_C = 0, o_Wd = 0, o_Wt = 0, o_reps = 0;
   size_t o_B = 0, o_X = 0, o_R = 0, o_Z = 0, o_D = 0, o_Q = 0, o_V = 0, o_U = 0;
   size_t o_Spart = 0, o_Ppart = 0, o_dot = 0, o_state = 0, o_alog = 0, o_blog = 0;
   size_t o_theta = 0, o_logdet = 0, o_tiles = 0, o_items = 0;
+  size_t o_Xs = 0, o_Xn = 0, o_Rs = 0, o_Rn = 0;
   size_t items_bytes = 0;
   int n_dot_blocks = 0;
   int max_iter = 0;
@@ -132,6 +136,9 @@ struct nugpr_ctx {
   // device views into the workspace
   nugpr::ClusterInfo* d_cl = nullptr;
   float *Kd = nullptr, *Lf = nullptr, *G = nullptr, *C = nullptr, *Wd = nullptr, *Wt = nullptr, *reps = nullptr;
+  // lengthscale-scaled coordinates in fp64, in MFMA operand order, and their squared norms:
+  // of the points (padded row numbering) and of the representatives
+  double *Xs = nullptr, *Xn = nullptr, *Rs = nullptr, *Rn = nullptr;
   // vector blocks: fp64 when acc64, else fp32 (sized for fp64 either way)
   void *Bv = nullptr, *Xv = nullptr, *Rv = nullptr, *Zv = nullptr, *Dv = nullptr, *Qv = nullptr, *Vv = nullptr,
        *Uv = nullptr;

@@ -57,9 +57,13 @@ __device__ __forceinline__ int acc_row(int lane, int i) {
 
 constexpr int CHUNK = 64;              // columns per pipeline stage
 constexpr int NL = CHUNK / 16;         // float4 loads per lane per chunk
+constexpr int NPRE = 1;                // register sets of matrix chunks in flight per wave (1 or 2)
 
+// At least two waves per SIMD: with at most 256 registers a wave the compiler keeps the MFMA
+// accumulators in ordinary vector registers instead of copying them in and out of the
+// accumulation registers around every chunk.
 template <int NG, bool ACC64>
-__global__ __launch_bounds__(256) void k_strip(const StripArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_strip(const StripArgs a) {
   typedef typename VecT<ACC64>::type VT;
   typedef typename std::conditional<ACC64, Quad64, Quad32>::type QuadT;
   constexpr int NCOLM = NG > 0 ? 16 * NG : 1;    // columns handled by the matrix cores
@@ -114,11 +118,14 @@ __global__ __launch_bounds__(256) void k_strip(const StripArgs a) {
   const int nelem = CHUNK * T;
   auto load_in = [&](int c, VT (&reg)[NE]) {
     const VT* __restrict__ src = vin + (uint64_t)(it.in_row0 + (uint32_t)c) * (uint64_t)T;
-    const int lim = min(nelem, (c_end - c) * T);
+    const int lim = min(nelem, (c_end - c) * T);       // >= T: chunk c starts before c_end
+    // every lane loads (from a clamped address) so the loads sit in straight-line code and
+    // the outstanding-load counter stays exact; lanes past the slab keep a zero instead
 #pragma unroll
     for (int k = 0; k < NE; ++k) {
       const int e = tid + 256 * k;
-      reg[k] = e < lim ? src[e] : (VT)0;
+      const VT v = src[e < lim ? e : lim - 1];
+      reg[k] = e < lim ? v : (VT)0;
     }
   };
   auto store_in = [&](int buf, const VT (&reg)[NE]) {
@@ -134,10 +141,26 @@ __global__ __launch_bounds__(256) void k_strip(const StripArgs a) {
     }
   };
 
-  // one 16-column step: 4 MFMAs per column group + the y column on the vector ALUs
-  auto step = [&](const float4 av, int buf, int s) {
+  // one 16-column step: 4 MFMAs per column group + the y column on the vector ALUs.
+  // `slot` is the register the 16 columns came from; it is reloaded from `next` as soon as its
+  // value has been consumed (widened in the fp64 mode, issued to the matrix cores in the
+  // fp32 mode).  The scheduling barriers keep the compiler from moving the reload ahead of
+  // that point, where it would need a second register set and a drain at the loop's end.
+  auto step = [&](float4& slot, const float* __restrict__ next, const bool masked, const int q0, int buf, int s) {
+    float4 av = slot;
+    if (masked) {
+      av.x = (q0 + 0 >= q_lo && q0 + 0 < q_hi) ? av.x : 0.f;
+      av.y = (q0 + 1 >= q_lo && q0 + 1 < q_hi) ? av.y : 0.f;
+      av.z = (q0 + 2 >= q_lo && q0 + 2 < q_hi) ? av.z : 0.f;
+      av.w = (q0 + 3 >= q_lo && q0 + 3 < q_hi) ? av.w : 0.f;
+    }
     if constexpr (ACC64) {
       const double ax = (double)av.x, ay = (double)av.y, az = (double)av.z, aw = (double)av.w;
+      // empty statement that ties the reload's address to the widened values: the reload
+      // cannot be issued before the old contents of the slot have been consumed
+      int dep = 0;
+      asm volatile("" : "+v"(dep) : "v"(ax), "v"(ay), "v"(az), "v"(aw));
+      slot = *reinterpret_cast<const float4*>(next + dep);
       if (NG > 0) {
 #pragma unroll
         for (int g = 0; g < NG; ++g) {
@@ -169,47 +192,40 @@ __global__ __launch_bounds__(256) void k_strip(const StripArgs a) {
       accy32[1] = fmaf(av.y, yv.y, accy32[1]);
       accy32[2] = fmaf(av.z, yv.z, accy32[2]);
       accy32[3] = fmaf(av.w, yv.w, accy32[3]);
+      __builtin_amdgcn_sched_barrier(0);
+      slot = *reinterpret_cast<const float4*>(next);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
-  float4 areg[NL];
+  // NPRE register sets hold the matrix chunks in flight: set (ch % NPRE) carries chunk ch
+  // and slot s of it is reloaded with chunk ch + NPRE right after it has been read, so
+  // the loads of NPRE chunks are outstanding while the matrix cores work on one.
+  float4 areg[NPRE][NL];
   VT inreg[NE];
+  const int c_last = c_begin + (nchunks - 1) * CHUNK;    // chunks past the end re-read the last one
   if (nchunks > 0) {
 #pragma unroll
-    for (int s = 0; s < NL; ++s) areg[s] = *reinterpret_cast<const float4*>(Arow + c_begin + 16 * s);
+    for (int p = 0; p < NPRE; ++p) {
+      const float* __restrict__ Ap = Arow + min(c_begin + p * CHUNK, c_last);
+#pragma unroll
+      for (int s = 0; s < NL; ++s) areg[p][s] = *reinterpret_cast<const float4*>(Ap + 16 * s);
+    }
     load_in(c_begin, inreg);
     store_in(0, inreg);
   }
   __syncthreads();
 
-  for (int ch = 0; ch < nchunks; ++ch) {
-    const int c = c_begin + ch * CHUNK;
+  auto chunk = [&](auto set_c, const int ch) {
+    constexpr int SET = decltype(set_c)::value;
     const int buf = ch & 1;
-    const bool more = ch + 1 < nchunks;
-    const int cn = more ? c + CHUNK : c;       // the last chunk re-reads itself instead of branching
-    load_in(cn, inreg);
-    const float* __restrict__ An = Arow + cn;
-    if (c >= mask_from || c < mask_upto) {
-      // chunk with elements outside the item's column range or on the wrong side of the diagonal
+    const int c = c_begin + ch * CHUNK;
+    load_in(min(c + CHUNK, c_last), inreg);
+    const float* __restrict__ An = Arow + min(c + NPRE * CHUNK, c_last);
+    // chunk with elements outside the item's column range or on the wrong side of the diagonal
+    const bool masked = (c >= mask_from || c < mask_upto);
 #pragma unroll
-      for (int s = 0; s < NL; ++s) {
-        float4 av = areg[s];
-        areg[s] = *reinterpret_cast<const float4*>(An + 16 * s);
-        const int q0 = c + 16 * s + 4 * kg;
-        av.x = (q0 + 0 >= q_lo && q0 + 0 < q_hi) ? av.x : 0.f;
-        av.y = (q0 + 1 >= q_lo && q0 + 1 < q_hi) ? av.y : 0.f;
-        av.z = (q0 + 2 >= q_lo && q0 + 2 < q_hi) ? av.z : 0.f;
-        av.w = (q0 + 3 >= q_lo && q0 + 3 < q_hi) ? av.w : 0.f;
-        step(av, buf, s);
-      }
-    } else {
-#pragma unroll
-      for (int s = 0; s < NL; ++s) {
-        const float4 av = areg[s];
-        areg[s] = *reinterpret_cast<const float4*>(An + 16 * s);
-        step(av, buf, s);
-      }
-    }
+    for (int s = 0; s < NL; ++s) step(areg[SET][s], An + 16 * s, masked, c + 16 * s + 4 * kg, buf, s);
     if constexpr (!ACC64) {
       // fold this chunk's short chains into the fp64 sums and restart them
       if (NG > 0) {
@@ -228,6 +244,17 @@ __global__ __launch_bounds__(256) void k_strip(const StripArgs a) {
     }
     store_in(buf ^ 1, inreg);
     __syncthreads();
+  };
+  if constexpr (NPRE == 1) {
+    for (int ch = 0; ch < nchunks; ++ch) chunk(std::integral_constant<int, 0>(), ch);
+  } else {
+    static_assert(NPRE <= 2, "the chunk loop is unrolled by the number of register sets");
+    // An odd chunk count is rounded up: the extra chunk starts at or past c_end, so it is a
+    // masked chunk whose every element is dropped (it re-reads the last chunk's data).
+    for (int ch = 0; ch < nchunks; ch += 2) {
+      chunk(std::integral_constant<int, 0>(), ch);
+      chunk(std::integral_constant<int, NPRE - 1>(), ch + 1);
+    }
   }
 
   // ---- epilogue ----
