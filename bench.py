@@ -27,7 +27,7 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of the dominant kernel from the two rocprofv3 --pmc runs summarised in
 # profiles/k_strip_C4_*_hbm_traffic.md (FETCH_SIZE + WRITE_SIZE, scaled by the copy probe).
 # Counter runs are separate from this program, so the figure is quoted, not measured live.
-MEASURED_TRAFFIC_BYTES = {("C4", "fp64"): 3.646e9}
+MEASURED_TRAFFIC_BYTES = {("C4", "fp64"): 3.711e9}
 
 
 def cpu_baseline(w, n_sample_clusters):
@@ -107,9 +107,11 @@ def main():
     ctx.nugpr_profile_enable(True)
     sync()
     t0 = time.perf_counter()
-    codes = []
+    codes, step_ms, step_iters = [], [], []
     for _ in range(args.steps):
-        out = ctx.nugpr_train_step(phi, m, v, step)
+        ts = time.perf_counter()
+        out = ctx.nugpr_train_step(phi, m, v, step)      # returns after the step's last synchronisation
+        step_ms.append((time.perf_counter() - ts) * 1e3)
         phi, m, v, step = out["log_theta"], out["adam_m"], out["adam_v"], out["step"]
         codes.append(out["code"])
     sync()
@@ -174,7 +176,7 @@ def main():
         "config": {"workload": "%s: n=%d, d=%d, %d clusters, r=%d, t=%d, tol=%g; one step = nugpr_train_step "
                                "(factor + %d loss evaluations + Adam)" % (args.config, n, ctx.d, nc, r, ctx.t,
                                                                           w.tol, 1 + 2 * p),
-                   "acc": args.acc, "status_codes": codes},
+                   "acc": args.acc, "status_codes": codes, "step_ms": [round(x, 2) for x in step_ms]},
         "kv_gbps": kv_alg_bytes / (kv_ms * 1e-3) / 1e9,
         "kv_ms": kv_ms,
         "kv_algorithmic_bytes": kv_alg_bytes,
@@ -184,7 +186,7 @@ def main():
         "precond_factor_ms": factor_ms,
         "mll_ms": mll_ms,
         "mll_iters": res["max_iters_used"],
-        "roofline": {"bound": "hbm", "kernel": "k_strip (K_diag.D and C.S in one launch)",
+        "roofline": {"bound": "hbm", "kernel": "strip kernel (K_diag.D and C.S in one launch)",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, args.acc)),

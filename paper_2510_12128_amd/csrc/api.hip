@@ -138,6 +138,13 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   c->L = L;
   c->params = *prm;
   c->acc64 = (prm->flags & NUGPR_ACC_FP32) == 0;
+  {
+    // the assembly launches run as persistent workgroups, two per compute unit of the current device
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+      c->build_grid = 2 * cus;
+  }
   if (c->params.beta1 == 0.0) c->params.beta1 = 0.9;
   if (c->params.beta2 == 0.0) c->params.beta2 = 0.999;
   if (c->params.eps == 0.0) c->params.eps = 1e-8;
@@ -156,6 +163,7 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   c->Xn = reinterpret_cast<double*>(w + L.o_Xn);
   c->Rs = reinterpret_cast<double*>(w + L.o_Rs);
   c->Rn = reinterpret_cast<double*>(w + L.o_Rn);
+  c->build_ctr = reinterpret_cast<int*>(w + L.o_bctr);
   c->Bv = w + L.o_B;
   c->Xv = w + L.o_X;
   c->Rv = w + L.o_R;

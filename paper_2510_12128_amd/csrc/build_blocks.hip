@@ -41,25 +41,6 @@ struct ScaleArgs {
   int32_t d;
 };
 
-// 2^(-a) in fp64: a = n + f, |f| <= 1/2, 2^-f by its Taylor series in g = -f ln 2
-// (degree 9 at |g| <= 0.347: relative error < 1e-11), scaled by 2^-n.
-__device__ __forceinline__ double exp2_neg(double a) {
-  const double n = rint(a);
-  const double g = (n - a) * 0.69314718055994530942;
-  double p = 1.0 / 362880.0;
-  p = fma(p, g, 1.0 / 40320.0);
-  p = fma(p, g, 1.0 / 5040.0);
-  p = fma(p, g, 1.0 / 720.0);
-  p = fma(p, g, 1.0 / 120.0);
-  p = fma(p, g, 1.0 / 24.0);
-  p = fma(p, g, 1.0 / 6.0);
-  p = fma(p, g, 0.5);
-  p = fma(p, g, 1.0);
-  p = fma(p, g, 1.0);
-  const int e = n > 2000.0 ? -2000 : -(int)n;
-  return ldexp(p, e);
-}
-
 __host__ __device__ inline int pair_kd(int d) { return (d + 3) & ~3; }
 
 // Scaled coordinates of the point with padded row number pr live at
@@ -70,7 +51,11 @@ __host__ __device__ inline int pair_kd(int d) { return (d + 3) & ~3; }
 // written as zeros.  grid.y = cluster (or 0 for the representatives), 64 points per block.
 __global__ __launch_bounds__(256) void k_scale_points(const ScaleArgs a, const ClusterInfo* __restrict__ cl,
                                                       const float* __restrict__ P, double* __restrict__ S,
-                                                      double* __restrict__ N, int single_total, int single_ld) {
+                                                      double* __restrict__ N, int single_total, int single_ld,
+                                                      int* __restrict__ counters, int start0, int start1) {
+  // first launch of an assembly: the work counters of the two panel launches that follow start
+  // after the items their workgroups take by index
+  if (counters && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) { counters[0] = start0; counters[1] = start1; }
   uint32_t first, total, ld, prow;
   if (cl) {
     const ClusterInfo c = cl[blockIdx.y];
@@ -100,64 +85,98 @@ struct PanelArgs {
   int32_t kd;           // coordinates per point in the scaled array (multiple of 4)
 };
 
-constexpr int ST_LD = 17;      // row stride of the staging area (floats)
-constexpr int MAX_ITEM_TILES = 16;   // tiles per work item
+constexpr int ST_LD = 20;            // row stride of the staging area (floats): rows stay 16-byte aligned
+constexpr int MAX_ITEM_TILES = 32;   // tiles per work item
+
+// alpha * 2^(-a) for a >= 0 (up to rounding), rounded once to fp32.
+// a = n + r with n = rint(a) by the 1.5 * 2^52 trick (n also lands in the low word of the
+// sum), 2^-r = 2^f, f = n - a in [-1/2, 1/2], by its Taylor series (degree 9 at
+// |f ln 2| <= 0.347: relative error < 1e-11); the factor 2^-n is a subtraction in the
+// exponent field.  Arguments above 900 give 2^-900 alpha, which rounds to zero like the true
+// value does.  Only full-rate vector instructions are used.
+__device__ __forceinline__ float kernel_value(double a, double alpha) {
+  constexpr double MAGIC = 6755399441055744.0;            // 1.5 * 2^52
+  constexpr double L = 0.69314718055994530942;
+  a = fmin(a, 900.0);
+  const double big = a + MAGIC;
+  const double f = (big - MAGIC) - a;
+  double p = L * L * L * L * L * L * L * L * L / 362880.0;
+  p = fma(p, f, L * L * L * L * L * L * L * L / 40320.0);
+  p = fma(p, f, L * L * L * L * L * L * L / 5040.0);
+  p = fma(p, f, L * L * L * L * L * L / 720.0);
+  p = fma(p, f, L * L * L * L * L / 120.0);
+  p = fma(p, f, L * L * L * L / 24.0);
+  p = fma(p, f, L * L * L / 6.0);
+  p = fma(p, f, L * L / 2.0);
+  p = fma(p, f, L);
+  p = fma(p, f, 1.0);
+  const int n = __double2loint(big);
+  const double scaled = __hiloint2double(__double2hiint(p) - (n << 20), __double2loint(p));
+  return (float)(alpha * scaled);
+}
 
 // One work item = tile row `tr` of one square symmetric matrix (a cluster's K_ii, or the
 // coupling C) and the run of tile columns tc0..tc1-1 (<= tr).
 // item = cluster << 48 | tr << 32 | tc0 << 16 | tc1.
-// Wave w computes columns 16 w .. 16 w + 15 of every tile: four 16 x 16 accumulators (one
-// per 16-row group), the row operands of the item held in registers (NKS > 0) and the
-// column operand of the next tile loaded while the current one is exponentiated and stored.
-// NKS = kd / 4 when positive; NKS = 0 handles any kd and re-reads the row operands per tile.
+//
+// Wave w computes columns 16 w .. 16 w + 15 of every tile with four 16 x 16 fp64 MFMA
+// accumulators (one per 16-row group); the row operands of the item sit in LDS, the
+// column operands of the tiles ahead in two register sets.  The rows of a group are fed to
+// the matrix cores in the order 0,4,8,12,1,5,.. so that a lane ends up with FOUR CONSECUTIVE
+// rows of one column: that is a 16-byte piece of the mirror image, stored straight from
+// registers.  The tile itself needs the other orientation and goes through a wave-private
+// LDS staging area (16-byte reads and stores).  The eight stores of a tile are issued one
+// after every second entry, each LDS read one row group ahead of its store.
+//
+// On this chip the fp64 matrix instructions run at the rate of the vector ALU and do not
+// overlap with it, so the kernel is bound by its instruction count: the exponential uses
+// full-rate instructions only, and the masks run on the tiles that need them.
+// NKS = kd / 4 when positive (operands prefetched); NKS = 0 handles any kd and reads the
+// column operands of a tile when it needs them.
 template <bool COUPLING, int NKS>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
-void k_build_panel(const PanelArgs a, const ClusterInfo* __restrict__ cl, const uint64_t* __restrict__ items,
-                   const double* __restrict__ S, const double* __restrict__ N, float* __restrict__ out_base,
-                   int ncr, int r, uint32_t ldc) {
+void k_build_panel(const PanelArgs a, const BuildItem* __restrict__ items, const double* __restrict__ S,
+                   const double* __restrict__ N, float* __restrict__ out_base, int n_items, int r,
+                   int* __restrict__ counter) {
+  extern __shared__ __attribute__((aligned(16))) double sA[];      // 4 * kd * 16 doubles: row operands
   __shared__ double sNr[TILE];
-  __shared__ double sNc[MAX_ITEM_TILES * TILE];      // column norms of every tile of the item
-  __shared__ float sT[4][TILE * ST_LD];
+  __shared__ double sNc[MAX_ITEM_TILES * TILE];                    // column norms of every tile of the item
+  __shared__ __attribute__((aligned(16))) float sT[4][TILE * ST_LD];
 
-  const uint64_t it = items[blockIdx.x];
-  const int ci = (int)(it >> 48), tr = (int)((it >> 32) & 0xffff), tc0 = (int)((it >> 16) & 0xffff),
-            tc1 = (int)(it & 0xffff);
-  int total;
-  uint32_t ld, prow;
-  float* out;
-  if (COUPLING) {
-    total = ncr; ld = ldc; out = out_base; prow = 0;
-  } else {
-    const ClusterInfo c = cl[ci];
-    total = (int)c.b; ld = c.ld; out = out_base + c.koff; prow = c.prow;
+  // Persistent workgroups: the first item is the workgroup's own index, the following ones come from a
+  // shared counter (the items differ in length and the tiles in cost).  Thread 0 draws the next index and
+  // fetches its descriptor into LDS while the current item is worked on; the barrier that ends the item
+  // publishes it, so an item starts with ONE round trip to memory (its operands).
+  __shared__ BuildItem s_item[2];
+  __shared__ int s_index[2];
+  if (threadIdx.x == 0) {
+    s_index[0] = (int)blockIdx.x;
+    if ((int)blockIdx.x < n_items) s_item[0] = items[blockIdx.x];
   }
+  __syncthreads();
+  for (int slot = 0; s_index[slot] < n_items; slot ^= 1) {
+  const BuildItem cur = s_item[slot];
+  int next_index = 0;
+  if (threadIdx.x == 0) next_index = atomicAdd(counter, 1);
+  const int tr = cur.tr, tc0 = cur.tc0, tc1 = cur.tc1;
+  const int total = (int)cur.total;
+  const uint32_t ld = cur.ld, prow = cur.prow;
+  float* __restrict__ out = out_base + cur.out_off;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int m = lane & 15, kk = lane >> 4;
   const int kd = a.kd, nks = NKS > 0 ? NKS : kd / 4;
   const int p0 = tr * TILE;
   const uint64_t gstride = (uint64_t)kd * 16;                 // doubles per group of 16 points
   const int lofs = kk * 16 + m;                               // this lane's element of a 4-coordinate step
-  const double* __restrict__ Srow = S + (uint64_t)((prow + p0) >> 4) * gstride + lofs;
+  // row operand: matrix row m of a group carries point 4 (m % 4) + m / 4, so accumulator
+  // component i of lane (kk, m) is point 4 kk + i of the group, column m
+  const int aofs = kk * 16 + 4 * (m & 3) + (m >> 2);
 
-  if (tid < TILE) sNr[tid] = N[prow + p0 + tid];
-  for (int i = tid; i < (tc1 - tc0) * TILE; i += 256) sNc[i] = N[prow + (uint32_t)tc0 * TILE + i];
   constexpr int NA = NKS > 0 ? NKS : 1;
-  double av[4][NA];
-  if (NKS > 0) {
-#pragma unroll
-    for (int ti = 0; ti < 4; ++ti)
-#pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) av[ti][ks] = Srow[ti * gstride + ks * 64];
-  }
-  __syncthreads();
-
-  // Column operands of two tiles ahead live in two register sets: the loads of tile
-  // tc + 2 are issued before the stores of tile tc, and because the outstanding-operation
-  // counter retires in order, waiting for them later only drains stores that are two tiles old.
-  // A store takes several microseconds to be acknowledged; this keeps two tiles of stores per
-  // wave in flight instead of stalling on each.
+  // Column operands of two tiles ahead live in two register sets: a load is issued before
+  // the stores that follow it in program order, and the outstanding-operation counter retires
+  // in order, so waiting for operands never waits for the stores of the last two tiles.
   double bv[2][NA];
-  const int tc_off = min(tc1, tr);            // tiles tc0 .. tc_off - 1 lie below the diagonal
   auto load_cols = [&](auto set_c, int tc) {
     constexpr int SET = decltype(set_c)::value;
     const uint32_t q = prow + (uint32_t)tc * TILE + 16 * wave;
@@ -172,16 +191,93 @@ void k_build_panel(const PanelArgs a, const ClusterInfo* __restrict__ cl, const 
   const int tc_last = tc1 - 1;                // prefetches past the item re-read its last tile
   load_cols(Set0(), tc0);
   load_cols(Set1(), min(tc0 + 1, tc_last));
+  // (the loads above are in flight while the shared operands are fetched: one round trip in all)
+  {
+    // all loads first, then the LDS writes: one round trip, not one per loop iteration
+    constexpr int NCN = MAX_ITEM_TILES * TILE / 256;            // column norms per thread
+    constexpr int NCA = NKS > 0 ? NKS : MAX_D / 4;              // row operand elements per thread (4 kd 16 / 256)
+    const double* __restrict__ Nc = N + prow + (uint32_t)tc0 * TILE;
+    const double* __restrict__ Sg = S + (uint64_t)((prow + p0) >> 4) * gstride;
+    const int n_nc = (tc1 - tc0) * TILE, n_a = 4 * (int)gstride;
+    double rn[NCN], ra[NCA];
+    const double rr = N[prow + p0 + (tid & (TILE - 1))];
+#pragma unroll
+    for (int j = 0; j < NCN; ++j) rn[j] = Nc[min(tid + 256 * j, n_nc - 1)];
+#pragma unroll
+    for (int j = 0; j < NCA; ++j) ra[j] = Sg[min(tid + 256 * j, n_a - 1)];
+    if (tid < TILE) sNr[tid] = rr;
+#pragma unroll
+    for (int j = 0; j < NCN; ++j)
+      if (tid + 256 * j < n_nc) sNc[tid + 256 * j] = rn[j];
+    // the row operands of the item (4 groups x kd coordinates x 16 points, already in operand order)
+#pragma unroll
+    for (int j = 0; j < NCA; ++j)
+      if (tid + 256 * j < n_a) sA[tid + 256 * j] = ra[j];
+  }
+  __syncthreads();
+
   // nothing is outstanding when the loop is entered: the compiler's count of outstanding
   // operations at the loop head is the minimum over the ways in, and must not be the prologue's
   __builtin_amdgcn_s_waitcnt(0x0F70);         // vmcnt(0)
 
-  float* __restrict__ sTw = &sT[wave][0];
   const float dv = a.diag_val;
-  // One tile, with the operands of register set SET; DIAG marks the tile on the diagonal, which
-  // has no mirror image and no successor.
-  auto tile = [&](auto diag_c, auto set_c, const int tc) {
-    constexpr bool DIAG = decltype(diag_c)::value;
+  const double alpha = a.alpha;
+  float* __restrict__ sTw = &sT[wave][0];
+  // staging: this lane writes rows 16 ti + 4 kk + i, column m; it reads rows 16 k + lane / 4, columns
+  // 4 (lane % 4) .. + 3 for the store of the tile's own rows
+  float* __restrict__ st_w = sTw + (4 * kk) * ST_LD + m;
+  const float4* __restrict__ st_r = reinterpret_cast<const float4*>(sTw + (lane >> 2) * ST_LD + 4 * (lane & 3));
+  const uint64_t ld64 = ld;
+
+  // the sixteen entries of a tile: masked (EDGE) or not
+  auto entries = [&](auto edge_c, const v4d (&acc)[4], const double nc, const int q0) {
+    constexpr bool EDGE = decltype(edge_c)::value;
+    const int q = q0 + 16 * wave + m;
+    // the tile itself: rows p0 + 16 k + lane / 4, this wave's 16 columns (64 bytes a row)
+    float* __restrict__ od = out + (uint64_t)(p0 + (lane >> 2)) * ld64 + q0 + 16 * wave + 4 * (lane & 3);
+    // its mirror image: row q, columns p0 + 16 ti + 4 kk .. + 3; a tile on the diagonal is its own mirror
+    // image, entry for entry, and is simply written twice
+    float* __restrict__ om = out + (uint64_t)q * ld64 + p0 + 4 * kk;
+    float4 pending;
+#pragma unroll
+    for (int ti = 0; ti < 4; ++ti) {
+      float x[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = 16 * ti + 4 * kk + i;
+        const double arg = fma(-2.0, acc[ti][i], sNr[row] + nc);
+        x[i] = kernel_value(arg, alpha);
+        if (EDGE) {
+          const int p = p0 + row;
+          bool keep = p < total && q < total;
+          if (COUPLING) {
+            // only blocks between DIFFERENT clusters enter K' (eq. (odsplit)): same-cluster entries are 0
+            keep = keep && (p / r) != (q / r);
+            x[i] = keep ? x[i] : 0.f;
+          } else {
+            x[i] = keep ? x[i] : 0.f;
+            if (p == q && p < total) x[i] = dv;
+          }
+        }
+        st_w[(16 * ti + i) * ST_LD] = x[i];
+        if (i == 1) {
+          // rows of the previous group: read a group ago, stored now
+          if (ti > 0) *reinterpret_cast<float4*>(od + (uint64_t)(16 * (ti - 1)) * ld64) = pending;
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      *reinterpret_cast<float4*>(om + 16 * ti) = make_float4(x[0], x[1], x[2], x[3]);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      pending = st_r[ti * (16 * ST_LD / 4)];
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    *reinterpret_cast<float4*>(od + (uint64_t)48 * ld64) = pending;
+  };
+
+  // One tile with the operands of register set SET.
+  auto tile = [&](auto set_c, const int tc) {
     constexpr int SET = decltype(set_c)::value;
     const int q0 = tc * TILE;
     v4d acc[4];
@@ -192,88 +288,37 @@ void k_build_panel(const PanelArgs a, const ClusterInfo* __restrict__ cl, const 
       for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
         for (int ti = 0; ti < 4; ++ti)
-          acc[ti] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[ti][ks], bv[SET][ks], acc[ti], 0, 0, 0);
+          acc[ti] = __builtin_amdgcn_mfma_f64_16x16x4f64(sA[(ti * NKS + ks) * 64 + aofs], bv[SET][ks], acc[ti], 0, 0,
+                                                         0);
     } else {
       const double* __restrict__ Sc = S + (uint64_t)((prow + (uint32_t)q0 + 16 * wave) >> 4) * gstride + lofs;
       for (int ks = 0; ks < nks; ++ks) {
         const double b = Sc[ks * 64];
 #pragma unroll
         for (int ti = 0; ti < 4; ++ti)
-          acc[ti] = __builtin_amdgcn_mfma_f64_16x16x4f64(Srow[ti * gstride + ks * 64], b, acc[ti], 0, 0, 0);
+          acc[ti] = __builtin_amdgcn_mfma_f64_16x16x4f64(sA[(ti * nks + ks) * 64 + aofs], b, acc[ti], 0, 0, 0);
       }
     }
     const double nc = sNc[(tc - tc0) * TILE + 16 * wave + m];
-    if (!DIAG) load_cols(set_c, min(tc + 2, tc_last));
-
-    // entry (row 16 ti + kk + 4 i, column 16 wave + m) of the tile, masked, into the staging area
-    const int q = q0 + 16 * wave + m;
+    load_cols(set_c, min(tc + 2, tc_last));
     // tiles that can hold dropped or replaced entries: on the diagonal, at the ragged end, or (coupling)
     // overlapping a same-cluster block of r x r representatives (q0 <= p0 inside an item)
-    const bool edge = DIAG || p0 + TILE > total || q0 + TILE > total ||
+    const bool edge = tr == tc || p0 + TILE > total || q0 + TILE > total ||
                       (COUPLING && (q0 + TILE - 1) / r >= p0 / r);
-#pragma unroll
-    for (int ti = 0; ti < 4; ++ti) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = 16 * ti + kk + 4 * i;
-        const double arg = fma(-2.0, acc[ti][i], sNr[row] + nc);
-        float x = (float)(a.alpha * exp2_neg(arg));
-        if (edge) {
-          const int p = p0 + row;
-          bool keep = p < total && q < total;
-          if (COUPLING) {
-            // only blocks between DIFFERENT clusters enter K' (eq. (odsplit)): same-cluster entries are 0
-            keep = keep && (p / r) != (q / r);
-            x = keep ? x : 0.f;
-          } else {
-            x = keep ? x : 0.f;
-            if (p == q && p < total) x = dv;
-          }
-        }
-        sTw[row * ST_LD + m] = x;
-      }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    // the tile itself: rows p0 + row, 64 bytes (this wave's 16 columns) per row
-    {
-      const int f = lane & 3;
-      float* __restrict__ o = out + (uint64_t)(p0 + (lane >> 2)) * ld + q0 + 16 * wave + 4 * f;
-      const float* __restrict__ t = sTw + (lane >> 2) * ST_LD + 4 * f;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float* tt = t + 16 * j * ST_LD;
-        *reinterpret_cast<float4*>(o + (uint64_t)(16 * j) * ld) = make_float4(tt[0], tt[1], tt[2], tt[3]);
-      }
-    }
-    // its mirror image: rows q0 + 16 wave + c, 256 bytes (64 columns starting at p0) per row
-    if (!DIAG) {
-      const int f = lane & 15;
-      float* __restrict__ o = out + (uint64_t)(q0 + 16 * wave + kk) * ld + p0 + 4 * f;
-      const float* __restrict__ t = sTw + (4 * f) * ST_LD + kk;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float* tt = t + 4 * j;
-        *reinterpret_cast<float4*>(o + (uint64_t)(4 * j) * ld) =
-            make_float4(tt[0], tt[ST_LD], tt[2 * ST_LD], tt[3 * ST_LD]);
-      }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+    if (edge) entries(std::true_type(), acc, nc, q0);
+    else entries(std::false_type(), acc, nc, q0);
   };
-  // pairs of off-diagonal tiles (identical memory-operation counts every trip), then an odd
-  // one, then the diagonal tile, whose operands sit in the set its parity selects
   int tc = tc0;
-  for (; tc + 1 < tc_off; tc += 2) {
-    tile(std::false_type(), Set0(), tc);
-    tile(std::false_type(), Set1(), tc + 1);
+  for (; tc + 1 < tc1; tc += 2) {
+    tile(Set0(), tc);
+    tile(Set1(), tc + 1);
   }
-  if (tc < tc_off) {
-    tile(std::false_type(), Set0(), tc);
-    if (tc1 > tr) tile(std::true_type(), Set1(), tr);
-  } else if (tc1 > tr) {
-    tile(std::true_type(), Set0(), tr);
+  if (tc < tc1) tile(Set0(), tc);
+  if (threadIdx.x == 0) {
+    s_index[slot ^ 1] = next_index;
+    if (next_index < n_items) s_item[slot ^ 1] = items[next_index];
+  }
+  __syncthreads();            // the next item refills the shared operands
   }
 }
 
@@ -354,32 +399,40 @@ int launch_setup(nugpr_ctx* c, const float* user_reps, const float* user_W, hipS
   // tile list of the diagonal blocks (used when the inverse factor is mirrored) and the
   // row-panel work items of the two assembly launches, longest first
   std::vector<uint64_t> tiles;
-  tiles.reserve(2 * L.n_diag_tiles + L.n_c_tiles);
+  tiles.reserve(L.n_diag_tiles);
   for (int i = 0; i < L.nc; ++i)
     for (uint32_t tr = 0; tr < L.cl[i].nt; ++tr)
       for (uint32_t tc = 0; tc <= tr; ++tc) tiles.push_back(((uint64_t)i << 32) | ((uint64_t)tr << 16) | tc);
   constexpr uint32_t MAXT = MAX_ITEM_TILES;
-  auto panel_items = [&](uint32_t nt, uint64_t ci, std::vector<uint64_t>& v) {
+  auto panel_items = [&](uint32_t nt, uint64_t out_off, uint32_t prow, uint32_t total, uint32_t ld,
+                         std::vector<BuildItem>& v) {
     for (uint32_t tr = 0; tr < nt; ++tr)
-      for (uint32_t t0 = 0; t0 <= tr; t0 += MAXT)
-        v.push_back((ci << 48) | ((uint64_t)tr << 32) | ((uint64_t)t0 << 16) | std::min<uint32_t>(t0 + MAXT, tr + 1));
+      for (uint32_t t0 = 0; t0 <= tr; t0 += MAXT) {
+        BuildItem b{};
+        b.out_off = out_off; b.prow = prow; b.total = total; b.ld = ld;
+        b.tr = (uint16_t)tr; b.tc0 = (uint16_t)t0; b.tc1 = (uint16_t)std::min<uint32_t>(t0 + MAXT, tr + 1);
+        v.push_back(b);
+      }
   };
-  auto by_length = [](uint64_t x, uint64_t y) {
-    return ((x & 0xffff) - ((x >> 16) & 0xffff)) > ((y & 0xffff) - ((y >> 16) & 0xffff));
+  // longest first: the kernel's persistent workgroups draw the items in this order
+  auto arrange = [&](std::vector<BuildItem>& v) {
+    std::stable_sort(v.begin(), v.end(), [](const BuildItem& x, const BuildItem& y) {
+      return (x.tc1 - x.tc0) > (y.tc1 - y.tc0);
+    });
   };
-  std::vector<uint64_t> pd, pc;
-  for (int i = 0; i < L.nc; ++i) panel_items(L.cl[i].nt, (uint64_t)i, pd);
-  panel_items((uint32_t)(L.ldc / TILE), 0, pc);
-  std::stable_sort(pd.begin(), pd.end(), by_length);
-  std::stable_sort(pc.begin(), pc.end(), by_length);
+  std::vector<BuildItem> pd, pc;
+  for (int i = 0; i < L.nc; ++i) panel_items(L.cl[i].nt, L.cl[i].koff, L.cl[i].prow, L.cl[i].b, L.cl[i].ld, pd);
+  panel_items((uint32_t)(L.ldc / TILE), 0, 0, (uint32_t)L.ncr, (uint32_t)L.ldc, pc);
+  arrange(pd);
+  arrange(pc);
   c->n_pan_diag = (int)pd.size();
   c->n_pan_c = (int)pc.size();
-  c->d_pan_diag = c->d_tiles + tiles.size();
+  c->d_pan_diag = reinterpret_cast<BuildItem*>(c->d_tiles + tiles.size());
   c->d_pan_c = c->d_pan_diag + pd.size();
-  tiles.insert(tiles.end(), pd.begin(), pd.end());
-  tiles.insert(tiles.end(), pc.begin(), pc.end());
   NUGPR_HIP(hipMemcpyAsync(c->d_tiles, tiles.data(), tiles.size() * sizeof(uint64_t), hipMemcpyHostToDevice, s));
-  NUGPR_HIP(hipStreamSynchronize(s));   // `tiles` is about to go out of scope
+  NUGPR_HIP(hipMemcpyAsync(c->d_pan_diag, pd.data(), pd.size() * sizeof(BuildItem), hipMemcpyHostToDevice, s));
+  NUGPR_HIP(hipMemcpyAsync(c->d_pan_c, pc.data(), pc.size() * sizeof(BuildItem), hipMemcpyHostToDevice, s));
+  NUGPR_HIP(hipStreamSynchronize(s));   // the host vectors are about to go out of scope
   // padding of Wt (columns b..ld of every row) must read as zero
   hipLaunchKernelGGL(k_fill, dim3(1024), dim3(256), 0, s, c->Wt, L.wt_elems, 0.f);
   if (user_reps) {
@@ -419,17 +472,19 @@ int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s) {
   a.diag_val = (float)(alpha + sigma2);
   a.kd = pair_kd(L.d);
   c->diag_residual = (float)((alpha + sigma2) - (double)a.diag_val);
+  // persistent workgroups, two per compute unit, drawing items from a counter
+  const dim3 gd((unsigned)std::min(c->n_pan_diag, c->build_grid)), gc((unsigned)std::min(c->n_pan_c, c->build_grid)), blk(256);
   hipLaunchKernelGGL(k_scale_points, dim3((unsigned)L.ntmax, (unsigned)L.nc), dim3(256), 0, s, sa, c->d_cl, c->X, c->Xs,
-                     c->Xn, 0, 0);
+                     c->Xn, 0, 0, c->build_ctr, (int)gd.x, (int)gc.x);
   hipLaunchKernelGGL(k_scale_points, dim3((unsigned)(L.ldc / TILE), 1u), dim3(256), 0, s, sa,
-                     (const ClusterInfo*)nullptr, c->reps, c->Rs, c->Rn, L.ncr, L.ldc);
-  const dim3 gd((unsigned)c->n_pan_diag), gc((unsigned)c->n_pan_c), blk(256);
+                     (const ClusterInfo*)nullptr, c->reps, c->Rs, c->Rn, L.ncr, L.ldc, (int*)nullptr, 0, 0);
+  const size_t lds = (size_t)4 * a.kd * 16 * sizeof(double);      // row operands of one item
 #define NUGPR_PANELS(NKS)                                                                                          \
   do {                                                                                                             \
-    hipLaunchKernelGGL((k_build_panel<false, NKS>), gd, blk, 0, s, a, c->d_cl, c->d_pan_diag, c->Xs, c->Xn, c->Kd, \
-                       0, 1, 0u);                                                                                  \
-    hipLaunchKernelGGL((k_build_panel<true, NKS>), gc, blk, 0, s, a, c->d_cl, c->d_pan_c, c->Rs, c->Rn, c->C,      \
-                       L.ncr, L.r, (uint32_t)L.ldc);                                                               \
+    hipLaunchKernelGGL((k_build_panel<false, NKS>), gd, blk, lds, s, a, c->d_pan_diag, c->Xs, c->Xn, c->Kd,          \
+                       c->n_pan_diag, 1, c->build_ctr);                                                                                  \
+    hipLaunchKernelGGL((k_build_panel<true, NKS>), gc, blk, lds, s, a, c->d_pan_c, c->Rs, c->Rn, c->C,               \
+                       c->n_pan_c, L.r, c->build_ctr + 1);                                                               \
   } while (0)
   switch (a.kd / 4) {        // the dimensions of the usual workloads get their own instantiation
     case 1: NUGPR_PANELS(1); break;

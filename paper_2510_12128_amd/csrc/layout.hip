@@ -103,6 +103,7 @@ int plan_layout(const nugpr_problem* pb, uint32_t flags, Layout& L) {
     L.o_Xn = take(cur, (size_t)L.rows_pad * sizeof(double));
     L.o_Rs = take(cur, (size_t)L.ldc * kd * sizeof(double));
     L.o_Rn = take(cur, (size_t)L.ldc * sizeof(double));
+    L.o_bctr = take(cur, 2 * sizeof(int));
   }
   L.o_B = take(cur, vec);
   L.o_X = take(cur, vec);
@@ -120,7 +121,8 @@ int plan_layout(const nugpr_problem* pb, uint32_t flags, Layout& L) {
   L.o_blog = take(cur, (size_t)L.max_iter * MAX_COLS * sizeof(double));
   L.o_logdet = take(cur, (size_t)L.nc * sizeof(double));
   // tile list of the diagonal blocks (mirroring) + row-panel work items of the two assembly launches
-  L.o_tiles = take(cur, (2 * L.n_diag_tiles + L.n_c_tiles) * sizeof(uint64_t));
+  // tile list of the diagonal blocks + the assembly work items (32 bytes each, at most one per tile)
+  L.o_tiles = take(cur, (5 * L.n_diag_tiles + 4 * L.n_c_tiles) * sizeof(uint64_t));
   // strip tables: exact item counts
   size_t items = 0;
   for (auto& c : L.cl) {

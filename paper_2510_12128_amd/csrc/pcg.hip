@@ -193,6 +193,15 @@ __global__ void k_copy_flags(PcgState* __restrict__ st, HostFlags* __restrict__ 
   out->bad_cluster = st->bad_cluster;
 }
 
+// start of a solve: X = 0, R = B, and the alpha / beta logs cleared
+template <typename VT>
+__global__ void k_pcg_init(VT* __restrict__ X, VT* __restrict__ R, const VT* __restrict__ B, int64_t count,
+                           double* __restrict__ alog, double* __restrict__ blog, int64_t nlog) {
+  const int64_t i0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = i0; i < count; i += stride) { X[i] = (VT)0; R[i] = B[i]; }
+  for (int64_t i = i0; i < nlog; i += stride) { alog[i] = 0.0; blog[i] = 0.0; }
+}
+
 template <typename SRC, typename DST>
 __global__ void k_convert(const SRC* __restrict__ src, DST* __restrict__ dst, int64_t count) {
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x)
@@ -293,20 +302,21 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
   const int max_iter = c->params.max_iter;
   int rc;
   VT *R = (VT*)c->Rv, *Z = (VT*)c->Zv, *D = (VT*)c->Dv, *Q = (VT*)c->Qv;
-  NUGPR_HIP(hipMemsetAsync(X, 0, bytes, s));
-  NUGPR_HIP(hipMemcpyAsync(R, B, bytes, hipMemcpyDeviceToDevice, s));
-  NUGPR_HIP(hipMemsetAsync(c->alog, 0, (size_t)max_iter * MAX_COLS * sizeof(double), s));
-  NUGPR_HIP(hipMemsetAsync(c->blog, 0, (size_t)max_iter * MAX_COLS * sizeof(double), s));
-  if ((rc = run_precond(c, R, Z, T, s))) return rc;
-  NUGPR_HIP(hipMemcpyAsync(D, Z, bytes, hipMemcpyDeviceToDevice, s));
-  hipLaunchKernelGGL((k_dot<2, VT>), dim3(nb), dim3(256), 0, s, R, R, R, Z, n, T, c->dotpart);
+  (void)bytes;
+  // x_0 = 0, r_0 = B, cleared coefficient logs: one launch
+  hipLaunchKernelGGL((k_pcg_init<VT>), dim3(1024), dim3(256), 0, s, X, R, B, n * T, c->alog, c->blog,
+                     (int64_t)max_iter * MAX_COLS);
+  // d_0 = z_0 = M^-1 r_0, written straight into D
+  if ((rc = run_precond(c, R, D, T, s))) return rc;
+  hipLaunchKernelGGL((k_dot<2, VT>), dim3(nb), dim3(256), 0, s, R, R, R, D, n, T, c->dotpart);
   hipLaunchKernelGGL(k_pcg_begin, dim3(T), dim3(256), 0, s, c->d_state, c->dotpart, nb);
   NUGPR_HIP(hipGetLastError());
   int it = 0;
   bool indefinite = false;
+  // The first iteration is issued without asking the device whether any column is active: columns
+  // that start inactive (zero right-hand side) are skipped by every kernel on their own flag, and
+  // the host learns the count at the first stop test.
   c->h_flags->n_active = 1;
-  hipLaunchKernelGGL(k_copy_flags, dim3(1), dim3(1), 0, s, c->d_state, c->h_flags, T);
-  NUGPR_HIP(hipStreamSynchronize(s));
   while (it < max_iter && c->h_flags->n_active > 0) {
     if ((rc = run_matvec(c, D, Q, T, s))) return rc;
     hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, D, Q, D, Q, n, T, c->dotpart);
@@ -328,8 +338,14 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
     NUGPR_HIP(hipGetLastError());
   }
   // per-column records
-  PcgState* hs = reinterpret_cast<PcgState*>(c->h_buf);
+  // per-column records and (if asked for) the coefficient logs: one synchronisation for all of them
+  const size_t cnt = (size_t)max_iter * MAX_COLS;
+  PcgState* hs = reinterpret_cast<PcgState*>(c->h_buf + 2 * cnt);
   NUGPR_HIP(hipMemcpyAsync(hs, c->d_state, sizeof(PcgState), hipMemcpyDeviceToHost, s));
+  if (alpha || beta) {
+    NUGPR_HIP(hipMemcpyAsync(c->h_buf, c->alog, cnt * sizeof(double), hipMemcpyDeviceToHost, s));
+    NUGPR_HIP(hipMemcpyAsync(c->h_buf + cnt, c->blog, cnt * sizeof(double), hipMemcpyDeviceToHost, s));
+  }
   NUGPR_HIP(hipStreamSynchronize(s));
   bool all_conv = true;
   int mx = 0;
@@ -341,11 +357,7 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
   }
   if (max_it_used) *max_it_used = mx;
   if (alpha || beta) {
-    double* ha = c->h_buf;
-    const size_t cnt = (size_t)max_iter * MAX_COLS;
-    NUGPR_HIP(hipMemcpyAsync(ha, c->alog, cnt * sizeof(double), hipMemcpyDeviceToHost, s));
-    NUGPR_HIP(hipMemcpyAsync(ha + cnt, c->blog, cnt * sizeof(double), hipMemcpyDeviceToHost, s));
-    NUGPR_HIP(hipStreamSynchronize(s));
+    const double* ha = c->h_buf;
     for (int j = 0; j < max_iter; ++j)
       for (int col = 0; col < T; ++col) {
         if (alpha) alpha[(size_t)j * T + col] = ha[(size_t)j * MAX_COLS + col];

@@ -289,6 +289,197 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   }
 }
 
+// ---------------------------------------------------------------------------
+// fp64 mode with T >= 2: producer / consumer version of the kernel above.
+//
+// A workgroup has FIVE waves.  Wave 4 only moves data: for every 64-column chunk it issues
+// LDS-direct loads (global_load_lds_dwordx4: memory -> LDS, no registers) of the 64 x 64 matrix
+// tile -- in exactly the per-lane order the consumers read it back, one 16-byte slot per lane
+// and step -- and of the chunk's contiguous (64 x T) slab of the vector block, into a ring of
+// STAGES buffers.  Waves 0..3 never touch global memory inside the loop: they read their
+// slots and the vector rows from LDS and run the same arithmetic as k_strip.  One workgroup
+// barrier per chunk hands a filled stage to the consumers and a drained one back to the
+// loader, which keeps STAGES - 1 chunks (about 50 KB per workgroup) in flight however long
+// the matrix cores are busy: the loads no longer wait for the wave that will use them.
+// Chunks with dropped elements (ragged end, diagonal tile) zero the matrix entries AND
+// the vector rows past the item's last column, so whatever follows a short slab in
+// memory never reaches the sums.
+// ---------------------------------------------------------------------------
+constexpr uint32_t waitcnt_vm(uint32_t n) {      // s_waitcnt immediate: vmcnt(n), the other counters unconstrained
+  return (n & 15u) | ((n >> 4) << 14) | 0x0F70u;
+}
+
+template <int NG, int RCH, int STAGES_>
+struct RingCfg {
+  static constexpr int NCOLM = 16 * NG;
+  static constexpr int NSLAB = (RCH * (NCOLM + 1) * 8 + 1023) / 1024;      // 1 KiB loads covering a slab of fp64
+  static constexpr int STAGES = STAGES_;
+  static constexpr int NSTEP = RCH / 16;                                   // 16-column steps per chunk
+  static constexpr int A_BYTES = RCH * 64 * 4;                             // 64 rows x RCH columns of fp32
+  static constexpr int STAGE_BYTES = A_BYTES + NSLAB * 1024;
+  static constexpr int LOADS = 4 * NSTEP + NSLAB;                                 // loader instructions per chunk
+  static constexpr int LDS_BYTES = STAGES * STAGE_BYTES + 512;             // + slack for reads of unused columns
+};
+
+template <int NG, int RCH, int STAGES_>
+__global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(2))) void k_strip_ring(const StripArgs a) {
+#if __HIP_DEVICE_COMPILE__
+  typedef RingCfg<NG, RCH, STAGES_> Cfg;
+  constexpr int NSTEP = Cfg::NSTEP;
+  constexpr int NCOLM = Cfg::NCOLM, STAGES = Cfg::STAGES;
+  extern __shared__ __attribute__((aligned(16))) unsigned char ring[];
+
+  const StripItem it = a.items[blockIdx.x];
+  const StripPort& pt = a.port[it.port];
+  const double* __restrict__ vin = static_cast<const double*>(pt.in);
+  const int T = a.T;
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+  const int m = lane & 15, kg = lane >> 4;
+  const int nrows = (int)it.nrows;
+  const int c_begin = (int)it.c_begin, c_end = (int)it.c_end;
+  const int nchunks = c_end > c_begin ? (c_end - c_begin + RCH - 1) / RCH : 0;
+
+  if (wave == 4) {
+    // ---- loader ----
+    // matrix: for consumer wave w and step s, lane (m, kg) fetches A[16 w + m][c + 16 s + 4 kg .. + 3]
+    // (rows past the strip's last one re-read it; the padded leading dimension keeps the columns in bounds)
+    const float* __restrict__ Ab = pt.A + it.a_off + 4 * kg;
+    uint64_t rowoff[4];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) rowoff[w] = (uint64_t)min(16 * w + m, nrows - 1) * (uint64_t)it.lda;
+    const unsigned char* __restrict__ vbytes = reinterpret_cast<const unsigned char*>(vin);
+    auto issue = [&](const int ch) {
+      const int c = c_begin + ch * RCH;
+      unsigned char* st = ring + (ch % STAGES) * Cfg::STAGE_BYTES;
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+#pragma unroll
+        for (int s = 0; s < NSTEP; ++s)
+          __builtin_amdgcn_global_load_lds(Ab + rowoff[w] + c + 16 * s, st + (w * NSTEP + s) * 1024, 16, 0, 0);
+      // vector slab: rows in_row0 + c .., T columns, contiguous; 16-byte pieces past its last valid byte
+      // re-read the last valid piece (the consumers drop those rows)
+      const uint64_t slab0 = (uint64_t)(it.in_row0 + (uint32_t)c) * (uint64_t)T * 8u;
+      const int valid = min(RCH, c_end - c) * T * 8;                    // > 0
+      const int last_piece = ((valid - 1) >> 4) << 4;
+#pragma unroll
+      for (int i = 0; i < Cfg::NSLAB; ++i) {
+        const int off = min((i * 64 + lane) * 16, last_piece);
+        __builtin_amdgcn_global_load_lds(vbytes + slab0 + off, st + Cfg::A_BYTES + i * 1024, 16, 0, 0);
+      }
+    };
+    for (int p = 0; p < STAGES - 1; ++p)
+      if (p < nchunks) issue(p);
+    for (int ch = 0; ch < nchunks; ++ch) {
+      // chunk ch must have landed; the chunks issued after it may still be in flight.  Near the end fewer
+      // chunks follow, so everything is waited for.
+      if (STAGES > 2 && ch + STAGES - 2 <= nchunks - 1) __builtin_amdgcn_s_waitcnt(waitcnt_vm((STAGES - 2) * Cfg::LOADS));
+      else __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+      __builtin_amdgcn_s_barrier();
+      // the consumers are done with chunk ch - 1: its stage takes chunk ch + STAGES - 1
+      if (ch + STAGES - 1 < nchunks) issue(ch + STAGES - 1);
+    }
+    return;
+  }
+
+  // ---- consumers ----
+  const int lr = wave * 16 + m;                               // local row of this lane's matrix slots
+  const int diag = (int)it.row_in_block + lr;
+  const int q_lo = it.mode == 2 ? diag : c_begin;
+  const int q_hi = it.mode == 1 ? (diag + 1 < c_end ? diag + 1 : c_end) : c_end;
+  const int rib = (int)it.row_in_block;
+
+  v4d acc64[NG][2];
+#pragma unroll
+  for (int g = 0; g < NG; ++g) {
+    acc64[g][0] = (v4d){0.0, 0.0, 0.0, 0.0};
+    acc64[g][1] = (v4d){0.0, 0.0, 0.0, 0.0};
+  }
+  double daccy = 0.0;
+
+  for (int ch = 0; ch < nchunks; ++ch) {
+    const int c = c_begin + ch * RCH;
+    __builtin_amdgcn_s_barrier();                             // chunk ch is in its stage
+    const unsigned char* st = ring + (ch % STAGES) * Cfg::STAGE_BYTES;
+    const float4* __restrict__ sAw = reinterpret_cast<const float4*>(st) + wave * (64 * NSTEP) + lane;
+    const double* __restrict__ sV = reinterpret_cast<const double*>(st + Cfg::A_BYTES);
+    // chunks that can hold dropped elements: past the last column, or touching the diagonal tile
+    const bool masked = c + RCH > c_end || (it.mode == 1 && c + RCH > rib) || (it.mode == 2 && c < rib + TILE);
+    const int kvalid = c_end - c;                             // vector rows of this chunk that exist
+#pragma unroll
+    for (int s = 0; s < NSTEP; ++s) {
+      float4 av = sAw[s * 64];
+      const int k0 = 16 * s + 4 * kg;                         // chunk-local column of av.x
+      const double* __restrict__ vr = sV + k0 * T;
+      double y[4], b[NG][4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        y[j] = vr[j * T];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) b[g][j] = vr[j * T + 1 + 16 * g + m];
+      }
+      if (masked) {
+        const int q0 = c + k0;
+        av.x = (q0 + 0 >= q_lo && q0 + 0 < q_hi) ? av.x : 0.f;
+        av.y = (q0 + 1 >= q_lo && q0 + 1 < q_hi) ? av.y : 0.f;
+        av.z = (q0 + 2 >= q_lo && q0 + 2 < q_hi) ? av.z : 0.f;
+        av.w = (q0 + 3 >= q_lo && q0 + 3 < q_hi) ? av.w : 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const bool ok = k0 + j < kvalid;
+          y[j] = ok ? y[j] : 0.0;
+#pragma unroll
+          for (int g = 0; g < NG; ++g) b[g][j] = ok ? b[g][j] : 0.0;
+        }
+      }
+      const double ax = (double)av.x, ay = (double)av.y, az = (double)av.z, aw = (double)av.w;
+#pragma unroll
+      for (int g = 0; g < NG; ++g) {
+        acc64[g][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(ax, b[g][0], acc64[g][0], 0, 0, 0);
+        acc64[g][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(ay, b[g][1], acc64[g][1], 0, 0, 0);
+        acc64[g][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(az, b[g][2], acc64[g][0], 0, 0, 0);
+        acc64[g][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(aw, b[g][3], acc64[g][1], 0, 0, 0);
+      }
+      daccy = fma(ax, y[0], daccy);
+      daccy = fma(ay, y[1], daccy);
+      daccy = fma(az, y[2], daccy);
+      daccy = fma(aw, y[3], daccy);
+    }
+    // every LDS read of this stage has returned before the barrier that lets the loader refill it
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  }
+
+  // ---- epilogue (as in k_strip) ----
+  double* __restrict__ out = static_cast<double*>(pt.out) + (uint64_t)it.out_part * pt.out_part_stride;
+  const double dadd = (double)it.diag_add * (double)pt.diag_add;
+  const bool add_diag = (dadd != 0.0);
+#pragma unroll
+  for (int g = 0; g < NG; ++g) {
+    const int col = 1 + 16 * g + m;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = wave * 16 + acc_row<true>(lane, i);
+      if (row < nrows && col < T) {
+        double v = acc64[g][0][i] + acc64[g][1][i];
+        if (add_diag) v = fma(dadd, vin[(uint64_t)(it.in_row0 + it.row_in_block + row) * T + col], v);
+        const uint64_t idx = (uint64_t)(it.out_row0 + row) * T + col;
+        if (pt.accumulate) v += out[idx];
+        out[idx] = v;
+      }
+    }
+  }
+  daccy += __shfl_xor(daccy, 16);
+  daccy += __shfl_xor(daccy, 32);
+  if (kg == 0 && lr < nrows) {
+    double v = daccy;
+    if (add_diag) v = fma(dadd, vin[(uint64_t)(it.in_row0 + it.row_in_block + lr) * T], v);
+    const uint64_t idx = (uint64_t)(it.out_row0 + lr) * T;
+    if (pt.accumulate) v += out[idx];
+    out[idx] = v;
+  }
+#endif
+}
+
 // out[i] = sum over `parts` slabs of in[part * stride + i]  (fixed order: deterministic)
 template <typename VT>
 __global__ void k_sum_parts(const VT* __restrict__ in, VT* __restrict__ out, int64_t count, int parts,
@@ -313,6 +504,10 @@ int launch_sum_parts(const void* in, void* out, int64_t count, int parts, uint64
   return NUGPR_OK;
 }
 
+constexpr int RING1_CH = 32, RING1_ST = 4, RING2_CH = 32, RING2_ST = 3;     // chunk columns and ring depth by column groups
+typedef RingCfg<1, RING1_CH, RING1_ST> Ring1;
+typedef RingCfg<2, RING2_CH, RING2_ST> Ring2;
+
 template <bool ACC64>
 static void launch_typed(int ng, dim3 grid, hipStream_t s, const StripArgs& a) {
   dim3 block(256);
@@ -332,7 +527,20 @@ int launch_strip(const StripTable& tab, const StripPort& p0, const StripPort& p1
   a.T = T;
   a.magicT = T == 1 ? 0u : (uint32_t)((1ull << 32) / (uint64_t)T + 1ull);
   const int ng = (T - 1 + 15) / 16;
-  if (acc64) launch_typed<true>(ng, dim3(tab.count), s, a);
+  // the ring kernels use more than the default 64 KiB of dynamic LDS: raise their limit once
+  static const hipError_t ring_attr = []() {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_strip_ring<1, RING1_CH, RING1_ST>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, Ring1::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_strip_ring<2, RING2_CH, RING2_ST>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, Ring2::LDS_BYTES);
+  }();
+  NUGPR_HIP(ring_attr);
+  if (acc64 && ng == 1)
+    hipLaunchKernelGGL((k_strip_ring<1, RING1_CH, RING1_ST>), dim3(tab.count), dim3(320), Ring1::LDS_BYTES, s, a);
+  else if (acc64 && ng == 2)
+    hipLaunchKernelGGL((k_strip_ring<2, RING2_CH, RING2_ST>), dim3(tab.count), dim3(320), Ring2::LDS_BYTES, s, a);
+  else if (acc64) launch_typed<true>(ng, dim3(tab.count), s, a);
   else launch_typed<false>(ng, dim3(tab.count), s, a);
   NUGPR_HIP(hipGetLastError());
   return NUGPR_OK;
