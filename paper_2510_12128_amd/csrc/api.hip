@@ -40,6 +40,40 @@ void sort_longest_first(std::vector<StripItem>& v) {
   });
 }
 
+// Workgroups are handed to the 8 accelerator dies (XCDs, each with its own L2) round-robin by
+// workgroup index.  Items that read the same rows of the vector block (the strips of one cluster,
+// the row strips of one column slab of C) are therefore placed 8 apart, so that they run on ONE die
+// and the slab is fetched from HBM once instead of once per die.  Inside a die's queue the order
+// (longest first) is kept.
+constexpr int NUM_XCD = 8;
+void arrange_for_dies(std::vector<StripItem>& v) {
+  if (v.size() < 2 * NUM_XCD) return;
+  std::vector<std::vector<StripItem>> q(NUM_XCD);
+  std::vector<uint64_t> keys;
+  for (const StripItem& it : v) {
+    const uint64_t key = ((uint64_t)it.port << 62) | ((uint64_t)it.in_row0 << 30) | (uint64_t)(it.c_begin & 0x3fffffffu);
+    size_t g = 0;
+    // groups are few (clusters + column slabs): a linear search over the last ones seen is enough
+    for (g = keys.size(); g > 0 && keys[g - 1] != key; --g) {}
+    if (g == 0) { keys.push_back(key); g = keys.size(); }
+    q[(g - 1) % NUM_XCD].push_back(it);
+  }
+  std::vector<size_t> pos(NUM_XCD, 0);
+  std::vector<StripItem> out;
+  out.reserve(v.size());
+  while (out.size() < v.size()) {
+    const int die = (int)(out.size() % NUM_XCD);
+    int src = die;
+    if (pos[src] >= q[src].size()) {          // this die's queue is empty: take from the fullest one
+      size_t best = 0;
+      for (int k = 0; k < NUM_XCD; ++k)
+        if (q[k].size() - pos[k] > best) { best = q[k].size() - pos[k]; src = k; }
+    }
+    out.push_back(q[src][pos[src]++]);
+  }
+  v.swap(out);
+}
+
 struct Tables {
   std::vector<StripItem> WtD, KC, WP, lowG, upG, lowL;
 };
@@ -88,6 +122,10 @@ void build_tables(const Layout& L, Tables& t) {
   sort_longest_first(t.lowG);
   sort_longest_first(t.upG);
   sort_longest_first(t.lowL);
+  arrange_for_dies(t.KC);
+  arrange_for_dies(t.lowG);
+  arrange_for_dies(t.upG);
+  arrange_for_dies(t.lowL);
 }
 
 int upload_table(const std::vector<StripItem>& v, StripItem*& cursor, StripTable& tab, hipStream_t s) {
@@ -138,13 +176,6 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   c->L = L;
   c->params = *prm;
   c->acc64 = (prm->flags & NUGPR_ACC_FP32) == 0;
-  {
-    // the assembly launches run as persistent workgroups, two per compute unit of the current device
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
-      c->build_grid = 2 * cus;
-  }
   if (c->params.beta1 == 0.0) c->params.beta1 = 0.9;
   if (c->params.beta2 == 0.0) c->params.beta2 = 0.999;
   if (c->params.eps == 0.0) c->params.eps = 1e-8;
@@ -163,7 +194,6 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   c->Xn = reinterpret_cast<double*>(w + L.o_Xn);
   c->Rs = reinterpret_cast<double*>(w + L.o_Rs);
   c->Rn = reinterpret_cast<double*>(w + L.o_Rn);
-  c->build_ctr = reinterpret_cast<int*>(w + L.o_bctr);
   c->Bv = w + L.o_B;
   c->Xv = w + L.o_X;
   c->Rv = w + L.o_R;

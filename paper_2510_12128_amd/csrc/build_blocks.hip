@@ -19,12 +19,11 @@
 //   k_scale_points  writes the scaled coordinates once, in fp64, in the order the matrix
 //                   cores read their operands (groups of 16 points, coordinate-major inside a
 //                   group), and the squared norms;
-//   k_build_panel   one work item = a run of 64 x 64 tiles of one tile row.  Each wave owns a
-//                   16-column slice of every tile and works on its own: operands come
-//                   straight from the scaled array (512-byte contiguous loads, served by
-//                   L2), the result is transposed through a wave-private LDS staging area
-//                   and written twice (the tile and its mirror image) with 16-byte stores.
-//                   No workgroup barrier inside the tile loop.
+//   k_build_tile    one workgroup = one 64 x 64 tile of a lower triangle.  Each wave owns a
+//                   16-column slice: operands come from the scaled array (512-byte contiguous
+//                   loads, served by L2), the mirror image is stored straight from registers
+//                   and the tile itself through a wave-private LDS staging area, both with
+//                   16-byte stores.
 #include <algorithm>
 #include <cmath>
 #include <type_traits>
@@ -51,11 +50,7 @@ __host__ __device__ inline int pair_kd(int d) { return (d + 3) & ~3; }
 // written as zeros.  grid.y = cluster (or 0 for the representatives), 64 points per block.
 __global__ __launch_bounds__(256) void k_scale_points(const ScaleArgs a, const ClusterInfo* __restrict__ cl,
                                                       const float* __restrict__ P, double* __restrict__ S,
-                                                      double* __restrict__ N, int single_total, int single_ld,
-                                                      int* __restrict__ counters, int start0, int start1) {
-  // first launch of an assembly: the work counters of the two panel launches that follow start
-  // after the items their workgroups take by index
-  if (counters && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) { counters[0] = start0; counters[1] = start1; }
+                                                      double* __restrict__ N, int single_total, int single_ld) {
   uint32_t first, total, ld, prow;
   if (cl) {
     const ClusterInfo c = cl[blockIdx.y];
@@ -86,7 +81,6 @@ struct PanelArgs {
 };
 
 constexpr int ST_LD = 20;            // row stride of the staging area (floats): rows stay 16-byte aligned
-constexpr int MAX_ITEM_TILES = 32;   // tiles per work item
 
 // alpha * 2^(-a) for a >= 0 (up to rounding), rounded once to fp32.
 // a = n + r with n = rint(a) by the 1.5 * 2^52 trick (n also lands in the low word of the
@@ -115,110 +109,91 @@ __device__ __forceinline__ float kernel_value(double a, double alpha) {
   return (float)(alpha * scaled);
 }
 
-// One work item = tile row `tr` of one square symmetric matrix (a cluster's K_ii, or the
-// coupling C) and the run of tile columns tc0..tc1-1 (<= tr).
-// item = cluster << 48 | tr << 32 | tc0 << 16 | tc1.
+// One workgroup = one 64 x 64 tile (tr, tc), tc <= tr, of one square symmetric matrix (a cluster's
+// K_ii, or the coupling C) and its mirror image.
 //
-// Wave w computes columns 16 w .. 16 w + 15 of every tile with four 16 x 16 fp64 MFMA
-// accumulators (one per 16-row group); the row operands of the item sit in LDS, the
-// column operands of the tiles ahead in two register sets.  The rows of a group are fed to
-// the matrix cores in the order 0,4,8,12,1,5,.. so that a lane ends up with FOUR CONSECUTIVE
-// rows of one column: that is a 16-byte piece of the mirror image, stored straight from
-// registers.  The tile itself needs the other orientation and goes through a wave-private
-// LDS staging area (16-byte reads and stores).  The eight stores of a tile are issued one
-// after every second entry, each LDS read one row group ahead of its store.
+// Wave w computes columns 16 w .. 16 w + 15 with four 16 x 16 fp64 MFMA accumulators (one per
+// 16-row group); the row operands of the tile are shared through LDS, the column operands go
+// straight into registers.  The rows of a group are fed to the matrix cores in the order
+// 0,4,8,12,1,5,.. so that a lane ends up with FOUR CONSECUTIVE rows of one column: that is a
+// 16-byte piece of the mirror image, stored straight from registers.  The tile itself needs the
+// other orientation and goes through a wave-private LDS staging area (16-byte reads and stores).
 //
-// On this chip the fp64 matrix instructions run at the rate of the vector ALU and do not
-// overlap with it, so the kernel is bound by its instruction count: the exponential uses
-// full-rate instructions only, and the masks run on the tiles that need them.
-// NKS = kd / 4 when positive (operands prefetched); NKS = 0 handles any kd and reads the
-// column operands of a tile when it needs them.
+// Why one tile per workgroup and nothing cleverer: on this chip the fp64 matrix instructions run
+// at the rate of the vector ALU and do not overlap with it, and a wave that alternates arithmetic
+// with bursts of stores stalls on the store path; long-lived workgroups that walk along a tile row
+// measured 30 % slower than the sum of their parts.  Short workgroups leave the overlap to the
+// hardware: while some wait for operands or drain their stores, others compute (three to four fit
+// on a compute unit).  Consecutive workgroups take neighbouring tiles of a row, so the row
+// operands they share stay in L2.  The exponential uses full-rate instructions only, and the masks
+// run on the tiles that need them.
+// NKS = kd / 4 when positive; NKS = 0 handles any kd with a loop over the coordinate groups.
 template <bool COUPLING, int NKS>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
-void k_build_panel(const PanelArgs a, const BuildItem* __restrict__ items, const double* __restrict__ S,
-                   const double* __restrict__ N, float* __restrict__ out_base, int n_items, int r,
-                   int* __restrict__ counter) {
+void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const double* __restrict__ S,
+                  const double* __restrict__ N, float* __restrict__ out_base, int r) {
   extern __shared__ __attribute__((aligned(16))) double sA[];      // 4 * kd * 16 doubles: row operands
   __shared__ double sNr[TILE];
-  __shared__ double sNc[MAX_ITEM_TILES * TILE];                    // column norms of every tile of the item
   __shared__ __attribute__((aligned(16))) float sT[4][TILE * ST_LD];
 
-  // Persistent workgroups: the first item is the workgroup's own index, the following ones come from a
-  // shared counter (the items differ in length and the tiles in cost).  Thread 0 draws the next index and
-  // fetches its descriptor into LDS while the current item is worked on; the barrier that ends the item
-  // publishes it, so an item starts with ONE round trip to memory (its operands).
-  __shared__ BuildItem s_item[2];
-  __shared__ int s_index[2];
-  if (threadIdx.x == 0) {
-    s_index[0] = (int)blockIdx.x;
-    if ((int)blockIdx.x < n_items) s_item[0] = items[blockIdx.x];
-  }
-  __syncthreads();
-  for (int slot = 0; s_index[slot] < n_items; slot ^= 1) {
-  const BuildItem cur = s_item[slot];
-  int next_index = 0;
-  if (threadIdx.x == 0) next_index = atomicAdd(counter, 1);
-  const int tr = cur.tr, tc0 = cur.tc0, tc1 = cur.tc1;
+  const BuildItem cur = items[blockIdx.x];
+  const int tr = cur.tr, tc = cur.tc0;
   const int total = (int)cur.total;
   const uint32_t ld = cur.ld, prow = cur.prow;
   float* __restrict__ out = out_base + cur.out_off;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int m = lane & 15, kk = lane >> 4;
   const int kd = a.kd, nks = NKS > 0 ? NKS : kd / 4;
-  const int p0 = tr * TILE;
+  const int p0 = tr * TILE, q0 = tc * TILE;
   const uint64_t gstride = (uint64_t)kd * 16;                 // doubles per group of 16 points
   const int lofs = kk * 16 + m;                               // this lane's element of a 4-coordinate step
   // row operand: matrix row m of a group carries point 4 (m % 4) + m / 4, so accumulator
   // component i of lane (kk, m) is point 4 kk + i of the group, column m
   const int aofs = kk * 16 + 4 * (m & 3) + (m >> 2);
 
-  constexpr int NA = NKS > 0 ? NKS : 1;
-  // Column operands of two tiles ahead live in two register sets: a load is issued before
-  // the stores that follow it in program order, and the outstanding-operation counter retires
-  // in order, so waiting for operands never waits for the stores of the last two tiles.
-  double bv[2][NA];
-  auto load_cols = [&](auto set_c, int tc) {
-    constexpr int SET = decltype(set_c)::value;
-    const uint32_t q = prow + (uint32_t)tc * TILE + 16 * wave;
-    const double* __restrict__ Sc = S + (uint64_t)(q >> 4) * gstride + lofs;
-    if (NKS > 0) {
+  // every load of the tile is issued before the first wait: one round trip to memory
+  constexpr int NB = NKS > 0 ? NKS : 1;
+  const uint32_t qg = prow + (uint32_t)q0 + 16 * wave;         // first of this wave's 16 column points
+  const double* __restrict__ Sc = S + (uint64_t)(qg >> 4) * gstride + lofs;
+  double bv[NB];
+  if (NKS > 0) {
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) bv[SET][ks] = Sc[ks * 64];
-    }
-  };
-  typedef std::integral_constant<int, 0> Set0;
-  typedef std::integral_constant<int, 1> Set1;
-  const int tc_last = tc1 - 1;                // prefetches past the item re-read its last tile
-  load_cols(Set0(), tc0);
-  load_cols(Set1(), min(tc0 + 1, tc_last));
-  // (the loads above are in flight while the shared operands are fetched: one round trip in all)
+    for (int ks = 0; ks < NKS; ++ks) bv[ks] = Sc[ks * 64];
+  }
+  const double nc = N[qg + m];
   {
-    // all loads first, then the LDS writes: one round trip, not one per loop iteration
-    constexpr int NCN = MAX_ITEM_TILES * TILE / 256;            // column norms per thread
     constexpr int NCA = NKS > 0 ? NKS : MAX_D / 4;              // row operand elements per thread (4 kd 16 / 256)
-    const double* __restrict__ Nc = N + prow + (uint32_t)tc0 * TILE;
     const double* __restrict__ Sg = S + (uint64_t)((prow + p0) >> 4) * gstride;
-    const int n_nc = (tc1 - tc0) * TILE, n_a = 4 * (int)gstride;
-    double rn[NCN], ra[NCA];
+    const int n_a = 4 * (int)gstride;
+    double ra[NCA];
     const double rr = N[prow + p0 + (tid & (TILE - 1))];
-#pragma unroll
-    for (int j = 0; j < NCN; ++j) rn[j] = Nc[min(tid + 256 * j, n_nc - 1)];
 #pragma unroll
     for (int j = 0; j < NCA; ++j) ra[j] = Sg[min(tid + 256 * j, n_a - 1)];
     if (tid < TILE) sNr[tid] = rr;
-#pragma unroll
-    for (int j = 0; j < NCN; ++j)
-      if (tid + 256 * j < n_nc) sNc[tid + 256 * j] = rn[j];
-    // the row operands of the item (4 groups x kd coordinates x 16 points, already in operand order)
+    // the row operands (4 groups x kd coordinates x 16 points, already in operand order)
 #pragma unroll
     for (int j = 0; j < NCA; ++j)
       if (tid + 256 * j < n_a) sA[tid + 256 * j] = ra[j];
   }
   __syncthreads();
 
-  // nothing is outstanding when the loop is entered: the compiler's count of outstanding
-  // operations at the loop head is the minimum over the ways in, and must not be the prologue's
-  __builtin_amdgcn_s_waitcnt(0x0F70);         // vmcnt(0)
+  v4d acc[4];
+#pragma unroll
+  for (int ti = 0; ti < 4; ++ti) acc[ti] = (v4d){0.0, 0.0, 0.0, 0.0};
+  if (NKS > 0) {
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+      for (int ti = 0; ti < 4; ++ti)
+        acc[ti] = __builtin_amdgcn_mfma_f64_16x16x4f64(sA[(ti * NKS + ks) * 64 + aofs], bv[ks], acc[ti], 0, 0, 0);
+  } else {
+    for (int ks = 0; ks < nks; ++ks) {
+      const double b = Sc[ks * 64];
+#pragma unroll
+      for (int ti = 0; ti < 4; ++ti)
+        acc[ti] = __builtin_amdgcn_mfma_f64_16x16x4f64(sA[(ti * nks + ks) * 64 + aofs], b, acc[ti], 0, 0, 0);
+    }
+  }
 
   const float dv = a.diag_val;
   const double alpha = a.alpha;
@@ -228,17 +203,16 @@ void k_build_panel(const PanelArgs a, const BuildItem* __restrict__ items, const
   float* __restrict__ st_w = sTw + (4 * kk) * ST_LD + m;
   const float4* __restrict__ st_r = reinterpret_cast<const float4*>(sTw + (lane >> 2) * ST_LD + 4 * (lane & 3));
   const uint64_t ld64 = ld;
+  const int q = q0 + 16 * wave + m;
+  // the tile itself: rows p0 + 16 k + lane / 4, this wave's 16 columns (64 bytes a row)
+  float* __restrict__ od = out + (uint64_t)(p0 + (lane >> 2)) * ld64 + q0 + 16 * wave + 4 * (lane & 3);
+  // its mirror image: row q, columns p0 + 16 ti + 4 kk .. + 3; a tile on the diagonal is its own mirror
+  // image, entry for entry, and is simply written twice
+  float* __restrict__ om = out + (uint64_t)q * ld64 + p0 + 4 * kk;
 
-  // the sixteen entries of a tile: masked (EDGE) or not
-  auto entries = [&](auto edge_c, const v4d (&acc)[4], const double nc, const int q0) {
+  // the sixteen entries of this lane: masked (EDGE) or not
+  auto entries = [&](auto edge_c) {
     constexpr bool EDGE = decltype(edge_c)::value;
-    const int q = q0 + 16 * wave + m;
-    // the tile itself: rows p0 + 16 k + lane / 4, this wave's 16 columns (64 bytes a row)
-    float* __restrict__ od = out + (uint64_t)(p0 + (lane >> 2)) * ld64 + q0 + 16 * wave + 4 * (lane & 3);
-    // its mirror image: row q, columns p0 + 16 ti + 4 kk .. + 3; a tile on the diagonal is its own mirror
-    // image, entry for entry, and is simply written twice
-    float* __restrict__ om = out + (uint64_t)q * ld64 + p0 + 4 * kk;
-    float4 pending;
 #pragma unroll
     for (int ti = 0; ti < 4; ++ti) {
       float x[4];
@@ -260,66 +234,21 @@ void k_build_panel(const PanelArgs a, const BuildItem* __restrict__ items, const
           }
         }
         st_w[(16 * ti + i) * ST_LD] = x[i];
-        if (i == 1) {
-          // rows of the previous group: read a group ago, stored now
-          if (ti > 0) *reinterpret_cast<float4*>(od + (uint64_t)(16 * (ti - 1)) * ld64) = pending;
-          __builtin_amdgcn_sched_barrier(0);
-        }
       }
       *reinterpret_cast<float4*>(om + 16 * ti) = make_float4(x[0], x[1], x[2], x[3]);
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      pending = st_r[ti * (16 * ST_LD / 4)];
-      __builtin_amdgcn_sched_barrier(0);
     }
-    *reinterpret_cast<float4*>(od + (uint64_t)48 * ld64) = pending;
   };
-
-  // One tile with the operands of register set SET.
-  auto tile = [&](auto set_c, const int tc) {
-    constexpr int SET = decltype(set_c)::value;
-    const int q0 = tc * TILE;
-    v4d acc[4];
+  // tiles that can hold dropped or replaced entries: on the diagonal, at the ragged end, or (coupling)
+  // overlapping a same-cluster block of r x r representatives (q0 <= p0)
+  const bool edge = tr == tc || p0 + TILE > total || q0 + TILE > total ||
+                    (COUPLING && (q0 + TILE - 1) / r >= p0 / r);
+  if (edge) entries(std::true_type());
+  else entries(std::false_type());
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
-    for (int ti = 0; ti < 4; ++ti) acc[ti] = (v4d){0.0, 0.0, 0.0, 0.0};
-    if (NKS > 0) {
-#pragma unroll
-      for (int ks = 0; ks < NKS; ++ks)
-#pragma unroll
-        for (int ti = 0; ti < 4; ++ti)
-          acc[ti] = __builtin_amdgcn_mfma_f64_16x16x4f64(sA[(ti * NKS + ks) * 64 + aofs], bv[SET][ks], acc[ti], 0, 0,
-                                                         0);
-    } else {
-      const double* __restrict__ Sc = S + (uint64_t)((prow + (uint32_t)q0 + 16 * wave) >> 4) * gstride + lofs;
-      for (int ks = 0; ks < nks; ++ks) {
-        const double b = Sc[ks * 64];
-#pragma unroll
-        for (int ti = 0; ti < 4; ++ti)
-          acc[ti] = __builtin_amdgcn_mfma_f64_16x16x4f64(sA[(ti * nks + ks) * 64 + aofs], b, acc[ti], 0, 0, 0);
-      }
-    }
-    const double nc = sNc[(tc - tc0) * TILE + 16 * wave + m];
-    load_cols(set_c, min(tc + 2, tc_last));
-    // tiles that can hold dropped or replaced entries: on the diagonal, at the ragged end, or (coupling)
-    // overlapping a same-cluster block of r x r representatives (q0 <= p0 inside an item)
-    const bool edge = tr == tc || p0 + TILE > total || q0 + TILE > total ||
-                      (COUPLING && (q0 + TILE - 1) / r >= p0 / r);
-    if (edge) entries(std::true_type(), acc, nc, q0);
-    else entries(std::false_type(), acc, nc, q0);
-  };
-  int tc = tc0;
-  for (; tc + 1 < tc1; tc += 2) {
-    tile(Set0(), tc);
-    tile(Set1(), tc + 1);
-  }
-  if (tc < tc1) tile(Set0(), tc);
-  if (threadIdx.x == 0) {
-    s_index[slot ^ 1] = next_index;
-    if (next_index < n_items) s_item[slot ^ 1] = items[next_index];
-  }
-  __syncthreads();            // the next item refills the shared operands
-  }
+  for (int k = 0; k < 4; ++k) *reinterpret_cast<float4*>(od + (uint64_t)(16 * k) * ld64) = st_r[k * (16 * ST_LD / 4)];
 }
 
 // ---------------------------------------------------------------------------
@@ -397,34 +326,26 @@ __global__ void k_export(const ST* __restrict__ src, uint64_t lds, float* __rest
 int launch_setup(nugpr_ctx* c, const float* user_reps, const float* user_W, hipStream_t s) {
   const Layout& L = c->L;
   // tile list of the diagonal blocks (used when the inverse factor is mirrored) and the
-  // row-panel work items of the two assembly launches, longest first
+  // work items of the two assembly launches
   std::vector<uint64_t> tiles;
   tiles.reserve(L.n_diag_tiles);
   for (int i = 0; i < L.nc; ++i)
     for (uint32_t tr = 0; tr < L.cl[i].nt; ++tr)
       for (uint32_t tc = 0; tc <= tr; ++tc) tiles.push_back(((uint64_t)i << 32) | ((uint64_t)tr << 16) | tc);
-  constexpr uint32_t MAXT = MAX_ITEM_TILES;
+  // one assembly work item per tile of the lower triangles, neighbours along a tile row next to each other
   auto panel_items = [&](uint32_t nt, uint64_t out_off, uint32_t prow, uint32_t total, uint32_t ld,
                          std::vector<BuildItem>& v) {
     for (uint32_t tr = 0; tr < nt; ++tr)
-      for (uint32_t t0 = 0; t0 <= tr; t0 += MAXT) {
+      for (uint32_t tc = 0; tc <= tr; ++tc) {
         BuildItem b{};
         b.out_off = out_off; b.prow = prow; b.total = total; b.ld = ld;
-        b.tr = (uint16_t)tr; b.tc0 = (uint16_t)t0; b.tc1 = (uint16_t)std::min<uint32_t>(t0 + MAXT, tr + 1);
+        b.tr = (uint16_t)tr; b.tc0 = (uint16_t)tc; b.tc1 = (uint16_t)(tc + 1);
         v.push_back(b);
       }
-  };
-  // longest first: the kernel's persistent workgroups draw the items in this order
-  auto arrange = [&](std::vector<BuildItem>& v) {
-    std::stable_sort(v.begin(), v.end(), [](const BuildItem& x, const BuildItem& y) {
-      return (x.tc1 - x.tc0) > (y.tc1 - y.tc0);
-    });
   };
   std::vector<BuildItem> pd, pc;
   for (int i = 0; i < L.nc; ++i) panel_items(L.cl[i].nt, L.cl[i].koff, L.cl[i].prow, L.cl[i].b, L.cl[i].ld, pd);
   panel_items((uint32_t)(L.ldc / TILE), 0, 0, (uint32_t)L.ncr, (uint32_t)L.ldc, pc);
-  arrange(pd);
-  arrange(pc);
   c->n_pan_diag = (int)pd.size();
   c->n_pan_c = (int)pc.size();
   c->d_pan_diag = reinterpret_cast<BuildItem*>(c->d_tiles + tiles.size());
@@ -472,27 +393,24 @@ int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s) {
   a.diag_val = (float)(alpha + sigma2);
   a.kd = pair_kd(L.d);
   c->diag_residual = (float)((alpha + sigma2) - (double)a.diag_val);
-  // persistent workgroups, two per compute unit, drawing items from a counter
-  const dim3 gd((unsigned)std::min(c->n_pan_diag, c->build_grid)), gc((unsigned)std::min(c->n_pan_c, c->build_grid)), blk(256);
   hipLaunchKernelGGL(k_scale_points, dim3((unsigned)L.ntmax, (unsigned)L.nc), dim3(256), 0, s, sa, c->d_cl, c->X, c->Xs,
-                     c->Xn, 0, 0, c->build_ctr, (int)gd.x, (int)gc.x);
+                     c->Xn, 0, 0);
   hipLaunchKernelGGL(k_scale_points, dim3((unsigned)(L.ldc / TILE), 1u), dim3(256), 0, s, sa,
-                     (const ClusterInfo*)nullptr, c->reps, c->Rs, c->Rn, L.ncr, L.ldc, (int*)nullptr, 0, 0);
-  const size_t lds = (size_t)4 * a.kd * 16 * sizeof(double);      // row operands of one item
-#define NUGPR_PANELS(NKS)                                                                                          \
-  do {                                                                                                             \
-    hipLaunchKernelGGL((k_build_panel<false, NKS>), gd, blk, lds, s, a, c->d_pan_diag, c->Xs, c->Xn, c->Kd,          \
-                       c->n_pan_diag, 1, c->build_ctr);                                                                                  \
-    hipLaunchKernelGGL((k_build_panel<true, NKS>), gc, blk, lds, s, a, c->d_pan_c, c->Rs, c->Rn, c->C,               \
-                       c->n_pan_c, L.r, c->build_ctr + 1);                                                               \
+                     (const ClusterInfo*)nullptr, c->reps, c->Rs, c->Rn, L.ncr, L.ldc);
+  const dim3 gd((unsigned)c->n_pan_diag), gc((unsigned)c->n_pan_c), blk(256);
+  const size_t lds = (size_t)4 * a.kd * 16 * sizeof(double);      // row operands of one tile
+#define NUGPR_TILES(NKS)                                                                                         \
+  do {                                                                                                           \
+    hipLaunchKernelGGL((k_build_tile<false, NKS>), gd, blk, lds, s, a, c->d_pan_diag, c->Xs, c->Xn, c->Kd, 1);   \
+    hipLaunchKernelGGL((k_build_tile<true, NKS>), gc, blk, lds, s, a, c->d_pan_c, c->Rs, c->Rn, c->C, L.r);      \
   } while (0)
   switch (a.kd / 4) {        // the dimensions of the usual workloads get their own instantiation
-    case 1: NUGPR_PANELS(1); break;
-    case 2: NUGPR_PANELS(2); break;
-    case 5: NUGPR_PANELS(5); break;
-    default: NUGPR_PANELS(0); break;
+    case 1: NUGPR_TILES(1); break;
+    case 2: NUGPR_TILES(2); break;
+    case 5: NUGPR_TILES(5); break;
+    default: NUGPR_TILES(0); break;
   }
-#undef NUGPR_PANELS
+#undef NUGPR_TILES
   NUGPR_HIP(hipGetLastError());
   c->built = true;
   return NUGPR_OK;

@@ -103,7 +103,6 @@ int plan_layout(const nugpr_problem* pb, uint32_t flags, Layout& L) {
     L.o_Xn = take(cur, (size_t)L.rows_pad * sizeof(double));
     L.o_Rs = take(cur, (size_t)L.ldc * kd * sizeof(double));
     L.o_Rn = take(cur, (size_t)L.ldc * sizeof(double));
-    L.o_bctr = take(cur, 2 * sizeof(int));
   }
   L.o_B = take(cur, vec);
   L.o_X = take(cur, vec);

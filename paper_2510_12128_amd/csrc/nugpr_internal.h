@@ -30,9 +30,9 @@ struct ClusterInfo {
   uint32_t pad_;
 };
 
-// Work item of the block assembly: tile row `tr` of one square symmetric matrix (a cluster's
-// K_ii or the coupling C), tile columns tc0 .. tc1 - 1 (<= tr), with everything the kernel
-// needs to address it, so that no second dependent load follows the descriptor.
+// Work item of the block assembly: tile (tr, tc0) of the lower triangle of one square symmetric
+// matrix (a cluster's K_ii or the coupling C), with everything the kernel needs to address it, so
+// that no second dependent load follows the descriptor (tc1 = tc0 + 1).
 struct BuildItem {
   uint64_t out_off;   // element offset of the matrix in its buffer
   uint32_t prow;      // first row of the matrix in the padded row numbering of the scaled coordinates
@@ -129,7 +129,7 @@ struct Layout {
   size_t o_B = 0, o_X = 0, o_R = 0, o_Z = 0, o_D = 0, o_Q = 0, o_V = 0, o_U = 0;
   size_t o_Spart = 0, o_Ppart = 0, o_dot = 0, o_state = 0, o_alog = 0, o_blog = 0;
   size_t o_theta = 0, o_logdet = 0, o_tiles = 0, o_items = 0;
-  size_t o_Xs = 0, o_Xn = 0, o_Rs = 0, o_Rn = 0, o_bctr = 0;
+  size_t o_Xs = 0, o_Xn = 0, o_Rs = 0, o_Rn = 0;
   size_t items_bytes = 0;
   int n_dot_blocks = 0;
   int max_iter = 0;
@@ -163,8 +163,6 @@ struct nugpr_ctx {
   nugpr::BuildItem* d_pan_diag = nullptr;    // work items of the K_ii assembly
   nugpr::BuildItem* d_pan_c = nullptr;       // work items of the coupling assembly
   int n_pan_diag = 0, n_pan_c = 0;
-  int build_grid = 512;              // workgroups of an assembly launch (two per compute unit)
-  int* build_ctr = nullptr;          // work counters of the two assembly launches
   nugpr::StripTable tab_WtD, tab_KC, tab_WP, tab_lowG, tab_upG, tab_lowL;
   // optional event timing of the K_diag / C streaming launch
   bool prof_on = false;
