@@ -65,6 +65,12 @@ enum {
                                   accumulation (faster).  Default: fp64 vector blocks and fp64
                                   matrix-core accumulation over the same fp32 stored matrices, which
                                   keeps accumulation rounding out of the finite-difference gradient. */
+  ,
+  NUGPR_NO_SHORTCUTS = 4u      /* nugpr_train_step assembles the blocks anew for every loss evaluation.
+                                  Default: evaluations that differ from the assembled blocks only in the
+                                  output scale or the noise reuse them through the linear relations of
+                                  Section 3.3 (eqs. (linear2), (linear3)): the operator becomes
+                                  s K_0 + shift I with s = alpha / alpha_0. */
 };
 
 /* Problem description (Section 2.1 notation; Section 3.3 for representatives). */
@@ -95,7 +101,7 @@ typedef struct {
   double fd_step;      /* h of the central differences on log(theta)                   */
   double lr;           /* Adam learning rate (paper: 0.05)                             */
   double beta1, beta2, eps;  /* Adam moments / epsilon (0 selects 0.9, 0.999, 1e-8)    */
-  uint32_t flags;      /* NUGPR_ISOTROPIC | NUGPR_ACC_FP32, or 0                       */
+  uint32_t flags;      /* NUGPR_ISOTROPIC | NUGPR_ACC_FP32 | NUGPR_NO_SHORTCUTS, or 0   */
 } nugpr_params;
 
 /* Result of one loss evaluation, eq. (loss function): nll = (quad + logdet + n log 2pi)/2. */
@@ -168,7 +174,8 @@ int nugpr_mll(nugpr_ctx* ctx, const double* theta /*HOST*/, nugpr_mll_result* re
 /* One pass of Algorithm 1's loop body on phi = log(theta): assemble and factor at
  * theta_0 = exp(phi), base loss, central differences
  *   g_i = (L(phi + h e_i) - L(phi - h e_i)) / (2h)
- * all with the theta_0 preconditioner and the same probes, then a bias-corrected
+ * all with the theta_0 preconditioner and the same probes (the output-scale and noise
+ * differences on the theta_0 blocks, see NUGPR_NO_SHORTCUTS), then a bias-corrected
  * Adam update of phi.  log_theta, adam_m, adam_v: HOST, p entries, in/out
  * (p = d+2, or 3 with NUGPR_ISOTROPIC); *step in/out; *nll0 and grad (p) out. */
 int nugpr_train_step(nugpr_ctx* ctx, double* log_theta, double* adam_m, double* adam_v,

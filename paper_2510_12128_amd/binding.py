@@ -19,6 +19,7 @@ NUGPR_INDEFINITE = 2
 NUGPR_NOT_CONVERGED = 3
 NUGPR_ISOTROPIC = 1
 NUGPR_ACC_FP32 = 2
+NUGPR_NO_SHORTCUTS = 4
 
 EXPORT_K, EXPORT_L, EXPORT_LINV, EXPORT_C, EXPORT_W, EXPORT_B, EXPORT_REPS = range(7)
 
@@ -128,7 +129,7 @@ class Context:
     array; reps / W optional.  Methods mirror the C entry points one to one."""
 
     def __init__(self, X, y, offsets, probes, rank, tol=1e-6, max_iter=100, fd_step=1e-3, lr=0.05,
-                 isotropic=False, reps=None, W=None, device="cuda:0", acc_fp32=False):
+                 isotropic=False, reps=None, W=None, device="cuda:0", acc_fp32=False, no_shortcuts=False):
         import torch
         self.torch = torch
         self.lib = load_library()
@@ -164,7 +165,8 @@ class Context:
         pb.workspace = (base + 255) // 256 * 256
         pb.workspace_bytes = self.workspace_bytes
         pr = Params(tol=tol, max_iter=max_iter, fd_step=fd_step, lr=lr, beta1=0.0, beta2=0.0, eps=0.0,
-                    flags=(NUGPR_ISOTROPIC if isotropic else 0) | (NUGPR_ACC_FP32 if acc_fp32 else 0))
+                    flags=(NUGPR_ISOTROPIC if isotropic else 0) | (NUGPR_ACC_FP32 if acc_fp32 else 0)
+                    | (NUGPR_NO_SHORTCUTS if no_shortcuts else 0))
         self.params = pr
         self.max_iter = int(max_iter)
         h = C.c_void_p()

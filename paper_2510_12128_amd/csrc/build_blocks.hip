@@ -88,25 +88,43 @@ constexpr int ST_LD = 20;            // row stride of the staging area (floats):
 // |f ln 2| <= 0.347: relative error < 1e-11); the factor 2^-n is a subtraction in the
 // exponent field.  Arguments above 900 give 2^-900 alpha, which rounds to zero like the true
 // value does.  Only full-rate vector instructions are used.
-__device__ __forceinline__ float kernel_value(double a, double alpha) {
+// W values at a time, step by step across all of them: a dependent fp64 instruction can issue only
+// every other slot, so W independent chains keep the vector ALU busy where one leaves it half idle.
+template <int W>
+__device__ __forceinline__ void kernel_values(const double (&arg)[W], double alpha, float (&out)[W]) {
   constexpr double MAGIC = 6755399441055744.0;            // 1.5 * 2^52
   constexpr double L = 0.69314718055994530942;
-  a = fmin(a, 900.0);
-  const double big = a + MAGIC;
-  const double f = (big - MAGIC) - a;
-  double p = L * L * L * L * L * L * L * L * L / 362880.0;
-  p = fma(p, f, L * L * L * L * L * L * L * L / 40320.0);
-  p = fma(p, f, L * L * L * L * L * L * L / 5040.0);
-  p = fma(p, f, L * L * L * L * L * L / 720.0);
-  p = fma(p, f, L * L * L * L * L / 120.0);
-  p = fma(p, f, L * L * L * L / 24.0);
-  p = fma(p, f, L * L * L / 6.0);
-  p = fma(p, f, L * L / 2.0);
-  p = fma(p, f, L);
-  p = fma(p, f, 1.0);
-  const int n = __double2loint(big);
-  const double scaled = __hiloint2double(__double2hiint(p) - (n << 20), __double2loint(p));
-  return (float)(alpha * scaled);
+  double a[W], big[W], f[W], p[W];
+#pragma unroll
+  for (int j = 0; j < W; ++j) a[j] = fmin(arg[j], 900.0);
+#pragma unroll
+  for (int j = 0; j < W; ++j) big[j] = a[j] + MAGIC;
+#pragma unroll
+  for (int j = 0; j < W; ++j) f[j] = (big[j] - MAGIC) - a[j];
+#pragma unroll
+  for (int j = 0; j < W; ++j) p[j] = fma(L * L * L * L * L * L * L * L * L / 362880.0, f[j], L * L * L * L * L * L * L * L / 40320.0);
+#pragma unroll
+  for (int j = 0; j < W; ++j) p[j] = fma(p[j], f[j], L * L * L * L * L * L * L / 5040.0);
+#pragma unroll
+  for (int j = 0; j < W; ++j) p[j] = fma(p[j], f[j], L * L * L * L * L * L / 720.0);
+#pragma unroll
+  for (int j = 0; j < W; ++j) p[j] = fma(p[j], f[j], L * L * L * L * L / 120.0);
+#pragma unroll
+  for (int j = 0; j < W; ++j) p[j] = fma(p[j], f[j], L * L * L * L / 24.0);
+#pragma unroll
+  for (int j = 0; j < W; ++j) p[j] = fma(p[j], f[j], L * L * L / 6.0);
+#pragma unroll
+  for (int j = 0; j < W; ++j) p[j] = fma(p[j], f[j], L * L / 2.0);
+#pragma unroll
+  for (int j = 0; j < W; ++j) p[j] = fma(p[j], f[j], L);
+#pragma unroll
+  for (int j = 0; j < W; ++j) p[j] = fma(p[j], f[j], 1.0);
+#pragma unroll
+  for (int j = 0; j < W; ++j) {
+    const int n = __double2loint(big[j]);
+    const double scaled = __hiloint2double(__double2hiint(p[j]) - (n << 20), __double2loint(p[j]));
+    out[j] = (float)(alpha * scaled);
+  }
 }
 
 // One workgroup = one 64 x 64 tile (tr, tc), tc <= tr, of one square symmetric matrix (a cluster's
@@ -216,11 +234,13 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
 #pragma unroll
     for (int ti = 0; ti < 4; ++ti) {
       float x[4];
+      double arg[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) arg[i] = fma(-2.0, acc[ti][i], sNr[16 * ti + 4 * kk + i] + nc);
+      kernel_values<4>(arg, alpha, x);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int row = 16 * ti + 4 * kk + i;
-        const double arg = fma(-2.0, acc[ti][i], sNr[row] + nc);
-        x[i] = kernel_value(arg, alpha);
         if (EDGE) {
           const int p = p0 + row;
           bool keep = p < total && q < total;
@@ -412,6 +432,9 @@ int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s) {
   }
 #undef NUGPR_TILES
   NUGPR_HIP(hipGetLastError());
+  c->theta_built.assign(theta, theta + L.p);
+  c->op_scale = 1.0;
+  c->op_shift = (double)c->diag_residual;
   c->built = true;
   return NUGPR_OK;
 }

@@ -71,8 +71,8 @@ struct StripPort {
   uint64_t out_part_stride;  // elements between output slabs
   int32_t nin;
   int32_t accumulate;        // out += result instead of out = result
-  float diag_add;            // scalar added on the diagonal of items that ask for it
-  int32_t pad_;
+  double scale = 1.0;        // the product is multiplied by this before anything is added
+  double diag_add = 0.0;     // scalar added on the diagonal of items that ask for it
 };
 
 struct StripArgs {
@@ -171,7 +171,12 @@ struct nugpr_ctx {
   nugpr::HostFlags* h_flags = nullptr;   // pinned
   double* h_buf = nullptr;               // pinned scratch for small device->host reads
   size_t h_buf_doubles = 0;
-  float diag_residual = 0.f;             // (alpha + sigma^2) - float(alpha + sigma^2)
+  float diag_residual = 0.f;             // (alpha + sigma^2) - float(alpha + sigma^2) of the stored blocks
+  // The stored blocks K_0 were assembled at theta_built.  The operator applied by run_matvec is
+  //   op_scale * K_0 + op_shift * I  (shift on the diagonal blocks only; the coupling is scaled),
+  // which is the covariance at any theta with the same lengthscales (eqs. (linear2), (linear3)).
+  std::vector<double> theta_built;
+  double op_scale = 1.0, op_shift = 0.0;
   bool built = false, factored = false;
   double logdetM = 0.0;
 };

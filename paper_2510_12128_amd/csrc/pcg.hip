@@ -236,8 +236,8 @@ int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s) {
   if (L.nsS > 1 && (rc = launch_sum_parts(c->Spart, c->Spart, (int64_t)spart, L.nsS, spart, c->acc64, s))) return rc;
   // Q_i = K_ii D_i   and   P = C_offdiag S (column slabs), one launch
   StripPort k0{}, k1{};
-  k0.A = c->Kd; k0.in = D; k0.out = Q; k0.nin = 1; k0.diag_add = c->diag_residual;
-  k1.A = c->C; k1.in = c->Spart; k1.nin = 1; k1.out = c->Ppart; k1.out_part_stride = ppart;
+  k0.A = c->Kd; k0.in = D; k0.out = Q; k0.nin = 1; k0.scale = c->op_scale; k0.diag_add = c->op_shift;
+  k1.A = c->C; k1.in = c->Spart; k1.nin = 1; k1.out = c->Ppart; k1.out_part_stride = ppart; k1.scale = c->op_scale;
   const bool timed = c->prof_on && (size_t)(2 * c->prof_used + 1) < c->prof_ev.size();
   if (timed) NUGPR_HIP(hipEventRecord(c->prof_ev[2 * c->prof_used], s));
   if ((rc = launch_strip(c->tab_KC, k0, k1, T, c->acc64, s))) return rc;

@@ -259,8 +259,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 
   // ---- epilogue ----
   VT* __restrict__ out = static_cast<VT*>(pt.out) + (uint64_t)it.out_part * pt.out_part_stride;
-  const double dadd = (double)it.diag_add * (double)pt.diag_add;   // part of the diagonal fp32 cannot hold
+  const double dadd = (double)it.diag_add * pt.diag_add;   // diagonal shift (incl. the part of the diagonal fp32 cannot hold)
   const bool add_diag = (dadd != 0.0);
+  const double scale = pt.scale;
   if (NG > 0) {
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
@@ -269,7 +270,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
       for (int i = 0; i < 4; ++i) {
         const int row = wave * 16 + acc_row<ACC64>(lane, i);
         if (row < nrows && col < T) {
-          double v = ACC64 ? (acc64[g][0][i] + acc64[g][1][i]) : dacc[g][i];
+          double v = scale * (ACC64 ? (acc64[g][0][i] + acc64[g][1][i]) : dacc[g][i]);
           if (add_diag) v = fma(dadd, (double)vin[(uint64_t)(it.in_row0 + it.row_in_block + row) * T + col], v);
           const uint64_t idx = (uint64_t)(it.out_row0 + row) * T + col;
           if (pt.accumulate) v += (double)out[idx];
@@ -281,7 +282,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   daccy += __shfl_xor(daccy, 16);
   daccy += __shfl_xor(daccy, 32);
   if (kg == 0 && lr < nrows) {
-    double v = daccy;
+    double v = scale * daccy;
     if (add_diag) v = fma(dadd, (double)vin[(uint64_t)(it.in_row0 + it.row_in_block + lr) * T], v);
     const uint64_t idx = (uint64_t)(it.out_row0 + lr) * T;
     if (pt.accumulate) v += (double)out[idx];
@@ -451,8 +452,9 @@ __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(2))) void k
 
   // ---- epilogue (as in k_strip) ----
   double* __restrict__ out = static_cast<double*>(pt.out) + (uint64_t)it.out_part * pt.out_part_stride;
-  const double dadd = (double)it.diag_add * (double)pt.diag_add;
+  const double dadd = (double)it.diag_add * pt.diag_add;
   const bool add_diag = (dadd != 0.0);
+  const double scale = pt.scale;
 #pragma unroll
   for (int g = 0; g < NG; ++g) {
     const int col = 1 + 16 * g + m;
@@ -460,7 +462,7 @@ __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(2))) void k
     for (int i = 0; i < 4; ++i) {
       const int row = wave * 16 + acc_row<true>(lane, i);
       if (row < nrows && col < T) {
-        double v = acc64[g][0][i] + acc64[g][1][i];
+        double v = scale * (acc64[g][0][i] + acc64[g][1][i]);
         if (add_diag) v = fma(dadd, vin[(uint64_t)(it.in_row0 + it.row_in_block + row) * T + col], v);
         const uint64_t idx = (uint64_t)(it.out_row0 + row) * T + col;
         if (pt.accumulate) v += out[idx];
@@ -471,7 +473,7 @@ __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(2))) void k
   daccy += __shfl_xor(daccy, 16);
   daccy += __shfl_xor(daccy, 32);
   if (kg == 0 && lr < nrows) {
-    double v = daccy;
+    double v = scale * daccy;
     if (add_diag) v = fma(dadd, vin[(uint64_t)(it.in_row0 + it.row_in_block + lr) * T], v);
     const uint64_t idx = (uint64_t)(it.out_row0 + lr) * T;
     if (pt.accumulate) v += out[idx];

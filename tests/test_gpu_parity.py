@@ -186,6 +186,33 @@ def test_train_step_gradient_matches_oracle(lib, case):
     ctx.close()
 
 
+@pytest.mark.parametrize("case", ["ragged-t16", "C1"])
+def test_train_step_operator_shortcuts_agree_with_fresh_assembly(lib, case):
+    # Section 3.3, eqs. (linear2) / (linear3): the output-scale and noise evaluations may reuse the blocks
+    # assembled at theta_0 (default) or assemble anew (NUGPR_NO_SHORTCUTS); both must match the oracle,
+    # which always assembles in fp64
+    w = CASES[case]()
+    prob = oracle_problem(w)
+    phi0 = np.log(w.theta)
+    p = phi0.shape[0]
+    _, _, _, _, nll0, g = O.train_step(prob, phi0, np.zeros(p), np.zeros(p), 0, w.fd_step, w.tol, w.max_iter, lr=w.lr)
+    grads = {}
+    for no_sc in (False, True):
+        ctx = make_ctx(lib, w, no_shortcuts=no_sc)
+        out = ctx.nugpr_train_step(phi0, np.zeros(p), np.zeros(p), 0)
+        assert out["code"] == 0
+        assert abs(out["nll0"] - nll0) <= 1e-4 * abs(nll0)
+        assert np.linalg.norm(out["grad"] - g) <= 1e-4 * np.linalg.norm(g) + GRAD_FLOOR.get(case, 0.0)
+        grads[no_sc] = out["grad"]
+        ctx.close()
+    # the two hyperparameters the shortcut serves (the last two entries of theta)
+    err_sc = np.abs(grads[False][-2:] - g[-2:]).max() / np.linalg.norm(g)
+    err_fresh = np.abs(grads[True][-2:] - g[-2:]).max() / np.linalg.norm(g)
+    print("alpha / sigma^2 gradient error: shortcut", err_sc, "fresh assembly", err_fresh, flush=True)
+    record_metric("shortcut:" + w.name, err_shortcut=float(err_sc), err_fresh=float(err_fresh))
+    np.testing.assert_allclose(grads[False][:-2], grads[True][:-2], rtol=0, atol=1e-9 * np.linalg.norm(g))
+
+
 def test_stale_factor_is_reused_across_theta(lib):
     # Section 3.2: the factor of theta_0 preconditions K(theta') too; eq. (logdet) stays exact
     w = small_ragged(seed=11, t=16)
