@@ -25,6 +25,8 @@ What each function follows:
   mll                 eq. (loss function) / ComputeLoss of Algorithm 1
   fd_gradient         eq. (numerical gradient), central form on log theta
   adam_step           Adam update of Algorithm 1
+  predict             posterior mean and variance, Section 2.1 "Posterior Forward
+                      Formulae", with the approximated covariance in place of K_y
 
 Readings where the paper is silent or garbled (each is pinned in the tests or
 listed as a reading in the design notes):
@@ -41,7 +43,11 @@ listed as a reading in the design notes):
     eq. (logdet); probe right-hand sides are b = L z so that left-preconditioned
     CG starts its Lanczos process at z;
   * CG stops per column on the relative recurrence residual
-    ||r_c|| <= tol ||b_c||; a stopped column is frozen.
+    ||r_c|| <= tol ||b_c||; a stopped column is frozen;
+  * prediction: K_* is the exact kernel between training and test points (the
+    paper approximates only the training covariance), K_** its prior variance
+    alpha (latent function, no noise term), the solves go through the same
+    preconditioned CG as training.
 
 Pins: every function here is pinned by tests/test_oracle_pins.py (dense
 Cholesky / slogdet, closed forms, explicit Lanczos, Hadamard-exact traces,
@@ -379,3 +385,34 @@ def train_step(prob: Problem, log_theta, m, v, step, h, tol, max_iter, lr=0.05,
     phi, m, v, step = adam_step(np.asarray(log_theta, dtype=np.float64), g, m, v, step,
                                 lr, beta1, beta2, eps)
     return phi, m, v, step, nll0, g
+
+
+# --------------------------------------------------------------------------
+# posterior prediction (Section 2.1, "Posterior Forward Formulae")
+# --------------------------------------------------------------------------
+def predict(prob: Problem, fac: Factor, theta, Xtest, tol, max_iter, variance=True):
+    """mu = K_*^T K'^-1 y and s^2 = diag(K_** - K_*^T K'^-1 K_*) at the test points.
+
+    K' = the approximated training covariance at theta, K_* = k(X_train, X_test)
+    exactly, K_** = k(x, x) = alpha.  Every solve is a preconditioned CG run with
+    the factor `fac` (columns: y, then the columns of K_*).
+    Returns dict(mean[m], var[m] or None, iters)."""
+    Xtest = np.asarray(Xtest, dtype=np.float64)
+    ell, alpha, _ = split_theta(theta, prob.d)
+    Ks = rbf(prob.X, Xtest, ell, alpha)                      # n x m
+    op = prob.operator(theta)
+    B = np.concatenate([prob.y[:, None], Ks], axis=1) if variance else prob.y[:, None].copy()
+    X, iters, _, _, _ = pcg(op, fac.apply, B, tol, max_iter)
+    mean = Ks.T @ X[:, 0]
+    var = None
+    if variance:
+        var = alpha - np.einsum("ij,ij->j", Ks, X[:, 1:])
+    return dict(mean=mean, var=var, iters=iters)
+
+
+def rmse(mean, ytest):
+    """Root mean squared error of the predictive mean (the usual definition; the paper's
+    printed formula takes the root of the 2-norm)."""
+    mean = np.asarray(mean, dtype=np.float64)
+    ytest = np.asarray(ytest, dtype=np.float64)
+    return float(np.sqrt(np.mean((mean - ytest) ** 2)))

@@ -468,6 +468,72 @@ def test_train_step_reduces_loss_on_small_problem():
 
 
 # ---------------------------------------------------------------- inputs
+# ---------------------------------------------------------------- prediction
+def _textbook_posterior(K, Ks, alpha, y):
+    """Posterior mean and variance of a zero-mean GP by dense solves (Section 2.1)."""
+    mean = Ks.T @ np.linalg.solve(K, y)
+    var = alpha - np.einsum("ij,ij->j", Ks, np.linalg.solve(K, Ks))
+    return mean, var
+
+
+def test_predict_equals_textbook_posterior_when_the_covariance_is_exact():
+    # one cluster: K' is the exact covariance, so the prediction must be the textbook GP posterior,
+    # computed here with dense solves and a brute-force cross-covariance
+    w = I.make_small(n_clusters=1, sizes=[40], d=2, rank=4, t=4, ell=1.1, seed=5)
+    prob = O.Problem(w.X, w.y, w.offsets, w.probes, w.rank)
+    fac = O.Factor(prob, w.theta)
+    rng = np.random.default_rng(0)
+    Xt = rng.uniform(-2, 2, size=(7, 2))
+    out = O.predict(prob, fac, w.theta, Xt, 1e-12, 200)
+    ell, alpha, sigma2 = O.split_theta(w.theta, 2)
+    X64 = np.asarray(w.X, dtype=np.float64)
+    K = np.array([[brute_kernel(a, b, ell, alpha) for b in X64] for a in X64]) + sigma2 * np.eye(40)
+    Ks = np.array([[brute_kernel(a, b, ell, alpha) for b in Xt] for a in X64])
+    mean, var = _textbook_posterior(K, Ks, alpha, np.asarray(w.y, dtype=np.float64))
+    np.testing.assert_allclose(out["mean"], mean, rtol=1e-9, atol=1e-10)
+    np.testing.assert_allclose(out["var"], var, rtol=1e-8, atol=1e-10)
+    assert np.all(out["var"] > 0) and np.all(out["var"] <= alpha + 1e-12)
+
+
+def test_predict_with_the_approximated_covariance_uses_dense_K_prime():
+    # several clusters: the solves are against K' (not the exact covariance); pinned with the dense K'
+    w = I.make_small(n_clusters=3, sizes=[20, 33, 17], d=3, rank=3, t=4, ell=1.5, spacing=4.5, sigma_blob=0.3, seed=8)
+    prob = O.Problem(w.X, w.y, w.offsets, w.probes, w.rank)
+    fac = O.Factor(prob, w.theta)
+    Xt = np.random.default_rng(1).normal(size=(5, 3)) * 3.0
+    out = O.predict(prob, fac, w.theta, Xt, 1e-12, 300)
+    ell, alpha, _ = O.split_theta(w.theta, 3)
+    Kp = prob.dense(w.theta)
+    Ks = np.array([[brute_kernel(a, b, ell, alpha) for b in Xt] for a in prob.X])
+    mean, var = _textbook_posterior(Kp, Ks, alpha, prob.y)
+    np.testing.assert_allclose(out["mean"], mean, rtol=1e-8, atol=1e-10)
+    np.testing.assert_allclose(out["var"], var, rtol=1e-8, atol=1e-10)
+    # mean only: same mean, no variance
+    out2 = O.predict(prob, fac, w.theta, Xt, 1e-12, 300, variance=False)
+    np.testing.assert_allclose(out2["mean"], mean, rtol=1e-8, atol=1e-10)
+    assert out2["var"] is None
+
+
+def test_predict_interpolates_training_points_when_noise_vanishes():
+    # special case: sigma^2 -> 0 at a training input gives mean -> y_i and variance -> 0
+    X = np.arange(8, dtype=np.float64)[:, None]              # a well-conditioned grid
+    y = np.sin(1.3 * X[:, 0]) + 0.5
+    theta = np.array([0.7, 1.3, 1e-10])
+    probes = I.rademacher(1, 8, 2)
+    prob = O.Problem(X, y, np.array([0, 8]), probes, 2)
+    fac = O.Factor(prob, theta)
+    out = O.predict(prob, fac, theta, prob.X[[3, 7]], 1e-13, 500)
+    np.testing.assert_allclose(out["mean"], prob.y[[3, 7]], rtol=0, atol=1e-7)
+    assert np.all(np.abs(out["var"]) < 1e-7)
+    # far from every training point the prior comes back: mean 0, variance alpha
+    far = O.predict(prob, fac, theta, np.array([[1e3]]), 1e-13, 500)
+    assert abs(far["mean"][0]) < 1e-12 and abs(far["var"][0] - theta[-2]) < 1e-12
+
+
+def test_rmse_definition():
+    assert abs(O.rmse([1.0, 2.0, 4.0], [1.0, 0.0, 0.0]) - math.sqrt((0 + 4 + 16) / 3)) < 1e-15
+
+
 def test_input_generators_are_seeded_and_shaped():
     a = I.make_config("C1")
     b = I.make_config("C1")
