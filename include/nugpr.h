@@ -181,6 +181,31 @@ int nugpr_mll(nugpr_ctx* ctx, const double* theta /*HOST*/, nugpr_mll_result* re
 int nugpr_train_step(nugpr_ctx* ctx, double* log_theta, double* adam_m, double* adam_v,
                      int64_t* step, double* nll0, double* grad, void* stream);
 
+/* Posterior prediction (Section 2.1, posterior forward formulae) at theta, with the
+ * approximated covariance K' (Section 3.3) in the place of the exact one:
+ *   mean_j = <k_j, K'^-1 y>,    var_j = alpha - <k_j, K'^-1 k_j>,
+ * k_j the exact kernel between the training points and test point j; alpha is the
+ * diagonal of K_** (the latent function's prior variance; add sigma^2 for a noisy
+ * observation).  Assembles the blocks at theta and solves with the stored preconditioner:
+ * one single-column PCG for y, then, only if var is not NULL, ceil(m / (n_probes+1))
+ * batched PCG solves on the cross-covariance columns, which are generated on the device
+ * and never stored as a whole.  Xtest: DEVICE m x d row-major fp32, read only, caller
+ * keeps ownership.  mean: HOST m doubles.  var: HOST m doubles or NULL (mean only).
+ * max_iters_used: HOST, may be NULL.  Synchronises `stream`.  Returns NUGPR_OK,
+ * NUGPR_NOT_CONVERGED (some solve hit max_iter; outputs written), NUGPR_INDEFINITE
+ * (outputs not complete) or a negative error; m = 0 is a no-op. */
+int nugpr_predict(nugpr_ctx* ctx, const double* theta /*HOST*/, const float* Xtest /*DEVICE*/,
+                  int64_t m, double* mean /*HOST*/, double* var /*HOST*/, int32_t* max_iters_used,
+                  void* stream);
+
+/* Root-mean-square error of a prediction (Section 2.1): sqrt(sum_j (mean_j - ytest_j)^2 / m).
+ * All HOST; m >= 1. */
+int nugpr_rmse(const double* mean, const double* ytest, int64_t m, double* out);
+
+/* Confidence region of Section 2.1: lo = mean - 2 s, hi = mean + 2 s with
+ * s = sqrt(max(var, 0)).  All HOST arrays of m doubles; lo / hi may alias nothing else. */
+int nugpr_confidence_band(const double* mean, const double* var, int64_t m, double* lo, double* hi);
+
 /* Copies one stored matrix to a dense row-major DEVICE array `dst` with leading
  * dimension `ld` (for verification).  what: 0 = K_ii (b_i x b_i), 1 = L_i lower
  * factor (b_i x b_i, zeros above the diagonal), 2 = L_i^-1 (b_i x b_i), 3 = coupling

@@ -87,6 +87,12 @@ def load_library():
     lib.nugpr_mll.argtypes = [vp, dp, C.POINTER(MllResult), vp]
     lib.nugpr_train_step.restype = C.c_int
     lib.nugpr_train_step.argtypes = [vp, dp, dp, dp, C.POINTER(C.c_int64), dp, dp, vp]
+    lib.nugpr_predict.restype = C.c_int
+    lib.nugpr_predict.argtypes = [vp, dp, vp, C.c_int64, dp, dp, ip, vp]
+    lib.nugpr_rmse.restype = C.c_int
+    lib.nugpr_rmse.argtypes = [dp, dp, C.c_int64, dp]
+    lib.nugpr_confidence_band.restype = C.c_int
+    lib.nugpr_confidence_band.argtypes = [dp, dp, C.c_int64, dp, dp]
     lib.nugpr_export.restype = C.c_int
     lib.nugpr_export.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_int64, vp]
     lib.nugpr_num_hyper.restype = C.c_int32
@@ -120,6 +126,26 @@ def nugpr_copy_probe(dst, src, stream=None):
     nbytes = src.numel() * src.element_size()
     st = C.c_void_p(torch.cuda.current_stream(src.device).cuda_stream if stream is None else stream)
     return _check(lib.nugpr_copy_probe(dst.data_ptr(), src.data_ptr(), nbytes, st))
+
+
+def nugpr_rmse(mean, ytest):
+    a = np.ascontiguousarray(np.asarray(mean, dtype=np.float64))
+    b = np.ascontiguousarray(np.asarray(ytest, dtype=np.float64))
+    if a.shape != b.shape or a.ndim != 1:
+        raise NugprError(NUGPR_ERR_INVALID, "mean and ytest must be vectors of one length")
+    out = C.c_double()
+    _check(load_library().nugpr_rmse(_dptr(a), _dptr(b), a.shape[0], C.byref(out)))
+    return out.value
+
+
+def nugpr_confidence_band(mean, var):
+    a = np.ascontiguousarray(np.asarray(mean, dtype=np.float64))
+    v = np.ascontiguousarray(np.asarray(var, dtype=np.float64))
+    if a.shape != v.shape or a.ndim != 1:
+        raise NugprError(NUGPR_ERR_INVALID, "mean and var must be vectors of one length")
+    lo, hi = np.zeros_like(a), np.zeros_like(a)
+    _check(load_library().nugpr_confidence_band(_dptr(a), _dptr(v), a.shape[0], _dptr(lo), _dptr(hi)))
+    return lo, hi
 
 
 class Context:
@@ -254,6 +280,19 @@ class Context:
         code = _check(self.lib.nugpr_train_step(self.handle, _dptr(phi), _dptr(m), _dptr(v), C.byref(st),
                                                 C.byref(nll0), _dptr(g), self._stream()))
         return dict(code=code, log_theta=phi, adam_m=m, adam_v=v, step=st.value, nll0=nll0.value, grad=g)
+
+    def nugpr_predict(self, theta, Xtest, variance=True):
+        th = self._theta(theta)
+        Xt = self.torch.as_tensor(Xtest).to(device=self.device, dtype=self.torch.float32).contiguous()
+        if Xt.dim() != 2 or Xt.shape[1] != self.d:
+            raise NugprError(NUGPR_ERR_INVALID, f"Xtest must be (m, {self.d})")
+        m = int(Xt.shape[0])
+        mean = np.zeros(m, dtype=np.float64)
+        var = np.zeros(m, dtype=np.float64) if variance else None
+        mx = C.c_int32()
+        code = _check(self.lib.nugpr_predict(self.handle, _dptr(th), Xt.data_ptr() if m else None, m, _dptr(mean),
+                                             _dptr(var) if variance else None, C.byref(mx), self._stream()))
+        return dict(code=code, mean=mean, var=var, max_iters_used=mx.value)
 
     def nugpr_matvec_into(self, D, Q):
         """nugpr_matvec on caller-held device tensors (no allocation; used for timing)."""

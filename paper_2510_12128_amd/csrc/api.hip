@@ -202,6 +202,7 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   c->Qv = w + L.o_Q;
   c->Vv = w + L.o_V;
   c->Uv = w + L.o_U;
+  c->x0 = w + L.o_x0;
   c->Spart = w + L.o_Spart;
   c->Ppart = w + L.o_Ppart;
   c->dotpart = reinterpret_cast<double*>(w + L.o_dot);
@@ -499,6 +500,39 @@ int nugpr_train_step(nugpr_ctx* c, double* log_theta, double* adam_m, double* ad
     log_theta[i] -= lr * mh / (std::sqrt(vh) + eps);
   }
   return worst;
+}
+
+int nugpr_predict(nugpr_ctx* c, const double* theta, const float* Xtest, int64_t m, double* mean, double* var,
+                  int32_t* max_iters_used, void* stream) {
+  if (!c || !theta) { set_error("null argument"); return NUGPR_ERR_INVALID; }
+  if (m < 0) { set_error("m must be >= 0"); return NUGPR_ERR_INVALID; }
+  if (m > 0 && (!Xtest || !mean)) { set_error("Xtest or mean is null"); return NUGPR_ERR_INVALID; }
+  if (reinterpret_cast<uintptr_t>(Xtest) & 3u) { set_error("Xtest misaligned"); return NUGPR_ERR_INVALID; }
+  if (!c->factored) { set_error("predict needs precond_factor first"); return NUGPR_ERR_STATE; }
+  if (max_iters_used) *max_iters_used = 0;
+  if (m == 0) return NUGPR_OK;
+  hipStream_t s = as_stream(stream);
+  int rc = launch_build(c, theta, s);          // validates theta
+  if (rc) return rc;
+  return run_predict(c, theta, Xtest, m, mean, var, max_iters_used, s);
+}
+
+int nugpr_rmse(const double* mean, const double* ytest, int64_t m, double* out) {
+  if (!mean || !ytest || !out || m < 1) { set_error("rmse needs m >= 1 and non-null arrays"); return NUGPR_ERR_INVALID; }
+  double acc = 0.0;
+  for (int64_t j = 0; j < m; ++j) { const double e = mean[j] - ytest[j]; acc += e * e; }
+  *out = std::sqrt(acc / (double)m);
+  return NUGPR_OK;
+}
+
+int nugpr_confidence_band(const double* mean, const double* var, int64_t m, double* lo, double* hi) {
+  if (m < 0 || (m > 0 && (!mean || !var || !lo || !hi))) { set_error("null argument"); return NUGPR_ERR_INVALID; }
+  for (int64_t j = 0; j < m; ++j) {
+    const double sd = std::sqrt(var[j] > 0.0 ? var[j] : 0.0);
+    lo[j] = mean[j] - 2.0 * sd;
+    hi[j] = mean[j] + 2.0 * sd;
+  }
+  return NUGPR_OK;
 }
 
 int nugpr_export(nugpr_ctx* c, int32_t what, int32_t index, float* dst, int64_t ld, void* stream) {

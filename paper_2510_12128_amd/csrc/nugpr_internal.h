@@ -130,6 +130,7 @@ struct Layout {
   size_t o_Spart = 0, o_Ppart = 0, o_dot = 0, o_state = 0, o_alog = 0, o_blog = 0;
   size_t o_theta = 0, o_logdet = 0, o_tiles = 0, o_items = 0;
   size_t o_Xs = 0, o_Xn = 0, o_Rs = 0, o_Rn = 0;
+  size_t o_x0 = 0;
   size_t items_bytes = 0;
   int n_dot_blocks = 0;
   int max_iter = 0;
@@ -156,6 +157,7 @@ struct nugpr_ctx {
   void *Bv = nullptr, *Xv = nullptr, *Rv = nullptr, *Zv = nullptr, *Dv = nullptr, *Qv = nullptr, *Vv = nullptr,
        *Uv = nullptr;
   void *Spart = nullptr, *Ppart = nullptr;
+  void* x0 = nullptr;                    // K'^-1 y of a prediction call (one column, internal type)
   bool acc64 = true;                     // arithmetic mode of the operator applications
   double *dotpart = nullptr, *alog = nullptr, *blog = nullptr, *d_theta = nullptr, *d_logdet = nullptr;
   nugpr::PcgState* d_state = nullptr;
@@ -220,6 +222,10 @@ int run_pcg(nugpr_ctx* c, const void* B, void* X, int T, int32_t* iters, double*
 int run_dot_col(nugpr_ctx* c, const void* A, const void* B, int T, double* out_host, hipStream_t s);
 int to_internal(nugpr_ctx* c, const float* src, void* dst, int64_t count, hipStream_t s);
 int from_internal(nugpr_ctx* c, const void* src, float* dst, int64_t count, hipStream_t s);
+
+// predict.hip ----------------------------------------------------------------
+int run_predict(nugpr_ctx* c, const double* theta, const float* Xt, int64_t m, double* mean, double* var,
+                int32_t* max_iters_used, hipStream_t s);
 
 // slq.cpp ---------------------------------------------------------------------
 // e_1^T log(T) e_1 for the k x k Lanczos matrix built from CG coefficients.

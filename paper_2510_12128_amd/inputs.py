@@ -209,6 +209,28 @@ def make_small(n_clusters: int = 3, sizes=None, d: int = 2, rank: int = 2, t: in
                     tol=tol, max_iter=max_iter, meta=dict(centres=centres))
 
 
+def test_points(w: Workload, m: int, seed: int = 0, margin: float = 0.1) -> np.ndarray:
+    """m seeded test inputs (float32) for a workload: half are training points displaced by a
+    fraction of their cluster's spread (inputs that fall inside the clusters, as a held-out
+    split of the same data would), half are uniform over the bounding box of the training set
+    widened by `margin` of its extent per side (the uniformly spread test inputs of the
+    synthetic experiments, some of them far from every cluster)."""
+    rng = np.random.default_rng(seed + 77001)
+    X = np.asarray(w.X, dtype=np.float64)
+    m_in = m // 2
+    idx = rng.integers(0, X.shape[0], size=m_in)
+    spread = X.std(axis=0) / max(w.n_clusters, 1) ** (1.0 / max(X.shape[1], 1))
+    inside = X[idx] + 0.25 * spread * rng.standard_normal((m_in, X.shape[1]))
+    lo, hi = X.min(axis=0), X.max(axis=0)
+    ext = hi - lo
+    outside = rng.uniform(lo - margin * ext, hi + margin * ext, size=(m - m_in, X.shape[1]))
+    out = np.concatenate([inside, outside], axis=0)
+    return out[rng.permutation(m)].astype(np.float32)
+
+
+test_points.__test__ = False     # not a pytest case
+
+
 def hadamard_probes(n: int) -> np.ndarray:
     """Sylvester-Hadamard matrix of order n (a power of two), entries +1/-1,
     H H^T = n I: with these n probes the Hutchinson trace estimate is exact."""

@@ -29,7 +29,8 @@ def declared_symbols():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
     for must in ["nugpr_build_blocks", "nugpr_precond_factor", "nugpr_pcg_solve", "nugpr_mll",
-                 "nugpr_train_step", "nugpr_matvec", "nugpr_create", "nugpr_destroy"]:
+                 "nugpr_train_step", "nugpr_matvec", "nugpr_create", "nugpr_destroy", "nugpr_predict",
+                 "nugpr_rmse", "nugpr_confidence_band"]:
         assert must in names
     for n in names:
         assert hasattr(lib, n), n
@@ -81,6 +82,16 @@ def test_create_rejects_bad_params_and_null_buffers_without_gpu(lib):
     assert not h.value
     assert lib.nugpr_destroy(None) == 0
     assert lib.nugpr_build_blocks(None, None, None) == B.NUGPR_ERR_INVALID
+
+
+def test_host_side_prediction_scores(lib):
+    # Section 2.1: RMSE and the two-sigma band, by hand on three numbers
+    assert abs(B.nugpr_rmse([1.0, 2.0, 4.0], [1.0, 0.0, 0.0]) - (20.0 / 3.0) ** 0.5) < 1e-15
+    lo, hi = B.nugpr_confidence_band([0.0, 1.0, -2.0], [4.0, 0.25, -1e-9])
+    np.testing.assert_allclose(lo, [-4.0, 0.0, -2.0], atol=1e-15)
+    np.testing.assert_allclose(hi, [4.0, 2.0, -2.0], atol=1e-15)
+    with pytest.raises(B.NugprError):
+        B.nugpr_rmse([], [])
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):

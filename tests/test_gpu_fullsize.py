@@ -155,6 +155,36 @@ def test_config4_full_size(lib):
     record_metric("fullsize:C4-wide-solve", iters=int(iters.max()), row_residual=rel, nll=out["nll"])
     assert rel < 1e-4, rel
     assert iters.max() >= 5
+    # ---- prediction at the wide lengthscale (Section 2.1).  The oracle supplies the cross-covariance
+    # columns one by one; the solves are the GPU's generic batched solve of those columns (whose
+    # residuals are checked above and below), the dot products are taken here in fp64.
+    import time
+    m = ctx.T + 3
+    Xt = I.test_points(w, m, seed=9)
+    t0 = time.perf_counter()
+    pred = ctx.nugpr_predict(wide, Xt)
+    t_pred = time.perf_counter() - t0
+    assert pred["code"] == 0
+    Ks = O.rbf(X64, Xt.astype(np.float64), op.ell, op.alpha)                   # n x m, fp64
+    mean_ref = Ks.T @ Xd[:, 0]
+    var_ref = np.empty(m)
+    for j0 in range(0, m, ctx.T):
+        cols = Ks[:, j0:j0 + ctx.T]
+        code, Sj, _, _, _ = ctx.nugpr_pcg_solve(cols.astype(np.float32))
+        assert code == 0
+        Sj = Sj.cpu().numpy().astype(np.float64)
+        r2 = op.rows(Sj, op.project(Sj), pts[:8]) - cols[pts[:8]]
+        assert np.max(np.abs(r2)) <= 1e-4 * max(np.max(np.abs(cols)), 1e-30)
+        var_ref[j0:j0 + cols.shape[1]] = op.alpha - np.einsum("ij,ij->j", cols, Sj)
+    e_mean = float(np.max(np.abs(pred["mean"] - mean_ref)) / np.max(np.abs(mean_ref)))
+    e_var = float(np.max(np.abs(pred["var"] - var_ref)) / op.alpha)
+    t0 = time.perf_counter()
+    pm = ctx.nugpr_predict(wide, I.test_points(w, 1000, seed=10), variance=False)
+    t_mean = time.perf_counter() - t0
+    record_metric("fullsize:C4-predict", m=m, err_mean=e_mean, err_var=e_var, seconds=t_pred,
+                  iters=int(pred["max_iters_used"]), mean_only_1000_points_seconds=t_mean)
+    assert e_mean < 1e-4 and e_var < 1e-4, (e_mean, e_var)
+    assert np.all(pred["var"] <= op.alpha) and np.all(np.isfinite(pm["mean"]))
     # ---- default lengthscale, the benchmark's own evaluation: one train step
     p = ctx.p
     step = ctx.nugpr_train_step(np.log(theta), np.zeros(p), np.zeros(p), 0)
@@ -214,6 +244,15 @@ def test_scaled_stress_variants_match_oracle(lib, name, nclus, shrink, with_grad
     Xg = Xg.cpu().numpy().astype(np.float64)
     Xo = O.pcg(prob.operator(w.theta), fac.apply, Bg.cpu().numpy().astype(np.float64), 1e-10, 200)[0]
     serr = max(np.linalg.norm(Xg[:, c] - Xo[:, c]) / np.linalg.norm(Xo[:, c]) for c in range(w.n_probes + 1))
+    # prediction at the real cluster shape, two batches of test points, same tightened tolerance
+    Xt = I.test_points(w, w.n_probes + 4, seed=6)
+    pref = O.predict(prob, fac, w.theta, Xt, 1e-10, 200)
+    pgot = tight.nugpr_predict(w.theta, Xt)
+    assert pgot["code"] == 0
+    perr_mean = float(np.max(np.abs(pgot["mean"] - pref["mean"])) / np.max(np.abs(pref["mean"])))
+    perr_var = float(np.max(np.abs(pgot["var"] - pref["var"])) / w.theta[-2])
+    record_metric("stress-predict:" + w.name, err_mean=perr_mean, err_var=perr_var)
+    assert perr_mean < 1e-4 and perr_var < 1e-4, (perr_mean, perr_var)
     tight.close()
     record_metric("stress:" + w.name, solve_err=float(serr), nll_err=abs(out["nll"] - ref["nll"]) / abs(ref["nll"]),
                   iters=int(out["max_iters_used"]), oracle_iters=int(ref["iters"].max()))

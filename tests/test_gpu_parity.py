@@ -213,6 +213,75 @@ def test_train_step_operator_shortcuts_agree_with_fresh_assembly(lib, case):
     np.testing.assert_allclose(grads[False][:-2], grads[True][:-2], rtol=0, atol=1e-9 * np.linalg.norm(g))
 
 
+# Prediction bar: the mean to 1e-4 of the largest mean; the variance to 1e-4 of the prior
+# variance alpha (it is alpha minus a quadratic form of that size, so the quadratic form's
+# 1e-4 relative accuracy is what can be asked of the difference).
+@pytest.mark.parametrize("case", ["ragged-t8", "ragged-t32", "tiny", "iso-d1", "C1", "C1-wide"])
+def test_predict_matches_oracle(lib, case):
+    w = CASES[case]()
+    print("case", w.name, flush=True)
+    ctx = make_ctx(lib, w)
+    prob = oracle_problem(w)
+    ctx.nugpr_build_blocks(w.theta)
+    assert ctx.nugpr_precond_factor()[0] == 0
+    fac = O.Factor(prob, w.theta)
+    # more test points than one batch holds, with a ragged last batch
+    m = 2 * (w.n_probes + 1) + 3
+    Xt = I.test_points(w, m, seed=5)
+    # a theta other than the preconditioner's: prediction after training steps
+    theta = w.theta * (1.0 + 0.04 * np.cos(np.arange(w.theta.shape[0])))
+    ref = O.predict(prob, fac, theta, Xt, w.tol, w.max_iter)
+    out = ctx.nugpr_predict(theta, Xt)
+    assert out["code"] == 0
+    alpha = theta[-2]
+    err_mean = float(np.max(np.abs(out["mean"] - ref["mean"])) / np.max(np.abs(ref["mean"])))
+    err_var = float(np.max(np.abs(out["var"] - ref["var"])) / alpha)
+    record_metric("predict:" + w.name, err_mean=err_mean, err_var=err_var, m=m,
+                  iters=int(out["max_iters_used"]))
+    assert err_mean < 1e-4, err_mean
+    assert err_var < 1e-4, err_var
+    assert abs(out["max_iters_used"] - int(np.max(ref["iters"]))) <= 2
+    # mean only: the same means, no variance solves
+    out2 = ctx.nugpr_predict(theta, Xt, variance=False)
+    assert out2["var"] is None
+    assert np.max(np.abs(out2["mean"] - out["mean"])) <= 1e-12 * np.max(np.abs(out["mean"]))
+    # the loss path still works on the same context afterwards (its right-hand sides are untouched)
+    refl = O.mll(prob, fac, w.theta, w.tol, w.max_iter)
+    got = ctx.nugpr_mll(w.theta)
+    assert abs(got["nll"] - refl["nll"]) <= 1e-4 * abs(refl["nll"])
+    # scores on the host side of the boundary
+    yt = np.sin(Xt.astype(np.float64).sum(axis=1))
+    assert abs(B.nugpr_rmse(out["mean"], yt) - O.rmse(ref["mean"], yt)) < 1e-4
+    ctx.close()
+
+
+def test_predict_edge_cases(lib):
+    w = small_ragged(seed=10, t=4)
+    ctx = make_ctx(lib, w)
+    Xt = I.test_points(w, 3, seed=1)
+    with pytest.raises(B.NugprError) as e:          # needs the factor
+        ctx.nugpr_predict(w.theta, Xt)
+    assert e.value.code == B.NUGPR_ERR_STATE
+    ctx.nugpr_build_blocks(w.theta)
+    assert ctx.nugpr_precond_factor()[0] == 0
+    out = ctx.nugpr_predict(w.theta, np.zeros((0, w.d), dtype=np.float32))     # no test points
+    assert out["code"] == 0 and out["mean"].shape == (0,)
+    with pytest.raises(B.NugprError):
+        ctx.nugpr_predict(w.theta, np.zeros((2, w.d + 1), dtype=np.float32))
+    # a training input as the test point.  K_* is exact while K' is approximated, so the joint
+    # matrix need not be positive semi-definite: the variance is below the prior (K'^-1 is
+    # positive definite) but can come out slightly negative, in the oracle as well.
+    prob = oracle_problem(w)
+    fac = O.Factor(prob, w.theta)
+    one = w.X[[17]]
+    ref = O.predict(prob, fac, w.theta, one, w.tol, w.max_iter)
+    out = ctx.nugpr_predict(w.theta, one)
+    assert abs(out["mean"][0] - ref["mean"][0]) < 1e-4 * max(abs(ref["mean"][0]), 1.0)
+    assert abs(out["var"][0] - ref["var"][0]) < 1e-4 * w.theta[-2]
+    assert out["var"][0] < w.theta[-2]
+    ctx.close()
+
+
 def test_stale_factor_is_reused_across_theta(lib):
     # Section 3.2: the factor of theta_0 preconditions K(theta') too; eq. (logdet) stays exact
     w = small_ragged(seed=11, t=16)
