@@ -203,6 +203,7 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   c->Vv = w + L.o_V;
   c->Uv = w + L.o_U;
   c->x0 = w + L.o_x0;
+  c->Z0v = w + L.o_Z0;
   c->Spart = w + L.o_Spart;
   c->Ppart = w + L.o_Ppart;
   c->dotpart = reinterpret_cast<double*>(w + L.o_dot);
@@ -420,19 +421,13 @@ static int mll_impl(nugpr_ctx* c, const double* theta, nugpr_mll_result* res, bo
   std::vector<int32_t> iters(T);
   std::vector<double> alpha((size_t)max_iter * T), beta((size_t)max_iter * T);
   int mx = 0;
-  rc = run_pcg(c, c->Bv, c->Xv, T, iters.data(), alpha.data(), beta.data(), &mx, s);
+  PcgExtras ex;
+  rc = run_pcg(c, c->Bv, c->Xv, T, iters.data(), alpha.data(), beta.data(), &mx, s, &ex);
   if (rc < 0) return rc;
   res->max_iters_used = mx;
   res->status = rc;
   if (rc == NUGPR_INDEFINITE) return rc;
-  double dots[MAX_COLS];
-  int rc2 = run_dot_col(c, c->Bv, c->Xv, T, dots, s);
-  if (rc2) return rc2;
-  res->quad = dots[0];                           // <y, K'^-1 y>: column 0 of B is y
-  // squared norms of the Lanczos start vectors
-  PcgState* hs = reinterpret_cast<PcgState*>(c->h_buf);
-  NUGPR_HIP(hipMemcpyAsync(hs, c->d_state, sizeof(PcgState), hipMemcpyDeviceToHost, s));
-  NUGPR_HIP(hipStreamSynchronize(s));
+  res->quad = ex.bx[0];                          // <y, K'^-1 y>: column 0 of B is y
   double est = 0.0;
   for (int col = 1; col < T; ++col) {
     double q = 0.0;
@@ -440,7 +435,7 @@ static int mll_impl(nugpr_ctx* c, const double* theta, nugpr_mll_result* res, bo
       res->status = NUGPR_INDEFINITE;
       return NUGPR_INDEFINITE;
     }
-    est += hs->rho0[col] * q;
+    est += ex.rho0[col] * q;            // rho_0: squared norm of the Lanczos start vector
   }
   res->logdet = c->logdetM + (L.t > 0 ? est / L.t : 0.0);
   res->nll = 0.5 * (res->quad + res->logdet + (double)L.n * std::log(2.0 * M_PI));

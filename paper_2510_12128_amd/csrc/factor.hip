@@ -379,6 +379,11 @@ int launch_factor(nugpr_ctx* c, hipStream_t s) {
   if (c->acc64) hipLaunchKernelGGL((k_set_col0<double>), dim3(1024), dim3(256), 0, s, (double*)c->Bv, c->y, (int64_t)L.n, L.T);
   else hipLaunchKernelGGL((k_set_col0<float>), dim3(1024), dim3(256), 0, s, (float*)c->Bv, c->y, (int64_t)L.n, L.T);
   NUGPR_HIP(hipGetLastError());
+  // z_0 = M^-1 B of every later solve on these right-hand sides (x_0 = 0, so r_0 = B whatever theta is)
+  c->z0_ready = false;
+  int rc = run_precond(c, c->Bv, c->Z0v, L.T, s);
+  if (rc) return rc;
+  c->z0_ready = true;
   return NUGPR_OK;
 }
 

@@ -130,7 +130,7 @@ struct Layout {
   size_t o_Spart = 0, o_Ppart = 0, o_dot = 0, o_state = 0, o_alog = 0, o_blog = 0;
   size_t o_theta = 0, o_logdet = 0, o_tiles = 0, o_items = 0;
   size_t o_Xs = 0, o_Xn = 0, o_Rs = 0, o_Rn = 0;
-  size_t o_x0 = 0;
+  size_t o_x0 = 0, o_Z0 = 0;
   size_t items_bytes = 0;
   int n_dot_blocks = 0;
   int max_iter = 0;
@@ -157,6 +157,10 @@ struct nugpr_ctx {
   void *Bv = nullptr, *Xv = nullptr, *Rv = nullptr, *Zv = nullptr, *Dv = nullptr, *Qv = nullptr, *Vv = nullptr,
        *Uv = nullptr;
   void *Spart = nullptr, *Ppart = nullptr;
+  // M^-1 [y | L Z]: the first preconditioned residual of every solve on the context's own right-hand
+  // sides; it depends on the factor only, so the factorisation computes it once
+  void* Z0v = nullptr;
+  bool z0_ready = false;
   void* x0 = nullptr;                    // K'^-1 y of a prediction call (one column, internal type)
   bool acc64 = true;                     // arithmetic mode of the operator applications
   double *dotpart = nullptr, *alog = nullptr, *blog = nullptr, *d_theta = nullptr, *d_logdet = nullptr;
@@ -217,8 +221,14 @@ int launch_factor(nugpr_ctx* c, hipStream_t s);
 // (vector blocks are the context's internal type: fp64 when acc64, else fp32)
 int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s);
 int run_precond(nugpr_ctx* c, const void* R, void* Z, int T, hipStream_t s);
+// What a loss evaluation needs besides the solution, fetched with the solve's last synchronisation:
+// <b_c, x_c> per column and rho_0 = <r_0, M^-1 r_0>.
+struct PcgExtras {
+  double bx[MAX_COLS];
+  double rho0[MAX_COLS];
+};
 int run_pcg(nugpr_ctx* c, const void* B, void* X, int T, int32_t* iters, double* alpha, double* beta,
-            int* max_it_used, hipStream_t s);
+            int* max_it_used, hipStream_t s, PcgExtras* extras = nullptr);
 int run_dot_col(nugpr_ctx* c, const void* A, const void* B, int T, double* out_host, hipStream_t s);
 int to_internal(nugpr_ctx* c, const float* src, void* dst, int64_t count, hipStream_t s);
 int from_internal(nugpr_ctx* c, const void* src, float* dst, int64_t count, hipStream_t s);

@@ -193,12 +193,18 @@ __global__ void k_copy_flags(PcgState* __restrict__ st, HostFlags* __restrict__ 
   out->bad_cluster = st->bad_cluster;
 }
 
-// start of a solve: X = 0, R = B, and the alpha / beta logs cleared
+// start of a solve: X = 0, R = B, the alpha / beta logs cleared and, when the first preconditioned
+// residual is already known (Z0 not null), D = Z0
 template <typename VT>
-__global__ void k_pcg_init(VT* __restrict__ X, VT* __restrict__ R, const VT* __restrict__ B, int64_t count,
+__global__ void k_pcg_init(VT* __restrict__ X, VT* __restrict__ R, const VT* __restrict__ B,
+                           const VT* __restrict__ Z0, VT* __restrict__ D, int64_t count,
                            double* __restrict__ alog, double* __restrict__ blog, int64_t nlog) {
   const int64_t i0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = i0; i < count; i += stride) { X[i] = (VT)0; R[i] = B[i]; }
+  if (Z0) {
+    for (int64_t i = i0; i < count; i += stride) { X[i] = (VT)0; R[i] = B[i]; D[i] = Z0[i]; }
+  } else {
+    for (int64_t i = i0; i < count; i += stride) { X[i] = (VT)0; R[i] = B[i]; }
+  }
   for (int64_t i = i0; i < nlog; i += stride) { alog[i] = 0.0; blog[i] = 0.0; }
 }
 
@@ -292,7 +298,7 @@ int run_dot_col(nugpr_ctx* c, const void* A, const void* B, int T, double* out_h
 
 template <typename VT>
 static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double* alpha, double* beta,
-                 int* max_it_used, hipStream_t s) {
+                 int* max_it_used, hipStream_t s, PcgExtras* extras) {
   const Layout& L = c->L;
   const int64_t n = L.n;
   const size_t bytes = (size_t)n * T * sizeof(VT);
@@ -304,10 +310,12 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
   VT *R = (VT*)c->Rv, *Z = (VT*)c->Zv, *D = (VT*)c->Dv, *Q = (VT*)c->Qv;
   (void)bytes;
   // x_0 = 0, r_0 = B, cleared coefficient logs: one launch
-  hipLaunchKernelGGL((k_pcg_init<VT>), dim3(1024), dim3(256), 0, s, X, R, B, n * T, c->alog, c->blog,
-                     (int64_t)max_iter * MAX_COLS);
-  // d_0 = z_0 = M^-1 r_0, written straight into D
-  if ((rc = run_precond(c, R, D, T, s))) return rc;
+  // d_0 = z_0 = M^-1 r_0, written straight into D; for the context's own right-hand sides it was
+  // computed with the factor
+  const bool known = (const void*)B == (const void*)c->Bv && T == L.T && c->z0_ready;
+  hipLaunchKernelGGL((k_pcg_init<VT>), dim3(1024), dim3(256), 0, s, X, R, B, known ? (const VT*)c->Z0v : (const VT*)nullptr,
+                     D, n * T, c->alog, c->blog, (int64_t)max_iter * MAX_COLS);
+  if (!known && (rc = run_precond(c, R, D, T, s))) return rc;
   hipLaunchKernelGGL((k_dot<2, VT>), dim3(nb), dim3(256), 0, s, R, R, R, D, n, T, c->dotpart);
   hipLaunchKernelGGL(k_pcg_begin, dim3(T), dim3(256), 0, s, c->d_state, c->dotpart, nb);
   NUGPR_HIP(hipGetLastError());
@@ -342,6 +350,12 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
   const size_t cnt = (size_t)max_iter * MAX_COLS;
   PcgState* hs = reinterpret_cast<PcgState*>(c->h_buf + 2 * cnt);
   NUGPR_HIP(hipMemcpyAsync(hs, c->d_state, sizeof(PcgState), hipMemcpyDeviceToHost, s));
+  double* hdot = c->h_buf + 2 * cnt + (sizeof(PcgState) + sizeof(double) - 1) / sizeof(double);
+  if (extras) {
+    hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, B, X, B, X, n, T, c->dotpart);
+    NUGPR_HIP(hipGetLastError());
+    NUGPR_HIP(hipMemcpyAsync(hdot, c->dotpart, (size_t)nb * MAX_COLS * sizeof(double), hipMemcpyDeviceToHost, s));
+  }
   if (alpha || beta) {
     NUGPR_HIP(hipMemcpyAsync(c->h_buf, c->alog, cnt * sizeof(double), hipMemcpyDeviceToHost, s));
     NUGPR_HIP(hipMemcpyAsync(c->h_buf + cnt, c->blog, cnt * sizeof(double), hipMemcpyDeviceToHost, s));
@@ -356,6 +370,14 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
     if (hs->indef[col]) indefinite = true;
   }
   if (max_it_used) *max_it_used = mx;
+  if (extras) {
+    for (int col = 0; col < T; ++col) {
+      double acc = 0.0;
+      for (int b = 0; b < nb; ++b) acc += hdot[(size_t)b * MAX_COLS + col];      // block order, as run_dot_col
+      extras->bx[col] = acc;
+      extras->rho0[col] = hs->rho0[col];
+    }
+  }
   if (alpha || beta) {
     const double* ha = c->h_buf;
     for (int j = 0; j < max_iter; ++j)
@@ -369,9 +391,9 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
 }
 
 int run_pcg(nugpr_ctx* c, const void* B, void* X, int T, int32_t* iters, double* alpha, double* beta,
-            int* max_it_used, hipStream_t s) {
-  if (c->acc64) return pcg_t<double>(c, (const double*)B, (double*)X, T, iters, alpha, beta, max_it_used, s);
-  return pcg_t<float>(c, (const float*)B, (float*)X, T, iters, alpha, beta, max_it_used, s);
+            int* max_it_used, hipStream_t s, PcgExtras* extras) {
+  if (c->acc64) return pcg_t<double>(c, (const double*)B, (double*)X, T, iters, alpha, beta, max_it_used, s, extras);
+  return pcg_t<float>(c, (const float*)B, (float*)X, T, iters, alpha, beta, max_it_used, s, extras);
 }
 
 }  // namespace nugpr
