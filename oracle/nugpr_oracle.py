@@ -27,6 +27,11 @@ What each function follows:
   adam_step           Adam update of Algorithm 1
   predict             posterior mean and variance, Section 2.1 "Posterior Forward
                       Formulae", with the approximated covariance in place of K_y
+  pade22_log, split_operator, pade_logdet
+                      the paper's own log-determinant: eq. (PQ) on the preconditioned
+                      operator of eq. (logdet), Q(A) s = z by plain CG
+  fd_forward_halving  eq. (numerical gradient) with the step halved until two
+                      consecutive quotients agree (Section 3.1, Algorithm 1's while loops)
 
 Readings where the paper is silent or garbled (each is pinned in the tests or
 listed as a reading in the design notes):
@@ -44,6 +49,12 @@ listed as a reading in the design notes):
     CG starts its Lanczos process at z;
   * CG stops per column on the relative recurrence residual
     ||r_c|| <= tol ||b_c||; a stopped column is frozen;
+  * forward differences: the initial step is a fraction of the hyperparameter
+    (Delta theta_i = rel_step * theta_i) and starts afresh for every gradient; two
+    consecutive quotients "agree" when |g - g_prev| <= threshold * |g| (relative: the
+    loss scales with n, an absolute threshold would not); after max_halvings
+    halvings the last quotient is taken; the gradient is then carried to
+    phi = log theta by the chain rule, where Adam acts as everywhere else here;
   * prediction: K_* is the exact kernel between training and test points (the
     paper approximates only the training covariance), K_** its prior variance
     alpha (latent function, no noise term), the solves go through the same
@@ -332,11 +343,22 @@ class Factor:
 # --------------------------------------------------------------------------
 # O9, O11: the loss (eq. (loss function))
 # --------------------------------------------------------------------------
-def mll(prob: Problem, fac: Factor, theta, tol, max_iter):
+def mll(prob: Problem, fac: Factor, theta, tol, max_iter, logdet="slq"):
     """Negative marginal log likelihood L(theta) with the theta_0 preconditioner.
 
+    logdet = "slq": Lanczos quadrature on the CG coefficients of the probe columns;
+    logdet = "pade": the paper's eq. (PQ) route (pade_logdet), y solved on its own.
     Returns dict(nll, quad, logdet, logdet_precond, iters, X, est)."""
     op = prob.operator(theta)
+    if logdet == "pade":
+        X, iters, _, _, conv = pcg(op, fac.apply, prob.y[:, None].copy(), tol, max_iter)
+        quad = float(prob.y @ X[:, 0])
+        ld, est, it2 = pade_logdet(prob, fac, theta, tol, max_iter)
+        nll = 0.5 * (quad + ld + prob.n * np.log(2.0 * np.pi))
+        return dict(nll=nll, quad=quad, logdet=ld, logdet_precond=fac.logdetM,
+                    iters=np.concatenate([iters, it2]), X=X, est=est, converged=conv)
+    if logdet != "slq":
+        raise ValueError(logdet)
     X, iters, alphas, betas, conv = pcg(op, fac.apply, fac.B, tol, max_iter)
     quad = float(prob.y @ X[:, 0])
     t = prob.probes.shape[1]
@@ -344,6 +366,49 @@ def mll(prob: Problem, fac: Factor, theta, tol, max_iter):
     nll = 0.5 * (quad + logdet + prob.n * np.log(2.0 * np.pi))
     return dict(nll=nll, quad=quad, logdet=logdet, logdet_precond=fac.logdetM,
                 iters=iters, X=X, est=est, converged=conv, alphas=alphas, betas=betas)
+
+
+# --------------------------------------------------------------------------
+# The paper's own log-determinant: 2-2 Pade form of the logarithm, eq. (PQ),
+# on the preconditioned operator of eq. (logdet)
+# --------------------------------------------------------------------------
+def pade22_log(x):
+    """P(x) / Q(x) of eq. (PQ): (3 x^2 - 3) / (x^2 + 4 x + 1)."""
+    return (3.0 * x * x - 3.0) / (x * x + 4.0 * x + 1.0)
+
+
+def split_operator(apply_op, Ls, offsets):
+    """D -> R^-T K' R^-1 D with R = blockdiag(L_i^T), i.e. L^-1 K' L^-T D (eq. (RKR))."""
+    def apply(D):
+        U = np.empty_like(D)
+        for i, L in enumerate(Ls):
+            si = slice(offsets[i], offsets[i + 1])
+            U[si] = solve_triangular(L, D[si], lower=True, trans="T")       # R^-1 D
+        V = apply_op(U)
+        out = np.empty_like(D)
+        for i, L in enumerate(Ls):
+            si = slice(offsets[i], offsets[i + 1])
+            out[si] = solve_triangular(L, V[si], lower=True)                # R^-T (.)
+        return out
+    return apply
+
+
+def pade_logdet(prob: Problem, fac: Factor, theta, tol, max_iter):
+    """log|K'| = 2 sum log|R_i| + (1/t) sum_i z_i^T P(A) Q(A)^-1 z_i, A = R^-T K' R^-1
+    (eqs. (logdet), (PQ)): Q(A) s_i = z_i by batched CG without a further
+    preconditioner (A is the preconditioned system), then P(A) s_i and the dot with z_i.
+    Returns (logdet, per-probe estimates, CG iteration counts)."""
+    A = split_operator(prob.operator(theta), fac.Ls, prob.offsets)
+    Z = np.asarray(prob.probes, dtype=np.float64)
+
+    def Qop(D):
+        AD = A(D)
+        return A(AD) + 4.0 * AD + D
+
+    S, iters, _, _, _ = pcg(Qop, lambda R: R.copy(), Z, tol, max_iter)
+    PS = 3.0 * (A(A(S)) - S)
+    est = np.sum(Z * PS, axis=0)
+    return fac.logdetM + float(np.mean(est)), est, iters
 
 
 # --------------------------------------------------------------------------
@@ -385,6 +450,53 @@ def train_step(prob: Problem, log_theta, m, v, step, h, tol, max_iter, lr=0.05,
     phi, m, v, step = adam_step(np.asarray(log_theta, dtype=np.float64), g, m, v, step,
                                 lr, beta1, beta2, eps)
     return phi, m, v, step, nll0, g
+
+
+# --------------------------------------------------------------------------
+# The paper's own gradient: forward differences whose step is halved until two
+# consecutive quotients agree (Section 3.1; the while loops of Algorithm 1)
+# --------------------------------------------------------------------------
+def fd_forward_halving(loss, theta, L0, rel_step, threshold, max_halvings):
+    """g_i = (L(theta + Delta e_i) - L0) / Delta on the raw hyperparameters.
+
+    Delta starts at rel_step * theta_i; it is halved and the quotient recomputed until
+    |g - g_prev| <= threshold * |g| or max_halvings halvings were made (at least one
+    halving always happens: the first quotient has nothing to be compared with).
+    Returns (g, halvings[i])."""
+    theta = np.asarray(theta, dtype=np.float64)
+    g = np.empty_like(theta)
+    halvings = np.zeros(theta.shape[0], dtype=np.int64)
+    for i in range(theta.shape[0]):
+        delta = rel_step * theta[i]
+        tp = theta.copy()
+        tp[i] = theta[i] + delta
+        g_prev = (loss(tp) - L0) / delta
+        gi = g_prev
+        for k in range(max_halvings):
+            delta *= 0.5
+            tp[i] = theta[i] + delta
+            gi = (loss(tp) - L0) / delta
+            halvings[i] = k + 1
+            if abs(gi - g_prev) <= threshold * abs(gi):
+                break
+            g_prev = gi
+        g[i] = gi
+    return g, halvings
+
+
+def train_step_forward(prob: Problem, log_theta, m, v, step, rel_step, threshold, max_halvings,
+                       tol, max_iter, lr=0.05, beta1=0.9, beta2=0.999, eps=1e-8, logdet="slq"):
+    """Algorithm 1's loop body with its own gradient: factor at theta_0, base loss,
+    forward differences with halving on theta, chain rule to phi = log theta, Adam."""
+    theta0 = np.exp(np.asarray(log_theta, dtype=np.float64))
+    fac = Factor(prob, theta0)
+    loss = lambda th: mll(prob, fac, th, tol, max_iter, logdet=logdet)["nll"]
+    nll0 = loss(theta0)
+    g_theta, halvings = fd_forward_halving(loss, theta0, nll0, rel_step, threshold, max_halvings)
+    g = theta0 * g_theta
+    phi, m, v, step = adam_step(np.asarray(log_theta, dtype=np.float64), g, m, v, step,
+                                lr, beta1, beta2, eps)
+    return phi, m, v, step, nll0, g, halvings
 
 
 # --------------------------------------------------------------------------

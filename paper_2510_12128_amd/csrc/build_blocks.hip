@@ -364,7 +364,9 @@ int launch_setup(nugpr_ctx* c, const float* user_reps, const float* user_W, hipS
       }
   };
   std::vector<BuildItem> pd, pc;
-  for (int i = 0; i < L.nc; ++i) panel_items(L.cl[i].nt, L.cl[i].koff, L.cl[i].prow, L.cl[i].b, L.cl[i].ld, pd);
+  // last cluster first: the blocks written last are the ones the product reads first (cluster 0 upwards),
+  // while they are still in the memory-side cache
+  for (int i = L.nc - 1; i >= 0; --i) panel_items(L.cl[i].nt, L.cl[i].koff, L.cl[i].prow, L.cl[i].b, L.cl[i].ld, pd);
   panel_items((uint32_t)(L.ldc / TILE), 0, 0, (uint32_t)L.ncr, (uint32_t)L.ldc, pc);
   c->n_pan_diag = (int)pd.size();
   c->n_pan_c = (int)pc.size();
@@ -421,8 +423,8 @@ int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s) {
   const size_t lds = (size_t)4 * a.kd * 16 * sizeof(double);      // row operands of one tile
 #define NUGPR_TILES(NKS)                                                                                         \
   do {                                                                                                           \
-    hipLaunchKernelGGL((k_build_tile<false, NKS>), gd, blk, lds, s, a, c->d_pan_diag, c->Xs, c->Xn, c->Kd, 1);   \
     hipLaunchKernelGGL((k_build_tile<true, NKS>), gc, blk, lds, s, a, c->d_pan_c, c->Rs, c->Rn, c->C, L.r);      \
+    hipLaunchKernelGGL((k_build_tile<false, NKS>), gd, blk, lds, s, a, c->d_pan_diag, c->Xs, c->Xn, c->Kd, 1);   \
   } while (0)
   switch (a.kd / 4) {        // the dimensions of the usual workloads get their own instantiation
     case 1: NUGPR_TILES(1); break;

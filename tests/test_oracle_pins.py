@@ -534,6 +534,102 @@ def test_rmse_definition():
     assert abs(O.rmse([1.0, 2.0, 4.0], [1.0, 0.0, 0.0]) - math.sqrt((0 + 4 + 16) / 3)) < 1e-15
 
 
+# ---------------------------------------------------------------- Pade log-determinant
+def test_pade22_is_the_2_2_approximant_of_the_logarithm():
+    # P(1+u) - log(1+u) Q(1+u) = O(u^5): exact polynomial arithmetic on the series of log(1+u)
+    from fractions import Fraction as F
+    logser = [F(0), F(1), F(-1, 2), F(1, 3), F(-1, 4)]                  # up to u^4
+    Q = [F(6), F(6), F(1)]                                               # (1+u)^2 + 4(1+u) + 1
+    P = [F(0), F(6), F(3)]                                               # 3(1+u)^2 - 3
+    prod = [F(0)] * 7
+    for i, a in enumerate(logser):
+        for j, b in enumerate(Q):
+            prod[i + j] += a * b
+    for k in range(5):
+        assert prod[k] == (P[k] if k < len(P) else 0), k
+    # the coefficients of the oracle's function are those of P and Q
+    for u in (-0.3, 0.0, 0.2, 0.7):
+        x = 1.0 + u
+        assert abs(O.pade22_log(x) - (6 * u + 3 * u * u) / (6 + 6 * u + u * u)) < 1e-15
+    # antisymmetry log(1/x) = -log(x) is inherited exactly; error against the logarithm
+    xs = np.linspace(0.5, 2.0, 301)
+    np.testing.assert_allclose(O.pade22_log(1.0 / xs), -O.pade22_log(xs), rtol=0, atol=1e-14)
+    err = np.abs(O.pade22_log(xs) - np.log(xs))
+    # leading error term of the approximant: log(x)^5 / 180
+    assert err.max() < 9e-4 and np.all(err <= np.abs(np.log(xs)) ** 5 / 175.0 + 1e-15)
+
+
+def test_split_operator_and_pade_logdet_against_dense_eigenvalues():
+    # Hadamard probes make the trace estimate exact, so the whole route must equal
+    # log det M + sum_i pade(lambda_i) with lambda_i from a dense eigen-solve of L^-1 K' L^-T
+    w = I.make_small(n_clusters=2, sizes=[10, 6], d=2, rank=2, t=2, seed=31, ell=1.3, spacing=3.0, sigma_blob=0.4)
+    H = I.hadamard_probes(16)
+    prob = O.Problem(w.X, w.y, w.offsets, H, w.rank)
+    theta0 = w.theta
+    theta = w.theta * np.array([1.1, 0.95, 1.2, 0.9])
+    fac = O.Factor(prob, theta0)
+    Kp = prob.dense(theta)
+    Lb = np.zeros_like(Kp)
+    for i, L in enumerate(fac.Ls):
+        Lb[w.offsets[i]:w.offsets[i + 1], w.offsets[i]:w.offsets[i + 1]] = L
+    Ah = np.linalg.inv(Lb) @ Kp @ np.linalg.inv(Lb).T
+    A = O.split_operator(prob.operator(theta), fac.Ls, prob.offsets)
+    np.testing.assert_allclose(A(np.eye(16)), Ah, rtol=1e-10, atol=1e-12)
+    lam = np.linalg.eigvalsh(0.5 * (Ah + Ah.T))
+    ld, est, iters = O.pade_logdet(prob, fac, theta, 1e-13, 200)
+    want = 2.0 * np.sum(np.log(np.diag(Lb))) + np.sum(O.pade22_log(lam))
+    assert abs(ld - want) < 1e-9 * max(1.0, abs(want))
+    # and within the approximant's own error of the true log-determinant
+    exact = np.linalg.slogdet(Kp)[1]
+    bound = np.sum(np.abs(np.log(lam)) ** 5) / 175.0
+    assert abs(ld - exact) <= bound + 1e-9
+    # the loss assembled around it
+    out = O.mll(prob, fac, theta, 1e-13, 200, logdet="pade")
+    y = prob.y
+    assert abs(out["quad"] - y @ np.linalg.solve(Kp, y)) < 1e-9
+    assert abs(out["nll"] - 0.5 * (out["quad"] + ld + 16 * math.log(2 * math.pi))) < 1e-12
+    with pytest.raises(ValueError):
+        O.mll(prob, fac, theta, 1e-6, 10, logdet="taylor")
+
+
+# ---------------------------------------------------------------- forward differences with halving
+def test_forward_differences_with_halving_on_closed_forms():
+    # L(theta) = a theta_0^2 + b theta_1: the forward quotient is 2 a theta_0 + a Delta exactly,
+    # consecutive quotients differ by a Delta_new, and the linear direction stops after one halving
+    a, b = 3.0, -2.0
+    loss = lambda th: a * th[0] ** 2 + b * th[1]
+    theta = np.array([2.0, 5.0])
+    L0 = loss(theta)
+    rel, thr = 0.1, 1e-2
+    g, halv = O.fd_forward_halving(loss, theta, L0, rel, thr, 20)
+    # by hand: Delta_k = 0.2 / 2^k, g_k = 12 + 3 Delta_k, stop at the first k >= 1 with 3 Delta_k <= thr g_k
+    k = 1
+    while 3.0 * 0.2 / 2 ** k > thr * (12.0 + 3.0 * 0.2 / 2 ** k):
+        k += 1
+    assert halv[0] == k and abs(g[0] - (12.0 + 3.0 * 0.2 / 2 ** k)) < 1e-12
+    assert halv[1] == 1 and abs(g[1] - b) < 1e-12
+    # cap: with a zero threshold the quadratic direction runs into max_halvings and returns the last quotient
+    g2, halv2 = O.fd_forward_halving(loss, theta, L0, rel, 0.0, 4)
+    assert halv2[0] == 4 and abs(g2[0] - (12.0 + 3.0 * 0.2 / 16)) < 1e-12
+    assert halv2[1] == 1                     # exact agreement meets "<=" even at threshold 0
+
+
+def test_forward_train_step_agrees_with_the_central_gradient_and_applies_adam():
+    w = I.make_small(n_clusters=2, sizes=[9, 12], d=2, rank=2, t=4, seed=19)
+    H = I.hadamard_probes(32)[:21]          # any fixed probes: both gradients see the same function
+    prob = O.Problem(w.X, w.y, w.offsets, H[:, :4], w.rank)
+    phi = np.log(w.theta)
+    p = phi.shape[0]
+    out = O.train_step_forward(prob, phi, np.zeros(p), np.zeros(p), 0, 1e-3, 1e-2, 6, 1e-12, 200)
+    phi1, m1, v1, step1, nll0, g, halv = out
+    fac = O.Factor(prob, w.theta)
+    gc = O.fd_gradient(prob, fac, phi, 1e-4, 1e-12, 200)
+    assert np.linalg.norm(g - gc) <= 5e-3 * np.linalg.norm(gc)      # same derivative, O(Delta) apart
+    ref = O.adam_step(phi, g, np.zeros(p), np.zeros(p), 0)
+    np.testing.assert_allclose(phi1, ref[0], rtol=0, atol=1e-15)
+    assert step1 == 1 and np.all(halv >= 1) and abs(nll0 - O.mll(prob, fac, w.theta, 1e-12, 200)["nll"]) < 1e-9
+
+
 def test_input_generators_are_seeded_and_shaped():
     a = I.make_config("C1")
     b = I.make_config("C1")
