@@ -71,6 +71,19 @@ enum {
                                   output scale or the noise reuse them through the linear relations of
                                   Section 3.3 (eqs. (linear2), (linear3)): the operator becomes
                                   s K_0 + shift I with s = alpha / alpha_0. */
+  ,
+  NUGPR_LOGDET_PADE = 8u       /* log-determinant by the paper's own route (Section 3.1, eqs. (PQ), (logdet)):
+                                  Q(A) s_i = z_i by batched CG on A = R^-T K' R^-1 (two applications of A per
+                                  iteration), then z_i^T P(A) s_i; y is solved on its own.  While the stored
+                                  blocks are the factored ones, A is applied through eqs. (linear1)-(linear3)
+                                  without streaming K_diag (unless NUGPR_NO_SHORTCUTS).  Default: stochastic
+                                  Lanczos quadrature on the CG coefficients of K' x = L z. */
+  ,
+  NUGPR_FD_FORWARD = 16u       /* nugpr_train_step takes the paper's own gradient (Section 3.1, the while
+                                  loops of Algorithm 1): forward differences on theta_i with the step
+                                  fd_step * theta_i halved until two consecutive quotients agree to
+                                  fd_threshold (relative) or fd_max_halvings halvings were made; the result
+                                  is carried to log(theta) by the chain rule.  Default: central differences. */
 };
 
 /* Problem description (Section 2.1 notation; Section 3.3 for representatives). */
@@ -101,7 +114,12 @@ typedef struct {
   double fd_step;      /* h of the central differences on log(theta)                   */
   double lr;           /* Adam learning rate (paper: 0.05)                             */
   double beta1, beta2, eps;  /* Adam moments / epsilon (0 selects 0.9, 0.999, 1e-8)    */
-  uint32_t flags;      /* NUGPR_ISOTROPIC | NUGPR_ACC_FP32 | NUGPR_NO_SHORTCUTS, or 0   */
+  uint32_t flags;      /* NUGPR_ISOTROPIC | NUGPR_ACC_FP32 | NUGPR_NO_SHORTCUTS |
+                          NUGPR_LOGDET_PADE | NUGPR_FD_FORWARD, or 0                   */
+  int32_t fd_max_halvings;   /* NUGPR_FD_FORWARD: cap on the halvings per hyperparameter,
+                                1..30 (0 selects 8)                                    */
+  double fd_threshold; /* NUGPR_FD_FORWARD: stop when |g - g_prev| <= fd_threshold |g|
+                          (0 selects 1e-2)                                             */
 } nugpr_params;
 
 /* Result of one loss evaluation, eq. (loss function): nll = (quad + logdet + n log 2pi)/2. */
@@ -155,6 +173,13 @@ int nugpr_matvec(nugpr_ctx* ctx, const float* D, float* Q, int32_t ncols, void* 
  * R, Z: DEVICE n x ncols, must not alias. */
 int nugpr_precond_apply(nugpr_ctx* ctx, const float* R, float* Z, int32_t ncols, void* stream);
 
+/* out = A D with A = R^-T K' R^-1 = L^-1 K' L^-T, the split-preconditioned operator of
+ * eq. (RKR) on which the Pade log-determinant works (Section 3.1).  While the stored blocks are
+ * the ones the factor was computed from (no nugpr_build_blocks since nugpr_precond_factor), the
+ * block-diagonal part is applied as the identity (eq. (linear1)) instead of being streamed,
+ * unless NUGPR_NO_SHORTCUTS.  D, out: DEVICE n x ncols row-major fp32, must not alias. */
+int nugpr_split_apply(nugpr_ctx* ctx, const float* D, float* out, int32_t ncols, void* stream);
+
 /* Batched PCG (Sections 3.1-3.2): solves K' X = B for ncols columns in lock step
  * from X = 0, preconditioned by the stored factor, until every column meets the
  * tolerance or max_iter.  B, Xout: DEVICE n x ncols.  iters: HOST ncols (iterations
@@ -176,7 +201,8 @@ int nugpr_mll(nugpr_ctx* ctx, const double* theta /*HOST*/, nugpr_mll_result* re
  *   g_i = (L(phi + h e_i) - L(phi - h e_i)) / (2h)
  * all with the theta_0 preconditioner and the same probes (the output-scale and noise
  * differences on the theta_0 blocks, see NUGPR_NO_SHORTCUTS), then a bias-corrected
- * Adam update of phi.  log_theta, adam_m, adam_v: HOST, p entries, in/out
+ * Adam update of phi.  With NUGPR_FD_FORWARD the differences are the forward ones with step
+ * halving described at that flag.  log_theta, adam_m, adam_v: HOST, p entries, in/out
  * (p = d+2, or 3 with NUGPR_ISOTROPIC); *step in/out; *nll0 and grad (p) out. */
 int nugpr_train_step(nugpr_ctx* ctx, double* log_theta, double* adam_m, double* adam_v,
                      int64_t* step, double* nll0, double* grad, void* stream);
@@ -205,6 +231,10 @@ int nugpr_rmse(const double* mean, const double* ytest, int64_t m, double* out);
 /* Confidence region of Section 2.1: lo = mean - 2 s, hi = mean + 2 s with
  * s = sqrt(max(var, 0)).  All HOST arrays of m doubles; lo / hi may alias nothing else. */
 int nugpr_confidence_band(const double* mean, const double* var, int64_t m, double* lo, double* hi);
+
+/* Halvings each hyperparameter's forward difference took in the last nugpr_train_step of a
+ * NUGPR_FD_FORWARD context (Section 3.1): out is HOST, p entries; zeros before the first step. */
+int nugpr_fd_halvings(const nugpr_ctx* ctx, int32_t* out /*HOST*/);
 
 /* Copies one stored matrix to a dense row-major DEVICE array `dst` with leading
  * dimension `ld` (for verification).  what: 0 = K_ii (b_i x b_i), 1 = L_i lower

@@ -20,6 +20,8 @@ NUGPR_NOT_CONVERGED = 3
 NUGPR_ISOTROPIC = 1
 NUGPR_ACC_FP32 = 2
 NUGPR_NO_SHORTCUTS = 4
+NUGPR_LOGDET_PADE = 8
+NUGPR_FD_FORWARD = 16
 
 EXPORT_K, EXPORT_L, EXPORT_LINV, EXPORT_C, EXPORT_W, EXPORT_B, EXPORT_REPS = range(7)
 
@@ -39,7 +41,8 @@ class Problem(C.Structure):
 
 class Params(C.Structure):
     _fields_ = [("tol", C.c_double), ("max_iter", C.c_int32), ("fd_step", C.c_double), ("lr", C.c_double),
-                ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double), ("flags", C.c_uint32)]
+                ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double), ("flags", C.c_uint32),
+                ("fd_max_halvings", C.c_int32), ("fd_threshold", C.c_double)]
 
 
 class MllResult(C.Structure):
@@ -79,6 +82,8 @@ def load_library():
     lib.nugpr_precond_factor.argtypes = [vp, dp, ip, vp]
     lib.nugpr_matvec.restype = C.c_int
     lib.nugpr_matvec.argtypes = [vp, vp, vp, C.c_int32, vp]
+    lib.nugpr_split_apply.restype = C.c_int
+    lib.nugpr_split_apply.argtypes = [vp, vp, vp, C.c_int32, vp]
     lib.nugpr_precond_apply.restype = C.c_int
     lib.nugpr_precond_apply.argtypes = [vp, vp, vp, C.c_int32, vp]
     lib.nugpr_pcg_solve.restype = C.c_int
@@ -93,6 +98,8 @@ def load_library():
     lib.nugpr_rmse.argtypes = [dp, dp, C.c_int64, dp]
     lib.nugpr_confidence_band.restype = C.c_int
     lib.nugpr_confidence_band.argtypes = [dp, dp, C.c_int64, dp, dp]
+    lib.nugpr_fd_halvings.restype = C.c_int
+    lib.nugpr_fd_halvings.argtypes = [vp, ip]
     lib.nugpr_export.restype = C.c_int
     lib.nugpr_export.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_int64, vp]
     lib.nugpr_num_hyper.restype = C.c_int32
@@ -155,7 +162,8 @@ class Context:
     array; reps / W optional.  Methods mirror the C entry points one to one."""
 
     def __init__(self, X, y, offsets, probes, rank, tol=1e-6, max_iter=100, fd_step=1e-3, lr=0.05,
-                 isotropic=False, reps=None, W=None, device="cuda:0", acc_fp32=False, no_shortcuts=False):
+                 isotropic=False, reps=None, W=None, device="cuda:0", acc_fp32=False, no_shortcuts=False,
+                 logdet_pade=False, fd_forward=False, fd_threshold=0.0, fd_max_halvings=0):
         import torch
         self.torch = torch
         self.lib = load_library()
@@ -192,7 +200,9 @@ class Context:
         pb.workspace_bytes = self.workspace_bytes
         pr = Params(tol=tol, max_iter=max_iter, fd_step=fd_step, lr=lr, beta1=0.0, beta2=0.0, eps=0.0,
                     flags=(NUGPR_ISOTROPIC if isotropic else 0) | (NUGPR_ACC_FP32 if acc_fp32 else 0)
-                    | (NUGPR_NO_SHORTCUTS if no_shortcuts else 0))
+                    | (NUGPR_NO_SHORTCUTS if no_shortcuts else 0) | (NUGPR_LOGDET_PADE if logdet_pade else 0)
+                    | (NUGPR_FD_FORWARD if fd_forward else 0),
+                    fd_max_halvings=int(fd_max_halvings), fd_threshold=float(fd_threshold))
         self.params = pr
         self.max_iter = int(max_iter)
         h = C.c_void_p()
@@ -242,6 +252,12 @@ class Context:
         Q = self.torch.empty_like(D)
         _check(self.lib.nugpr_matvec(self.handle, D.data_ptr(), Q.data_ptr(), D.shape[1], self._stream()))
         return Q
+
+    def nugpr_split_apply(self, D):
+        D = self._block(D)
+        out = self.torch.empty_like(D)
+        _check(self.lib.nugpr_split_apply(self.handle, D.data_ptr(), out.data_ptr(), D.shape[1], self._stream()))
+        return out
 
     def nugpr_precond_apply(self, R):
         R = self._block(R)
@@ -293,6 +309,11 @@ class Context:
         code = _check(self.lib.nugpr_predict(self.handle, _dptr(th), Xt.data_ptr() if m else None, m, _dptr(mean),
                                              _dptr(var) if variance else None, C.byref(mx), self._stream()))
         return dict(code=code, mean=mean, var=var, max_iters_used=mx.value)
+
+    def nugpr_fd_halvings(self):
+        out = np.zeros(self.p, dtype=np.int32)
+        _check(self.lib.nugpr_fd_halvings(self.handle, out.ctypes.data_as(C.POINTER(C.c_int32))))
+        return out
 
     def nugpr_matvec_into(self, D, Q):
         """nugpr_matvec on caller-held device tensors (no allocation; used for timing)."""

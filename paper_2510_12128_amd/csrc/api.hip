@@ -75,7 +75,7 @@ void arrange_for_dies(std::vector<StripItem>& v) {
 }
 
 struct Tables {
-  std::vector<StripItem> WtD, KC, WP, lowG, upG, lowL;
+  std::vector<StripItem> WtD, KC, Conly, WP, lowG, upG, lowL;
 };
 
 void build_tables(const Layout& L, Tables& t) {
@@ -123,6 +123,8 @@ void build_tables(const Layout& L, Tables& t) {
   sort_longest_first(t.upG);
   sort_longest_first(t.lowL);
   arrange_for_dies(t.KC);
+  for (const StripItem& it : t.KC)
+    if (it.port == 1) t.Conly.push_back(it);       // the coupling product on its own (eq. (linear1) route)
   arrange_for_dies(t.lowG);
   arrange_for_dies(t.upG);
   arrange_for_dies(t.lowL);
@@ -158,6 +160,10 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   if (!(prm->tol > 0.0) || !(prm->tol < 1.0)) { set_error("tol must be in (0, 1)"); return NUGPR_ERR_INVALID; }
   if (prm->max_iter < 1 || prm->max_iter > MAX_ITER_CAP) { set_error("max_iter must be 1..4096"); return NUGPR_ERR_INVALID; }
   if (!(prm->fd_step > 0.0) || !(prm->lr >= 0.0)) { set_error("fd_step must be > 0 and lr >= 0"); return NUGPR_ERR_INVALID; }
+  if (prm->fd_max_halvings < 0 || prm->fd_max_halvings > 30 || !(prm->fd_threshold >= 0.0)) {
+    set_error("fd_max_halvings must be 0..30 and fd_threshold >= 0");
+    return NUGPR_ERR_INVALID;
+  }
   Layout L;
   int rc = plan_layout(pb, prm->flags, L);
   if (rc) return rc;
@@ -179,6 +185,9 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   if (c->params.beta1 == 0.0) c->params.beta1 = 0.9;
   if (c->params.beta2 == 0.0) c->params.beta2 = 0.999;
   if (c->params.eps == 0.0) c->params.eps = 1e-8;
+  if (c->params.fd_max_halvings == 0) c->params.fd_max_halvings = 8;
+  if (c->params.fd_threshold == 0.0) c->params.fd_threshold = 1e-2;
+  c->fd_halvings.assign(L.p, 0);
   c->ws = static_cast<char*>(pb->workspace);
   c->X = pb->X; c->y = pb->y; c->probes = pb->probes;
   char* w = c->ws;
@@ -204,6 +213,7 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   c->Uv = w + L.o_U;
   c->x0 = w + L.o_x0;
   c->Z0v = w + L.o_Z0;
+  c->Pv = w + L.o_P;
   c->Spart = w + L.o_Spart;
   c->Ppart = w + L.o_Ppart;
   c->dotpart = reinterpret_cast<double*>(w + L.o_dot);
@@ -227,11 +237,12 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   if (e != hipSuccess) return fail(hip_fail(e, "upload cluster table"));
   Tables t;
   build_tables(L, t);
-  const size_t total_items = t.WtD.size() + t.KC.size() + t.WP.size() + t.lowG.size() + t.upG.size() + t.lowL.size();
+  const size_t total_items = t.WtD.size() + t.KC.size() + t.Conly.size() + t.WP.size() + t.lowG.size() + t.upG.size() + t.lowL.size();
   if (total_items * sizeof(StripItem) > L.items_bytes) { set_error("internal: strip table overflow"); return fail(NUGPR_ERR_INVALID); }
   StripItem* cur = reinterpret_cast<StripItem*>(w + L.o_items);
   if ((rc = upload_table(t.WtD, cur, c->tab_WtD, s))) return fail(rc);
   if ((rc = upload_table(t.KC, cur, c->tab_KC, s))) return fail(rc);
+  if ((rc = upload_table(t.Conly, cur, c->tab_C, s))) return fail(rc);
   if ((rc = upload_table(t.WP, cur, c->tab_WP, s))) return fail(rc);
   if ((rc = upload_table(t.lowG, cur, c->tab_lowG, s))) return fail(rc);
   if ((rc = upload_table(t.upG, cur, c->tab_upG, s))) return fail(rc);
@@ -354,6 +365,24 @@ int nugpr_matvec(nugpr_ctx* c, const float* D, float* Q, int32_t ncols, void* st
   return from_internal(c, c->Qv, Q, cnt, s);
 }
 
+int nugpr_split_apply(nugpr_ctx* c, const float* D, float* out, int32_t ncols, void* stream) {
+  int rc = check_block_args(c, D, out, ncols);
+  if (rc) return rc;
+  if (!c->built || !c->factored) { set_error("split_apply needs build_blocks and precond_factor first"); return NUGPR_ERR_STATE; }
+  hipStream_t s = as_stream(stream);
+  const int64_t cnt = c->L.n * ncols;
+  if (!c->acc64) {
+    // fp32 blocks are the internal type: stage through R / Q, which the operator does not use
+    NUGPR_HIP(hipMemcpyAsync(c->Rv, D, (size_t)cnt * sizeof(float), hipMemcpyDeviceToDevice, s));
+    if ((rc = run_split_op(c, c->Rv, c->Qv, ncols, s))) return rc;
+    NUGPR_HIP(hipMemcpyAsync(out, c->Qv, (size_t)cnt * sizeof(float), hipMemcpyDeviceToDevice, s));
+    return NUGPR_OK;
+  }
+  if ((rc = to_internal(c, D, c->Rv, cnt, s))) return rc;
+  if ((rc = run_split_op(c, c->Rv, c->Qv, ncols, s))) return rc;
+  return from_internal(c, c->Qv, out, cnt, s);
+}
+
 int nugpr_precond_apply(nugpr_ctx* c, const float* R, float* Z, int32_t ncols, void* stream) {
   int rc = check_block_args(c, R, Z, ncols);
   if (rc) return rc;
@@ -404,6 +433,44 @@ static int set_operator(nugpr_ctx* c, const double* theta, bool allow_reuse, hip
   return NUGPR_OK;
 }
 
+// The loss with the paper's own log-determinant (Section 3.1): y solved by the left-preconditioned CG
+// as one column; Q(A) s_i = z_i by plain batched CG on the split-preconditioned A (eq. (PQ)), then
+// z_i^T P(A) s_i = 3 z_i^T (A^2 s_i - s_i), averaged over the probes and completed by log det M (eq. (logdet)).
+static int mll_pade(nugpr_ctx* c, nugpr_mll_result* res, hipStream_t s) {
+  const Layout& L = c->L;
+  const int T = L.T;
+  int rc = to_internal(c, c->y, c->x0, L.n, s);               // y as an n x 1 block
+  if (rc) return rc;
+  PcgExtras ex;
+  int mx = 0, mx2 = 0;
+  rc = run_pcg(c, c->x0, c->Xv, 1, nullptr, nullptr, nullptr, &mx, s, &ex);
+  if (rc < 0) return rc;
+  res->max_iters_used = mx;
+  res->status = rc;
+  if (rc == NUGPR_INDEFINITE) return rc;
+  res->quad = ex.bx[0];
+  int worst = rc;
+  double est = 0.0;
+  if (L.t > 0) {
+    rc = run_pcg(c, c->Pv, c->Xv, T, nullptr, nullptr, nullptr, &mx2, s, nullptr, PCG_PADE_Q);
+    if (rc < 0) return rc;
+    res->max_iters_used = std::max(mx, mx2);
+    if (rc == NUGPR_INDEFINITE) { res->status = rc; return rc; }
+    worst = std::max(worst, rc);
+    int rc2;
+    if ((rc2 = run_split_op(c, c->Xv, c->Zv, T, s))) return rc2;           // A s
+    if ((rc2 = run_split_op(c, c->Zv, c->Qv, T, s))) return rc2;           // A^2 s
+    double zaas[MAX_COLS], zs[MAX_COLS];
+    if ((rc2 = run_dot2(c, c->Pv, c->Qv, c->Pv, c->Xv, T, zaas, zs, s))) return rc2;
+    for (int col = 1; col < T; ++col) est += 3.0 * (zaas[col] - zs[col]);
+    est /= L.t;
+  }
+  res->status = worst;
+  res->logdet = c->logdetM + est;
+  res->nll = 0.5 * (res->quad + res->logdet + (double)L.n * std::log(2.0 * M_PI));
+  return worst;
+}
+
 static int mll_impl(nugpr_ctx* c, const double* theta, nugpr_mll_result* res, bool allow_reuse, void* stream) {
   if (!c || !res) { set_error("null argument"); return NUGPR_ERR_INVALID; }
   if (!c->factored) { set_error("mll needs precond_factor first"); return NUGPR_ERR_STATE; }
@@ -417,6 +484,7 @@ static int mll_impl(nugpr_ctx* c, const double* theta, nugpr_mll_result* res, bo
   if (!theta) { set_error("theta is null"); return NUGPR_ERR_INVALID; }
   int rc = set_operator(c, theta, allow_reuse, s);
   if (rc) return rc;
+  if (c->params.flags & NUGPR_LOGDET_PADE) return mll_pade(c, res, s);
   const int T = L.T, max_iter = c->params.max_iter;
   std::vector<int32_t> iters(T);
   std::vector<double> alpha((size_t)max_iter * T), beta((size_t)max_iter * T);
@@ -470,7 +538,31 @@ int nugpr_train_step(nugpr_ctx* c, double* log_theta, double* adam_m, double* ad
   if (rc < 0 || rc == NUGPR_INDEFINITE) return rc;
   worst = std::max(worst, rc);
   *nll0 = r0.nll;
-  for (int k = 0; k < p; ++k) {
+  const bool forward = (c->params.flags & NUGPR_FD_FORWARD) != 0;
+  for (int k = 0; forward && k < p; ++k) {
+    // Forward quotient on theta_i, step halved until two consecutive quotients agree (Section 3.1);
+    // the gradient with respect to log(theta_i) is theta_i times it.
+    const int i = k < 2 ? p - 2 + k : k - 2;          // alpha, sigma^2, then the lengthscales
+    const double t0 = theta[i];
+    double delta = h * t0, g_prev = 0.0, g = 0.0;
+    int halv = 0;
+    for (int e = 0; e <= c->params.fd_max_halvings; ++e) {
+      if (e > 0) delta *= 0.5;
+      nugpr_mll_result r1;
+      theta[i] = t0 + delta;
+      rc = mll_impl(c, theta.data(), &r1, true, stream);
+      theta[i] = t0;
+      if (rc < 0 || rc == NUGPR_INDEFINITE) return rc;
+      worst = std::max(worst, rc);
+      g = (r1.nll - r0.nll) / delta;
+      halv = e;
+      if (e > 0 && std::fabs(g - g_prev) <= c->params.fd_threshold * std::fabs(g)) break;
+      g_prev = g;
+    }
+    c->fd_halvings[i] = halv;
+    grad[i] = t0 * g;
+  }
+  for (int k = 0; !forward && k < p; ++k) {
     const int i = k < 2 ? p - 2 + k : k - 2;          // alpha, sigma^2, then the lengthscales
     nugpr_mll_result rp, rm;
     theta[i] = std::exp(log_theta[i] + h);
@@ -527,6 +619,12 @@ int nugpr_confidence_band(const double* mean, const double* var, int64_t m, doub
     lo[j] = mean[j] - 2.0 * sd;
     hi[j] = mean[j] + 2.0 * sd;
   }
+  return NUGPR_OK;
+}
+
+int nugpr_fd_halvings(const nugpr_ctx* c, int32_t* out) {
+  if (!c || !out) { set_error("null argument"); return NUGPR_ERR_INVALID; }
+  for (int i = 0; i < c->L.p; ++i) out[i] = c->fd_halvings[i];
   return NUGPR_OK;
 }
 

@@ -438,6 +438,7 @@ int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s) {
   c->op_scale = 1.0;
   c->op_shift = (double)c->diag_residual;
   c->built = true;
+  c->build_gen += 1;
   return NUGPR_OK;
 }
 

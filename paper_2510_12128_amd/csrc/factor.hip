@@ -368,11 +368,11 @@ int launch_factor(nugpr_ctx* c, hipStream_t s) {
   // right-hand sides B = [y | L Z]
   if (L.t > 0) {
     if (c->acc64)
-      hipLaunchKernelGGL((k_probes_to_block<double>), dim3(1024), dim3(256), 0, s, c->probes, (double*)c->Vv, (int64_t)L.n, L.t);
+      hipLaunchKernelGGL((k_probes_to_block<double>), dim3(1024), dim3(256), 0, s, c->probes, (double*)c->Pv, (int64_t)L.n, L.t);
     else
-      hipLaunchKernelGGL((k_probes_to_block<float>), dim3(1024), dim3(256), 0, s, c->probes, (float*)c->Vv, (int64_t)L.n, L.t);
+      hipLaunchKernelGGL((k_probes_to_block<float>), dim3(1024), dim3(256), 0, s, c->probes, (float*)c->Pv, (int64_t)L.n, L.t);
     StripPort p0{};
-    p0.A = c->Lf; p0.in = c->Vv; p0.out = c->Bv; p0.nin = 1;
+    p0.A = c->Lf; p0.in = c->Pv; p0.out = c->Bv; p0.nin = 1;
     int rc = launch_strip(c->tab_lowL, p0, p0, L.T, c->acc64, s);
     if (rc) return rc;
   }
@@ -384,6 +384,7 @@ int launch_factor(nugpr_ctx* c, hipStream_t s) {
   int rc = run_precond(c, c->Bv, c->Z0v, L.T, s);
   if (rc) return rc;
   c->z0_ready = true;
+  c->factor_gen = c->build_gen;
   return NUGPR_OK;
 }
 

@@ -114,6 +114,7 @@ int plan_layout(const nugpr_problem* pb, uint32_t flags, Layout& L) {
   L.o_U = take(cur, vec);
   L.o_x0 = take(cur, (size_t)L.n * sizeof(double));
   L.o_Z0 = take(cur, vec);
+  L.o_P = take(cur, vec);
   L.o_Spart = take(cur, (size_t)L.nsS * L.ncr * L.T * sizeof(double));
   L.o_Ppart = take(cur, (size_t)L.nsP * L.ncr * L.T * sizeof(double));
   L.o_dot = take(cur, (size_t)2 * L.n_dot_blocks * MAX_COLS * sizeof(double));
@@ -132,7 +133,7 @@ int plan_layout(const nugpr_problem* pb, uint32_t flags, Layout& L) {
     items += c.nt;                                       // W * P
     items += 3 * (size_t)c.nt;                           // tril(G), triu(G), tril(L)
   }
-  items += (size_t)(L.ldc / TILE) * L.nsP;               // C * S
+  items += 2 * (size_t)(L.ldc / TILE) * L.nsP;           // C * S, in the joint table and on its own
   L.items_bytes = items * sizeof(StripItem);
   L.o_items = take(cur, L.items_bytes);
   L.total = align_up(cur, 256);

@@ -130,7 +130,7 @@ struct Layout {
   size_t o_Spart = 0, o_Ppart = 0, o_dot = 0, o_state = 0, o_alog = 0, o_blog = 0;
   size_t o_theta = 0, o_logdet = 0, o_tiles = 0, o_items = 0;
   size_t o_Xs = 0, o_Xn = 0, o_Rs = 0, o_Rn = 0;
-  size_t o_x0 = 0, o_Z0 = 0;
+  size_t o_x0 = 0, o_Z0 = 0, o_P = 0;
   size_t items_bytes = 0;
   int n_dot_blocks = 0;
   int max_iter = 0;
@@ -161,6 +161,7 @@ struct nugpr_ctx {
   // sides; it depends on the factor only, so the factorisation computes it once
   void* Z0v = nullptr;
   bool z0_ready = false;
+  void* Pv = nullptr;                    // [0 | Z]: the probes as a vector block (column 0 empty)
   void* x0 = nullptr;                    // K'^-1 y of a prediction call (one column, internal type)
   bool acc64 = true;                     // arithmetic mode of the operator applications
   double *dotpart = nullptr, *alog = nullptr, *blog = nullptr, *d_theta = nullptr, *d_logdet = nullptr;
@@ -169,7 +170,7 @@ struct nugpr_ctx {
   nugpr::BuildItem* d_pan_diag = nullptr;    // work items of the K_ii assembly
   nugpr::BuildItem* d_pan_c = nullptr;       // work items of the coupling assembly
   int n_pan_diag = 0, n_pan_c = 0;
-  nugpr::StripTable tab_WtD, tab_KC, tab_WP, tab_lowG, tab_upG, tab_lowL;
+  nugpr::StripTable tab_WtD, tab_KC, tab_C, tab_WP, tab_lowG, tab_upG, tab_lowL;
   // optional event timing of the K_diag / C streaming launch
   bool prof_on = false;
   std::vector<hipEvent_t> prof_ev;       // start/stop pairs
@@ -184,6 +185,10 @@ struct nugpr_ctx {
   std::vector<double> theta_built;
   double op_scale = 1.0, op_shift = 0.0;
   bool built = false, factored = false;
+  // The stored blocks are the very ones the factor was computed from while build_gen == factor_gen:
+  // then Y K_diag Y^T = I for the stored K_diag and Y = L^-1 (eq. (linear1)).
+  uint64_t build_gen = 0, factor_gen = ~0ull;
+  std::vector<int32_t> fd_halvings;      // halvings per hyperparameter in the last forward-difference step
   double logdetM = 0.0;
 };
 
@@ -223,12 +228,21 @@ int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s);
 int run_precond(nugpr_ctx* c, const void* R, void* Z, int T, hipStream_t s);
 // What a loss evaluation needs besides the solution, fetched with the solve's last synchronisation:
 // <b_c, x_c> per column and rho_0 = <r_0, M^-1 r_0>.
+// Which system a batched CG run solves.
+enum PcgSystem {
+  PCG_KPRIME = 0,    // K' x = b, left-preconditioned with the block-Jacobi factor
+  PCG_PADE_Q = 1     // Q(A) s = z, A = Y K' Y^T the split-preconditioned operator; no further preconditioner
+};
 struct PcgExtras {
   double bx[MAX_COLS];
   double rho0[MAX_COLS];
 };
 int run_pcg(nugpr_ctx* c, const void* B, void* X, int T, int32_t* iters, double* alpha, double* beta,
-            int* max_it_used, hipStream_t s, PcgExtras* extras = nullptr);
+            int* max_it_used, hipStream_t s, PcgExtras* extras = nullptr, int system = PCG_KPRIME);
+// A D = Y K' Y^T D (eq. (RKR)); with the linear relations of eqs. (linear1)-(linear3) when they apply
+int run_split_op(nugpr_ctx* c, const void* D, void* out, int T, hipStream_t s);
+int run_dot2(nugpr_ctx* c, const void* A0, const void* B0, const void* A1, const void* B1, int T, double* out0,
+             double* out1, hipStream_t s);
 int run_dot_col(nugpr_ctx* c, const void* A, const void* B, int T, double* out_host, hipStream_t s);
 int to_internal(nugpr_ctx* c, const float* src, void* dst, int64_t count, hipStream_t s);
 int from_internal(nugpr_ctx* c, const void* src, float* dst, int64_t count, hipStream_t s);

@@ -258,6 +258,85 @@ int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s) {
   return launch_strip(c->tab_WP, w0, w0, T, c->acc64, s);
 }
 
+// out = a * x  (elementwise over a vector block)
+template <typename VT>
+__global__ void k_scaled_copy(VT* __restrict__ out, const VT* __restrict__ x, double a, int64_t count) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x)
+    out[i] = (VT)(a * (double)x[i]);
+}
+
+// q = q + 4 a + d: the last step of Q(A) d = A(A d) + 4 A d + d (eq. (PQ)), with a = A d and q = A a on entry
+template <typename VT>
+__global__ void k_pade_q_combine(VT* __restrict__ q, const VT* __restrict__ a, const VT* __restrict__ d, int64_t count) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x)
+    q[i] = (VT)((double)q[i] + 4.0 * (double)a[i] + (double)d[i]);
+}
+
+template <typename VT>
+static int scaled_copy(void* out, const void* x, double a, int64_t count, hipStream_t s) {
+  hipLaunchKernelGGL((k_scaled_copy<VT>), dim3(1024), dim3(256), 0, s, (VT*)out, (const VT*)x, a, count);
+  NUGPR_HIP(hipGetLastError());
+  return NUGPR_OK;
+}
+
+// Q += scale * W (C_offdiag (W^T D)): the low-rank part of the product on its own
+static int run_lowrank_accumulate(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s) {
+  const Layout& L = c->L;
+  int rc;
+  const uint64_t spart = (uint64_t)L.ncr * T, ppart = (uint64_t)L.ncr * T;
+  StripPort s0{};
+  s0.A = c->Wt; s0.in = D; s0.out = c->Spart; s0.nin = 1; s0.out_part_stride = spart;
+  if ((rc = launch_strip(c->tab_WtD, s0, s0, T, c->acc64, s))) return rc;
+  if (L.nsS > 1 && (rc = launch_sum_parts(c->Spart, c->Spart, (int64_t)spart, L.nsS, spart, c->acc64, s))) return rc;
+  StripPort k1{};
+  k1.A = c->C; k1.in = c->Spart; k1.nin = 1; k1.out = c->Ppart; k1.out_part_stride = ppart; k1.scale = c->op_scale;
+  if ((rc = launch_strip(c->tab_C, k1, k1, T, c->acc64, s))) return rc;
+  if (L.nsP > 1 && (rc = launch_sum_parts(c->Ppart, c->Ppart, (int64_t)ppart, L.nsP, ppart, c->acc64, s))) return rc;
+  StripPort w0{};
+  w0.A = c->Wd; w0.in = c->Ppart; w0.nin = 1; w0.out = Q; w0.accumulate = 1;
+  return launch_strip(c->tab_WP, w0, w0, T, c->acc64, s);
+}
+
+// out = A D with A = Y K' Y^T, Y = L^-1 (the paper's R^-T K' R^-1, eq. (RKR)).  Scratch: Vv, Uv.
+// While the stored blocks are the ones that were factored, K_diag = s L L^T + shift I for the
+// operator in force (eqs. (linear1)-(linear3)), so A D = s D + Y (shift U + s W C W^T U), U = Y^T D,
+// and the block-diagonal matrix is not streamed at all.
+int run_split_op(nugpr_ctx* c, const void* D, void* out, int T, hipStream_t s) {
+  int rc;
+  const int64_t cnt = c->L.n * T;
+  StripPort up{};
+  up.A = c->G; up.in = D; up.out = c->Vv; up.nin = 1;
+  if ((rc = launch_strip(c->tab_upG, up, up, T, c->acc64, s))) return rc;                 // U = Y^T D
+  const bool identity = c->build_gen == c->factor_gen && !(c->params.flags & NUGPR_NO_SHORTCUTS);
+  StripPort lo{};
+  lo.A = c->G; lo.in = c->Uv; lo.out = out; lo.nin = 1;
+  if (!identity) {
+    if ((rc = run_matvec(c, c->Vv, c->Uv, T, s))) return rc;                              // K' U
+  } else {
+    rc = c->acc64 ? scaled_copy<double>(c->Uv, c->Vv, c->op_shift, cnt, s) : scaled_copy<float>(c->Uv, c->Vv, c->op_shift, cnt, s);
+    if (rc) return rc;
+    if ((rc = run_lowrank_accumulate(c, c->Vv, c->Uv, T, s))) return rc;
+    rc = c->acc64 ? scaled_copy<double>(out, D, c->op_scale, cnt, s) : scaled_copy<float>(out, D, c->op_scale, cnt, s);
+    if (rc) return rc;
+    lo.accumulate = 1;
+  }
+  return launch_strip(c->tab_lowG, lo, lo, T, c->acc64, s);                               // Y (.)
+}
+
+// Q = (A^2 + 4 A + I) D, eq. (PQ).  Scratch: Zv (holds A D), and what run_split_op uses.
+static int run_pade_q(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s) {
+  int rc;
+  if ((rc = run_split_op(c, D, c->Zv, T, s))) return rc;
+  if ((rc = run_split_op(c, c->Zv, Q, T, s))) return rc;
+  const int64_t cnt = c->L.n * T;
+  if (c->acc64)
+    hipLaunchKernelGGL((k_pade_q_combine<double>), dim3(1024), dim3(256), 0, s, (double*)Q, (const double*)c->Zv, (const double*)D, cnt);
+  else
+    hipLaunchKernelGGL((k_pade_q_combine<float>), dim3(1024), dim3(256), 0, s, (float*)Q, (const float*)c->Zv, (const float*)D, cnt);
+  NUGPR_HIP(hipGetLastError());
+  return NUGPR_OK;
+}
+
 int run_precond(nugpr_ctx* c, const void* R, void* Z, int T, hipStream_t s) {
   int rc;
   StripPort a{};
@@ -297,8 +376,36 @@ int run_dot_col(nugpr_ctx* c, const void* A, const void* B, int T, double* out_h
 }
 
 template <typename VT>
+static int dot2_t(nugpr_ctx* c, const VT* A0, const VT* B0, const VT* A1, const VT* B1, int T, double* out0,
+                  double* out1, hipStream_t s) {
+  const Layout& L = c->L;
+  const int nb = L.n_dot_blocks;
+  hipLaunchKernelGGL((k_dot<2, VT>), dim3(nb), dim3(256), 0, s, A0, B0, A1, B1, (int64_t)L.n, T, c->dotpart);
+  NUGPR_HIP(hipGetLastError());
+  NUGPR_HIP(hipMemcpyAsync(c->h_buf, c->dotpart, (size_t)2 * nb * MAX_COLS * sizeof(double), hipMemcpyDeviceToHost, s));
+  NUGPR_HIP(hipStreamSynchronize(s));
+  for (int col = 0; col < T; ++col) {
+    double a0 = 0.0, a1 = 0.0;
+    for (int b = 0; b < nb; ++b) {
+      a0 += c->h_buf[(size_t)b * MAX_COLS + col];
+      a1 += c->h_buf[((size_t)nb + b) * MAX_COLS + col];
+    }
+    out0[col] = a0;
+    out1[col] = a1;
+  }
+  return NUGPR_OK;
+}
+
+// <A0, B0> and <A1, B1> per column, one synchronisation
+int run_dot2(nugpr_ctx* c, const void* A0, const void* B0, const void* A1, const void* B1, int T, double* out0,
+             double* out1, hipStream_t s) {
+  if (c->acc64) return dot2_t<double>(c, (const double*)A0, (const double*)B0, (const double*)A1, (const double*)B1, T, out0, out1, s);
+  return dot2_t<float>(c, (const float*)A0, (const float*)B0, (const float*)A1, (const float*)B1, T, out0, out1, s);
+}
+
+template <typename VT>
 static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double* alpha, double* beta,
-                 int* max_it_used, hipStream_t s, PcgExtras* extras) {
+                 int* max_it_used, hipStream_t s, PcgExtras* extras, int system) {
   const Layout& L = c->L;
   const int64_t n = L.n;
   const size_t bytes = (size_t)n * T * sizeof(VT);
@@ -312,8 +419,12 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
   // x_0 = 0, r_0 = B, cleared coefficient logs: one launch
   // d_0 = z_0 = M^-1 r_0, written straight into D; for the context's own right-hand sides it was
   // computed with the factor
-  const bool known = (const void*)B == (const void*)c->Bv && T == L.T && c->z0_ready;
-  hipLaunchKernelGGL((k_pcg_init<VT>), dim3(1024), dim3(256), 0, s, X, R, B, known ? (const VT*)c->Z0v : (const VT*)nullptr,
+  // Without a preconditioner (the Pade system, already preconditioned) z = r throughout.
+  const bool plain = system == PCG_PADE_Q;
+  const VT* Zr = plain ? R : Z;
+  const bool known = plain || ((const void*)B == (const void*)c->Bv && T == L.T && c->z0_ready);
+  const VT* z0 = plain ? B : (const VT*)c->Z0v;
+  hipLaunchKernelGGL((k_pcg_init<VT>), dim3(1024), dim3(256), 0, s, X, R, B, known ? z0 : (const VT*)nullptr,
                      D, n * T, c->alog, c->blog, (int64_t)max_iter * MAX_COLS);
   if (!known && (rc = run_precond(c, R, D, T, s))) return rc;
   hipLaunchKernelGGL((k_dot<2, VT>), dim3(nb), dim3(256), 0, s, R, R, R, D, n, T, c->dotpart);
@@ -326,7 +437,7 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
   // the host learns the count at the first stop test.
   c->h_flags->n_active = 1;
   while (it < max_iter && c->h_flags->n_active > 0) {
-    if ((rc = run_matvec(c, D, Q, T, s))) return rc;
+    if ((rc = plain ? run_pade_q(c, D, Q, T, s) : run_matvec(c, D, Q, T, s))) return rc;
     hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, D, Q, D, Q, n, T, c->dotpart);
     hipLaunchKernelGGL(k_pcg_alpha, dim3(T), dim3(256), 0, s, c->d_state, c->dotpart, nb, it, c->alog);
     hipLaunchKernelGGL((k_update_xr<VT>), dim3(eg), dim3(256), 0, s, X, R, D, Q, c->d_state, n, T);
@@ -339,10 +450,10 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
     const int j = it++;
     if (c->h_flags->indefinite) indefinite = true;
     if (c->h_flags->n_active == 0 || it >= max_iter) break;
-    if ((rc = run_precond(c, R, Z, T, s))) return rc;
-    hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, R, Z, R, Z, n, T, c->dotpart);
+    if (!plain && (rc = run_precond(c, R, Z, T, s))) return rc;
+    hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, (const VT*)R, Zr, (const VT*)R, Zr, n, T, c->dotpart);
     hipLaunchKernelGGL(k_pcg_beta, dim3(T), dim3(256), 0, s, c->d_state, c->dotpart, nb, j, c->blog);
-    hipLaunchKernelGGL((k_update_d<VT>), dim3(eg), dim3(256), 0, s, D, Z, c->d_state, n, T);
+    hipLaunchKernelGGL((k_update_d<VT>), dim3(eg), dim3(256), 0, s, D, Zr, c->d_state, n, T);
     NUGPR_HIP(hipGetLastError());
   }
   // per-column records
@@ -391,9 +502,9 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
 }
 
 int run_pcg(nugpr_ctx* c, const void* B, void* X, int T, int32_t* iters, double* alpha, double* beta,
-            int* max_it_used, hipStream_t s, PcgExtras* extras) {
-  if (c->acc64) return pcg_t<double>(c, (const double*)B, (double*)X, T, iters, alpha, beta, max_it_used, s, extras);
-  return pcg_t<float>(c, (const float*)B, (float*)X, T, iters, alpha, beta, max_it_used, s, extras);
+            int* max_it_used, hipStream_t s, PcgExtras* extras, int system) {
+  if (c->acc64) return pcg_t<double>(c, (const double*)B, (double*)X, T, iters, alpha, beta, max_it_used, s, extras, system);
+  return pcg_t<float>(c, (const float*)B, (float*)X, T, iters, alpha, beta, max_it_used, s, extras, system);
 }
 
 }  // namespace nugpr

@@ -211,6 +211,21 @@ def test_config4_full_size(lib):
         assert nerr <= 1e-4
         assert worst <= 1e-4
     ctx.close()
+    # ---- the paper's own machinery at full size (Pade log-determinant, forward differences with halving,
+    # eqs. (linear1)-(linear3)): one train step against the same closed form, timed
+    pctx = make_ctx(lib, w, logdet_pade=True, fd_forward=True, fd_step=0.01, fd_threshold=1e-2, fd_max_halvings=4)
+    t0 = time.perf_counter()
+    pstep = pctx.nugpr_train_step(np.log(theta), np.zeros(p), np.zeros(p), 0)
+    t_pade = time.perf_counter() - t0
+    halv = pctx.nugpr_fd_halvings()
+    assert pstep["code"] == 0
+    assert abs(pstep["nll0"] - nll) <= 1e-3 * abs(nll)
+    # forward quotients of the closed form at the step actually taken: d/dtheta at theta + O(Delta)
+    assert np.linalg.norm(pstep["grad"] - g) <= 2e-2 * np.linalg.norm(g)
+    assert np.all(halv >= 1) and np.all(halv <= 4)
+    record_metric("fullsize:C4-pade-forward-step", seconds=t_pade, loss_evaluations=int(p + halv.sum()),
+                  nll0=pstep["nll0"], closed_form=nll)
+    pctx.close()
 
 
 @pytest.mark.parametrize("name,nclus,shrink,with_grad", [
@@ -254,6 +269,19 @@ def test_scaled_stress_variants_match_oracle(lib, name, nclus, shrink, with_grad
     record_metric("stress-predict:" + w.name, err_mean=perr_mean, err_var=perr_var)
     assert perr_mean < 1e-4 and perr_var < 1e-4, (perr_mean, perr_var)
     tight.close()
+    # the paper's own log-determinant (eq. (PQ)) at the real cluster shape
+    pctx = make_ctx(lib, w, logdet_pade=True)
+    pctx.nugpr_build_blocks(w.theta)
+    assert pctx.nugpr_precond_factor()[0] == 0
+    pref = O.mll(prob, fac, w.theta, w.tol, w.max_iter, logdet="pade")
+    pout = pctx.nugpr_mll(w.theta)
+    pctx.close()
+    assert pout["code"] == 0
+    record_metric("stress-pade:" + w.name, nll_err=abs(pout["nll"] - pref["nll"]) / abs(pref["nll"]),
+                  logdet_err=abs(pout["logdet"] - pref["logdet"]) / abs(pref["logdet"]),
+                  iters=int(pout["max_iters_used"]), oracle_iters=int(pref["iters"].max()))
+    for key in ("quad", "logdet", "nll"):
+        assert abs(pout[key] - pref[key]) <= 1e-4 * abs(pref[key]), (key, pout[key], pref[key])
     record_metric("stress:" + w.name, solve_err=float(serr), nll_err=abs(out["nll"] - ref["nll"]) / abs(ref["nll"]),
                   iters=int(out["max_iters_used"]), oracle_iters=int(ref["iters"].max()))
     assert serr < 1e-4, serr

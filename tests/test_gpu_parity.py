@@ -282,6 +282,101 @@ def test_predict_edge_cases(lib):
     ctx.close()
 
 
+# ---- the paper's own loss machinery (Section 3.1): split operator, Pade log-determinant, forward differences
+@pytest.mark.parametrize("case", ["ragged-t8", "ragged-t32", "tiny", "iso-d1", "C1-wide"])
+def test_split_operator_matches_oracle_with_and_without_the_identity_relation(lib, case):
+    w = CASES[case]()
+    print("case", w.name, flush=True)
+    prob = oracle_problem(w)
+    fac = O.Factor(prob, w.theta)
+    rng = np.random.default_rng(21)
+    D = rng.standard_normal((w.n, w.n_probes + 1)).astype(np.float32)
+    theta2 = w.theta * (1.0 + 0.05 * np.sin(1.0 + np.arange(w.theta.shape[0])))
+    for no_shortcuts in (False, True):
+        ctx = make_ctx(lib, w, no_shortcuts=no_shortcuts)
+        ctx.nugpr_build_blocks(w.theta)
+        assert ctx.nugpr_precond_factor()[0] == 0
+        # stored blocks = factored blocks: eq. (linear1) applies (or is switched off)
+        A0 = O.split_operator(prob.operator(w.theta), fac.Ls, prob.offsets)
+        got = ctx.nugpr_split_apply(D).cpu().numpy().astype(np.float64)
+        ref = A0(D.astype(np.float64))
+        e0 = relmax(got, ref)
+        # blocks of another theta under the same factor: the general route
+        ctx.nugpr_build_blocks(theta2)
+        A2 = O.split_operator(prob.operator(theta2), fac.Ls, prob.offsets)
+        got2 = ctx.nugpr_split_apply(D[:, :2]).cpu().numpy().astype(np.float64)
+        e2 = relmax(got2, A2(D[:, :2].astype(np.float64)))
+        record_metric("split:" + w.name, no_shortcuts=int(no_shortcuts), err_same_theta=e0, err_other_theta=e2)
+        # the factor and its inverse are fp32: 1e-4 is the bar of the solves they take part in
+        assert e0 < 1e-4 and e2 < 1e-4, (e0, e2)
+        ctx.close()
+
+
+@pytest.mark.parametrize("case", ["ragged-t8", "ragged-t32", "tiny", "iso-d1", "C1", "C1-wide"])
+def test_pade_loss_matches_oracle(lib, case):
+    w = CASES[case]()
+    print("case", w.name, flush=True)
+    ctx = make_ctx(lib, w, logdet_pade=True)
+    prob = oracle_problem(w)
+    ctx.nugpr_build_blocks(w.theta)
+    assert ctx.nugpr_precond_factor()[0] == 0
+    fac = O.Factor(prob, w.theta)
+    theta2 = w.theta * (1.0 + 0.03 * np.cos(np.arange(w.theta.shape[0])))
+    for th in (w.theta, theta2):
+        ref = O.mll(prob, fac, th, w.tol, w.max_iter, logdet="pade")
+        out = ctx.nugpr_mll(th)
+        assert out["code"] == 0
+        record_metric("pade:" + w.name, nll_err=abs(out["nll"] - ref["nll"]) / abs(ref["nll"]),
+                      logdet_err=abs(out["logdet"] - ref["logdet"]) / abs(ref["logdet"]),
+                      iters=int(out["max_iters_used"]), oracle_iters=int(ref["iters"].max()))
+        for key in ("quad", "logdet", "nll"):
+            assert abs(out[key] - ref[key]) <= 1e-4 * abs(ref[key]), (key, out[key], ref[key])
+        assert abs(out["max_iters_used"] - int(ref["iters"].max())) <= 2
+    ctx.close()
+
+
+@pytest.mark.parametrize("case,pade", [("ragged-t8", False), ("ragged-t8", True), ("iso-d1", True), ("C1", False),
+                                       ("C1", True)])
+def test_forward_difference_step_matches_oracle(lib, case, pade):
+    w = CASES[case]()
+    print("case", w.name, "pade", pade, flush=True)
+    rel_step, thr, cap = 0.04, 2e-2, 6
+    prob = oracle_problem(w)
+    phi = np.log(w.theta)
+    p = phi.shape[0]
+    ref = O.train_step_forward(prob, phi, np.zeros(p), np.zeros(p), 0, rel_step, thr, cap, w.tol, w.max_iter,
+                               logdet="pade" if pade else "slq")
+    phi_o, m_o, v_o, step_o, nll_o, g_o, halv_o = ref
+    results = {}
+    for no_shortcuts in (False, True):
+        ctx = make_ctx(lib, w, fd_step=rel_step, fd_forward=True, fd_threshold=thr, fd_max_halvings=cap,
+                       logdet_pade=pade, no_shortcuts=no_shortcuts)
+        out = ctx.nugpr_train_step(phi, np.zeros(p), np.zeros(p), 0)
+        assert out["code"] == 0
+        results[no_shortcuts] = (out, ctx.nugpr_fd_halvings().astype(np.int64))
+        ctx.close()
+    for no_shortcuts, (out, halv) in results.items():
+        assert abs(out["nll0"] - nll_o) <= 1e-4 * abs(nll_o)
+        gerr = float(np.linalg.norm(out["grad"] - g_o) / np.linalg.norm(g_o))
+        record_metric("forward:" + w.name, pade=int(pade), no_shortcuts=int(no_shortcuts), grad_err=gerr,
+                      halvings=halv.tolist(), oracle_halvings=halv_o.tolist())
+        # The halving count is a decision taken on floating-point quotients: where both sides took the
+        # same number of halvings the quotient itself is compared; where they differ by the one step a
+        # marginal comparison can cost, both quotients are valid answers of the rule and agree to the
+        # threshold the rule itself applies.
+        same = halv == halv_o
+        assert np.all(np.abs(halv - halv_o) <= 1), (halv, halv_o)
+        scale = np.linalg.norm(g_o)
+        assert np.all(np.abs(out["grad"] - g_o)[same] <= 1e-4 * scale), (out["grad"], g_o)
+        assert np.all(np.abs(out["grad"] - g_o)[~same] <= 2 * thr * np.abs(g_o)[~same] + 1e-4 * scale)
+        assert same.sum() >= p - 1
+        if np.all(same):
+            np.testing.assert_allclose(out["log_theta"], phi_o, rtol=0, atol=2e-4)
+    # with and without the linear relations: the same function
+    a, b = results[False][0], results[True][0]
+    assert np.linalg.norm(a["grad"] - b["grad"]) <= 1e-4 * np.linalg.norm(b["grad"])
+
+
 def test_stale_factor_is_reused_across_theta(lib):
     # Section 3.2: the factor of theta_0 preconditions K(theta') too; eq. (logdet) stays exact
     w = small_ragged(seed=11, t=16)
