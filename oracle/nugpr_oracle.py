@@ -17,7 +17,9 @@ What each function follows:
   diag_blocks         K_diag of Section 3.2 with the noise term of Section 2.1
   default_reps/basis  representative points of Section 3.3 (reading, see below)
   coupling            K_rep of Section 3.3 generalised to r points per cluster
-  dense_K/apply_K     the approximated covariance, eq. (odblock)/(odsplit)
+  dense_K/apply_K     the approximated covariance, eq. (odblock)/(odsplit); with a
+                      compensation lambda_0 the SPD form of eqs. (krep), (kypp)
+  compensation_lambda lambda_0 of eq. (krep)
   precond_factor      eq. (cholesky factorization); R_i = L_i^T
   pcg                 batched preconditioned CG, Sections 3.1-3.2
   slq_logdet          eq. (log to trace), (trace estimation), (logdet) with the
@@ -42,7 +44,11 @@ listed as a reading in the design notes):
     basis (default: one-hot "nearest representative"); at r = 1 this is exactly
     eq. (odblock), at r = b_i with the points as their own representatives it is
     the exact covariance;
-  * the uncompensated matrix K' = K_diag + K_offdiag of eq. (odsplit) is used;
+  * the uncompensated matrix K' = K_diag + K_offdiag of eq. (odsplit) is the default;
+    Problem(compensate=True) switches to the compensated K'' of eq. (kypp), generalised to
+    r representatives per cluster as K'' = K_diag + W (C - lambda_0 I) W^T with lambda_0
+    the smallest eigenvalue of the full kernel matrix C of all representatives (at r = 1
+    this adds k(r_i, r_i) - lambda_0 to every entry of diagonal block i, as printed);
   * the log-determinant uses stochastic Lanczos quadrature on the CG
     coefficients in place of the Pade form, on the preconditioned operator of
     eq. (logdet); probe right-hand sides are b = L z so that left-preconditioned
@@ -151,13 +157,21 @@ def coupling(reps, theta):
 # --------------------------------------------------------------------------
 # O5: approximated covariance K' = blockdiag(K_ii) + W (C - blockdiag(C_ii)) W^T
 # --------------------------------------------------------------------------
-def dense_K(blocks, Ws, C, offsets, r):
+def compensation_lambda(C):
+    """lambda_0 of eq. (krep): the smallest eigenvalue of the representatives' kernel matrix."""
+    return float(np.linalg.eigvalsh(C)[0])
+
+
+def dense_K(blocks, Ws, C, offsets, r, lam0=None):
+    """K' (lam0 None) or the compensated K'' = K_diag + W (C - lam0 I) W^T (eq. (kypp))."""
     n = int(offsets[-1])
     nc = len(blocks)
     K = np.zeros((n, n))
     for i in range(nc):
         si = slice(offsets[i], offsets[i + 1])
         K[si, si] = blocks[i]
+        if lam0 is not None:                               # compensation on the diagonal block
+            K[si, si] += Ws[i] @ (C[i * r:(i + 1) * r, i * r:(i + 1) * r] - lam0 * np.eye(r)) @ Ws[i].T
         for j in range(nc):
             if j == i:
                 continue
@@ -166,8 +180,9 @@ def dense_K(blocks, Ws, C, offsets, r):
     return K
 
 
-def apply_K(blocks, Ws, C, offsets, r, D):
-    """Q = K' D without forming K' (the four sub-steps of the block-low-rank product)."""
+def apply_K(blocks, Ws, C, offsets, r, D, lam0=None):
+    """Q = K' D without forming K' (the four sub-steps of the block-low-rank product);
+    with lam0 the compensated K'' D: P = (C - lam0 I) S, diagonal blocks of C included."""
     nc = len(blocks)
     T = D.shape[1]
     Q = np.empty_like(D)
@@ -175,8 +190,11 @@ def apply_K(blocks, Ws, C, offsets, r, D):
     for j in range(nc):                                   # S_j = W_j^T D_j
         S[j * r:(j + 1) * r] = Ws[j].T @ D[offsets[j]:offsets[j + 1]]
     P = C @ S                                             # P_i = sum_j C_ij S_j ...
-    for i in range(nc):                                   # ... minus the j = i term
-        P[i * r:(i + 1) * r] -= C[i * r:(i + 1) * r, i * r:(i + 1) * r] @ S[i * r:(i + 1) * r]
+    if lam0 is None:
+        for i in range(nc):                               # ... minus the j = i term
+            P[i * r:(i + 1) * r] -= C[i * r:(i + 1) * r, i * r:(i + 1) * r] @ S[i * r:(i + 1) * r]
+    else:
+        P -= lam0 * S                                     # ... or all of it, shifted by lambda_0
     for i in range(nc):                                   # Q_i = K_ii D_i + W_i P_i
         si = slice(offsets[i], offsets[i + 1])
         Q[si] = blocks[i] @ D[si] + Ws[i] @ P[i * r:(i + 1) * r]
@@ -300,7 +318,8 @@ def slq_logdet(alphas, betas, iters, n, logdetM, probe_cols):
 class Problem:
     """Inputs widened to float64 plus the theta-independent pieces (reps, W)."""
 
-    def __init__(self, X, y, offsets, probes, rank, reps=None, Ws=None):
+    def __init__(self, X, y, offsets, probes, rank, reps=None, Ws=None, compensate=False):
+        self.compensate = bool(compensate)
         self.X = np.asarray(X, dtype=np.float64)
         self.y = np.asarray(y, dtype=np.float64)
         self.offsets = np.asarray(offsets, dtype=np.int64)
@@ -320,11 +339,13 @@ class Problem:
 
     def operator(self, theta):
         blocks, C = self.assemble(theta)
-        return lambda D: apply_K(blocks, self.Ws, C, self.offsets, self.r, D)
+        lam0 = compensation_lambda(C) if self.compensate else None
+        return lambda D: apply_K(blocks, self.Ws, C, self.offsets, self.r, D, lam0)
 
     def dense(self, theta):
         blocks, C = self.assemble(theta)
-        return dense_K(blocks, self.Ws, C, self.offsets, self.r)
+        lam0 = compensation_lambda(C) if self.compensate else None
+        return dense_K(blocks, self.Ws, C, self.offsets, self.r, lam0)
 
 
 class Factor:

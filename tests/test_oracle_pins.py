@@ -534,6 +534,81 @@ def test_rmse_definition():
     assert abs(O.rmse([1.0, 2.0, 4.0], [1.0, 0.0, 0.0]) - math.sqrt((0 + 4 + 16) / 3)) < 1e-15
 
 
+# ---------------------------------------------------------------- SPD compensation, eqs. (krep), (kypp)
+def test_compensation_lambda_by_the_cholesky_criterion():
+    # closed form for a 2 x 2 kernel matrix, then the criterion the paper itself states: a symmetric
+    # matrix is positive definite exactly when its Cholesky factorisation succeeds
+    assert abs(O.compensation_lambda(np.array([[2.0, -0.5], [-0.5, 2.0]])) - 1.5) < 1e-14
+    rng = np.random.default_rng(3)
+    R = rng.normal(size=(7, 2))
+    C = O.rbf(R, R, np.array([1.2, 0.8]), 1.7)
+    lam0 = O.compensation_lambda(C)
+    assert lam0 > 0.0
+    np.linalg.cholesky(C - (lam0 - 1e-9) * np.eye(7))
+    with pytest.raises(np.linalg.LinAlgError):
+        np.linalg.cholesky(C - (lam0 + 1e-9) * np.eye(7))
+
+
+def test_compensated_matrix_has_the_printed_form_at_rank_one_and_is_spd():
+    # r = 1: off-diagonal block (i, j) is k(r_i, r_j) in every entry, and diagonal block i gains
+    # k(r_i, r_i) - lambda_0 in every entry (Section 3.3), built here with plain loops
+    w = I.make_small(n_clusters=3, sizes=[5, 7, 4], d=2, rank=1, t=2, seed=41, ell=1.0, spacing=0.8, sigma_blob=0.8,
+                     noise=0.05)
+    prob = O.Problem(w.X, w.y, w.offsets, w.probes, 1, compensate=True)
+    ell, alpha, sigma2 = O.split_theta(w.theta, 2)
+    reps = [prob.X[w.offsets[i]] for i in range(3)]
+    Krep = np.array([[brute_kernel(a, b, ell, alpha) for b in reps] for a in reps])
+    lam0 = O.compensation_lambda(Krep)
+    n = prob.n
+    K = np.zeros((n, n))
+    cl = np.searchsorted(w.offsets, np.arange(n), side="right") - 1
+    for p_ in range(n):
+        for q in range(n):
+            if cl[p_] == cl[q]:
+                K[p_, q] = brute_kernel(prob.X[p_], prob.X[q], ell, alpha) + (sigma2 if p_ == q else 0.0) \
+                    + (brute_kernel(reps[cl[p_]], reps[cl[p_]], ell, alpha) - lam0)
+            else:
+                K[p_, q] = brute_kernel(reps[cl[p_]], reps[cl[q]], ell, alpha)
+    Kpp = prob.dense(w.theta)
+    np.testing.assert_allclose(Kpp, K, rtol=1e-12, atol=1e-13)
+    # the uncompensated matrix of this (strongly coupled) case is indefinite, the compensated one is not
+    Kp = O.Problem(w.X, w.y, w.offsets, w.probes, 1).dense(w.theta)
+    assert np.linalg.eigvalsh(Kp)[0] < 0.0
+    assert np.linalg.eigvalsh(Kpp)[0] >= sigma2 * (1 - 1e-9)
+    # K_offdiag' = K'' - K_diag is positive semi-definite with smallest eigenvalue 0
+    blocks = O.diag_blocks(prob.X, prob.offsets, w.theta)
+    Koff = Kpp.copy()
+    for i in range(3):
+        si = slice(w.offsets[i], w.offsets[i + 1])
+        Koff[si, si] -= blocks[i]
+    ev = np.linalg.eigvalsh(Koff)
+    assert abs(ev[0]) < 1e-10 and ev[-1] > 0
+    # matrix-free product = dense product
+    D = np.random.default_rng(1).standard_normal((n, 3))
+    np.testing.assert_allclose(prob.operator(w.theta)(D), Kpp @ D, rtol=1e-12, atol=1e-12)
+
+
+def test_preconditioned_compensated_system_has_few_distinct_eigenvalues():
+    # Section 3.3: R^-T K'' R^-1 = I + (rank <= n_c r) has at most n_c r + 1 distinct eigenvalues,
+    # so the preconditioned CG ends in at most that many iterations
+    w = I.make_small(n_clusters=3, sizes=[9, 6, 8], d=2, rank=2, t=3, seed=43, ell=2.0, spacing=2.0, sigma_blob=0.5,
+                     tol=1e-10, max_iter=50)
+    prob = O.Problem(w.X, w.y, w.offsets, w.probes, 2, compensate=True)
+    fac = O.Factor(prob, w.theta)
+    Kpp = prob.dense(w.theta)
+    Lb = np.zeros_like(Kpp)
+    for i, L in enumerate(fac.Ls):
+        Lb[w.offsets[i]:w.offsets[i + 1], w.offsets[i]:w.offsets[i + 1]] = L
+    Li = np.linalg.inv(Lb)
+    ev = np.linalg.eigvalsh(Li @ Kpp @ Li.T)
+    distinct = 1 + int(np.sum(np.diff(ev) > 1e-8))
+    assert distinct <= 3 * 2 + 1
+    assert np.sum(np.abs(ev - 1.0) < 1e-8) >= prob.n - 6
+    out = O.mll(prob, fac, w.theta, 1e-10, 50)
+    assert out["iters"].max() <= 3 * 2 + 1 and out["converged"].all()
+    assert abs(out["quad"] - prob.y @ np.linalg.solve(Kpp, prob.y)) < 1e-8
+
+
 # ---------------------------------------------------------------- Pade log-determinant
 def test_pade22_is_the_2_2_approximant_of_the_logarithm():
     # P(1+u) - log(1+u) Q(1+u) = O(u^5): exact polynomial arithmetic on the series of log(1+u)
