@@ -84,6 +84,14 @@ enum {
                                   fd_step * theta_i halved until two consecutive quotients agree to
                                   fd_threshold (relative) or fd_max_halvings halvings were made; the result
                                   is carried to log(theta) by the chain rule.  Default: central differences. */
+  ,
+  NUGPR_COMPENSATE = 32u       /* the operator is the compensated K'' = K_diag + W (C - lambda_0 I) W^T of
+                                  Section 3.3 (eqs. (krep), (kypp)), positive definite by construction:
+                                  C is the full kernel matrix of the representatives (its diagonal blocks
+                                  included) and lambda_0 its smallest eigenvalue, computed on the host in
+                                  fp64 at every assembly (dense symmetric eigen-solve).  Supported for
+                                  n_clusters * rank <= 512, the paper's regime (n_c <= 20, rank 1).
+                                  Default: the uncompensated K' of eq. (odsplit). */
 };
 
 /* Problem description (Section 2.1 notation; Section 3.3 for representatives). */
@@ -115,7 +123,7 @@ typedef struct {
   double lr;           /* Adam learning rate (paper: 0.05)                             */
   double beta1, beta2, eps;  /* Adam moments / epsilon (0 selects 0.9, 0.999, 1e-8)    */
   uint32_t flags;      /* NUGPR_ISOTROPIC | NUGPR_ACC_FP32 | NUGPR_NO_SHORTCUTS |
-                          NUGPR_LOGDET_PADE | NUGPR_FD_FORWARD, or 0                   */
+                          NUGPR_LOGDET_PADE | NUGPR_FD_FORWARD | NUGPR_COMPENSATE, or 0 */
   int32_t fd_max_halvings;   /* NUGPR_FD_FORWARD: cap on the halvings per hyperparameter,
                                 1..30 (0 selects 8)                                    */
   double fd_threshold; /* NUGPR_FD_FORWARD: stop when |g - g_prev| <= fd_threshold |g|
@@ -232,6 +240,14 @@ int nugpr_rmse(const double* mean, const double* ytest, int64_t m, double* out);
  * s = sqrt(max(var, 0)).  All HOST arrays of m doubles; lo / hi may alias nothing else. */
 int nugpr_confidence_band(const double* mean, const double* var, int64_t m, double* lo, double* hi);
 
+/* lambda_0 of eq. (krep) at the last assembly of a NUGPR_COMPENSATE context (HOST double out). */
+int nugpr_compensation_lambda(const nugpr_ctx* ctx, double* out /*HOST*/);
+
+/* Smallest eigenvalue of a dense symmetric n x n matrix A (HOST, row-major fp64, not modified; only
+ * its lower triangle and diagonal are meaningful as a symmetric matrix): the host routine behind
+ * lambda_0, Householder tridiagonalisation + QL.  n = 1..4096.  Pure host arithmetic. */
+int nugpr_host_smallest_eigenvalue(const double* A /*HOST*/, int32_t n, double* out /*HOST*/);
+
 /* Halvings each hyperparameter's forward difference took in the last nugpr_train_step of a
  * NUGPR_FD_FORWARD context (Section 3.1): out is HOST, p entries; zeros before the first step. */
 int nugpr_fd_halvings(const nugpr_ctx* ctx, int32_t* out /*HOST*/);
@@ -239,7 +255,8 @@ int nugpr_fd_halvings(const nugpr_ctx* ctx, int32_t* out /*HOST*/);
 /* Copies one stored matrix to a dense row-major DEVICE array `dst` with leading
  * dimension `ld` (for verification).  what: 0 = K_ii (b_i x b_i), 1 = L_i lower
  * factor (b_i x b_i, zeros above the diagonal), 2 = L_i^-1 (b_i x b_i), 3 = coupling
- * C with zeroed diagonal blocks ((n_c r) x (n_c r); index ignored), 4 = W_i (b_i x r),
+ * C with zeroed diagonal blocks, or C - lambda_0 I under NUGPR_COMPENSATE
+ * ((n_c r) x (n_c r); index ignored), 4 = W_i (b_i x r),
  * 5 = right-hand sides B (n x (t+1); index ignored), 6 = representatives
  * ((n_c r) x d; index ignored). */
 int nugpr_export(nugpr_ctx* ctx, int32_t what, int32_t index, float* dst /*DEVICE*/, int64_t ld,

@@ -22,6 +22,7 @@ NUGPR_ACC_FP32 = 2
 NUGPR_NO_SHORTCUTS = 4
 NUGPR_LOGDET_PADE = 8
 NUGPR_FD_FORWARD = 16
+NUGPR_COMPENSATE = 32
 
 EXPORT_K, EXPORT_L, EXPORT_LINV, EXPORT_C, EXPORT_W, EXPORT_B, EXPORT_REPS = range(7)
 
@@ -98,6 +99,10 @@ def load_library():
     lib.nugpr_rmse.argtypes = [dp, dp, C.c_int64, dp]
     lib.nugpr_confidence_band.restype = C.c_int
     lib.nugpr_confidence_band.argtypes = [dp, dp, C.c_int64, dp, dp]
+    lib.nugpr_compensation_lambda.restype = C.c_int
+    lib.nugpr_compensation_lambda.argtypes = [vp, dp]
+    lib.nugpr_host_smallest_eigenvalue.restype = C.c_int
+    lib.nugpr_host_smallest_eigenvalue.argtypes = [dp, C.c_int32, dp]
     lib.nugpr_fd_halvings.restype = C.c_int
     lib.nugpr_fd_halvings.argtypes = [vp, ip]
     lib.nugpr_export.restype = C.c_int
@@ -145,6 +150,15 @@ def nugpr_rmse(mean, ytest):
     return out.value
 
 
+def nugpr_host_smallest_eigenvalue(A):
+    a = np.ascontiguousarray(np.asarray(A, dtype=np.float64))
+    if a.ndim != 2 or a.shape[0] != a.shape[1]:
+        raise NugprError(NUGPR_ERR_INVALID, "A must be square")
+    out = C.c_double()
+    _check(load_library().nugpr_host_smallest_eigenvalue(_dptr(a), a.shape[0], C.byref(out)))
+    return out.value
+
+
 def nugpr_confidence_band(mean, var):
     a = np.ascontiguousarray(np.asarray(mean, dtype=np.float64))
     v = np.ascontiguousarray(np.asarray(var, dtype=np.float64))
@@ -163,7 +177,7 @@ class Context:
 
     def __init__(self, X, y, offsets, probes, rank, tol=1e-6, max_iter=100, fd_step=1e-3, lr=0.05,
                  isotropic=False, reps=None, W=None, device="cuda:0", acc_fp32=False, no_shortcuts=False,
-                 logdet_pade=False, fd_forward=False, fd_threshold=0.0, fd_max_halvings=0):
+                 logdet_pade=False, fd_forward=False, fd_threshold=0.0, fd_max_halvings=0, compensate=False):
         import torch
         self.torch = torch
         self.lib = load_library()
@@ -201,7 +215,7 @@ class Context:
         pr = Params(tol=tol, max_iter=max_iter, fd_step=fd_step, lr=lr, beta1=0.0, beta2=0.0, eps=0.0,
                     flags=(NUGPR_ISOTROPIC if isotropic else 0) | (NUGPR_ACC_FP32 if acc_fp32 else 0)
                     | (NUGPR_NO_SHORTCUTS if no_shortcuts else 0) | (NUGPR_LOGDET_PADE if logdet_pade else 0)
-                    | (NUGPR_FD_FORWARD if fd_forward else 0),
+                    | (NUGPR_FD_FORWARD if fd_forward else 0) | (NUGPR_COMPENSATE if compensate else 0),
                     fd_max_halvings=int(fd_max_halvings), fd_threshold=float(fd_threshold))
         self.params = pr
         self.max_iter = int(max_iter)
@@ -309,6 +323,11 @@ class Context:
         code = _check(self.lib.nugpr_predict(self.handle, _dptr(th), Xt.data_ptr() if m else None, m, _dptr(mean),
                                              _dptr(var) if variance else None, C.byref(mx), self._stream()))
         return dict(code=code, mean=mean, var=var, max_iters_used=mx.value)
+
+    def nugpr_compensation_lambda(self):
+        out = C.c_double()
+        _check(self.lib.nugpr_compensation_lambda(self.handle, C.byref(out)))
+        return out.value
 
     def nugpr_fd_halvings(self):
         out = np.zeros(self.p, dtype=np.int32)

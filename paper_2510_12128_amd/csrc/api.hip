@@ -167,6 +167,10 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   Layout L;
   int rc = plan_layout(pb, prm->flags, L);
   if (rc) return rc;
+  if (L.compensate && L.ncr > 512) {
+    set_error("NUGPR_COMPENSATE supports n_clusters * rank <= 512 (lambda_0 is a dense host eigen-solve)");
+    return NUGPR_ERR_INVALID;
+  }
   if (!pb->X || !pb->y || (pb->n_probes > 0 && !pb->probes)) { set_error("X, y or probes is null"); return NUGPR_ERR_INVALID; }
   if (!pb->workspace || (reinterpret_cast<uintptr_t>(pb->workspace) & 255u)) {
     set_error("workspace is null or not 256-byte aligned");
@@ -196,6 +200,7 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   c->Lf = reinterpret_cast<float*>(w + L.o_Lf);
   c->G = reinterpret_cast<float*>(w + L.o_G);
   c->C = reinterpret_cast<float*>(w + L.o_C);
+  c->Clo = L.compensate ? reinterpret_cast<float*>(w + L.o_Clo) : nullptr;
   c->Wd = reinterpret_cast<float*>(w + L.o_Wd);
   c->Wt = reinterpret_cast<float*>(w + L.o_Wt);
   c->reps = reinterpret_cast<float*>(w + L.o_reps);
@@ -252,6 +257,13 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   if ((rc = launch_setup(c, pb->reps, pb->W, s))) return fail(rc);
   e = hipStreamSynchronize(s);
   if (e != hipSuccess) return fail(hip_fail(e, "sync after setup"));
+  if (L.compensate) {
+    // lambda_0 is computed on the host from the representatives themselves, in fp64
+    std::vector<float> hr((size_t)L.ncr * L.d);
+    e = hipMemcpy(hr.data(), c->reps, hr.size() * sizeof(float), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail(hip_fail(e, "copy representatives to the host"));
+    c->h_reps.assign(hr.begin(), hr.end());
+  }
   *out = c;
   return NUGPR_OK;
 }
@@ -619,6 +631,22 @@ int nugpr_confidence_band(const double* mean, const double* var, int64_t m, doub
     lo[j] = mean[j] - 2.0 * sd;
     hi[j] = mean[j] + 2.0 * sd;
   }
+  return NUGPR_OK;
+}
+
+int nugpr_compensation_lambda(const nugpr_ctx* c, double* out) {
+  if (!c || !out) { set_error("null argument"); return NUGPR_ERR_INVALID; }
+  if (!c->L.compensate || !c->built) { set_error("no compensated assembly yet"); return NUGPR_ERR_STATE; }
+  *out = c->lambda0;
+  return NUGPR_OK;
+}
+
+int nugpr_host_smallest_eigenvalue(const double* A, int32_t n, double* out) {
+  if (!A || !out || n < 1 || n > 4096) { set_error("smallest_eigenvalue needs a matrix with n = 1..4096"); return NUGPR_ERR_INVALID; }
+  std::vector<double> work((size_t)n * n);
+  for (int i = 0; i < n; ++i)                      // symmetric copy of the lower triangle
+    for (int j = 0; j <= i; ++j) work[(size_t)i * n + j] = work[(size_t)j * n + i] = A[(size_t)i * n + j];
+  if (sym_smallest_eigenvalue(work, n, out)) { set_error("eigen-solve did not converge"); return NUGPR_ERR_INVALID; }
   return NUGPR_OK;
 }
 

@@ -76,7 +76,8 @@ __global__ __launch_bounds__(256) void k_scale_points(const ScaleArgs a, const C
 
 struct PanelArgs {
   double alpha;
-  float diag_val;       // float(alpha + sigma^2)
+  float diag_val;       // diagonal entries: float(alpha + sigma^2); coupling under compensation: float(alpha - lambda_0)
+  int keep_same;        // coupling: keep the entries between representatives of one cluster (compensation)
   int32_t kd;           // coordinates per point in the scaled array (multiple of 4)
 };
 
@@ -246,8 +247,10 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
           bool keep = p < total && q < total;
           if (COUPLING) {
             // only blocks between DIFFERENT clusters enter K' (eq. (odsplit)): same-cluster entries are 0
-            keep = keep && (p / r) != (q / r);
+            // (all of C, with alpha - lambda_0 on its diagonal, under the compensation of eq. (krep))
+            keep = keep && (a.keep_same || (p / r) != (q / r));
             x[i] = keep ? x[i] : 0.f;
+            if (a.keep_same && p == q && p < total) x[i] = dv;
           } else {
             x[i] = keep ? x[i] : 0.f;
             if (p == q && p < total) x[i] = dv;
@@ -269,6 +272,35 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
   for (int k = 0; k < 4; ++k) *reinterpret_cast<float4*>(od + (uint64_t)(16 * k) * ld64) = st_r[k * (16 * ST_LD / 4)];
+}
+
+// What fp32 storage of the compensated coupling matrix drops (eq. (krep)): every entry of
+// C - lambda_0 I is evaluated once more in plain fp64 from the representatives and the stored fp32 value
+// is subtracted; the difference, in fp32, is the second term of a two-term representation of the entry.
+// The matrix is small here (n_c r <= 512).
+struct CouplingArgs {
+  double inv_ell[MAX_D];
+  double alpha, lambda0;
+  int n, d;
+  uint32_t ld;
+};
+__global__ __launch_bounds__(256) void k_coupling_residual(CouplingArgs a, const float* __restrict__ reps,
+                                                           const float* __restrict__ Chi, float* __restrict__ Clo) {
+  const uint64_t idx = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (uint64_t)a.ld * a.ld) return;
+  const int i = (int)(idx / a.ld), j = (int)(idx - (uint64_t)i * a.ld);
+  float lo = 0.f;
+  if (i < a.n && j < a.n) {
+    double q = 0.0;
+    for (int k = 0; k < a.d; ++k) {
+      const double t = ((double)reps[(uint64_t)i * a.d + k] - (double)reps[(uint64_t)j * a.d + k]) * a.inv_ell[k];
+      q = fma(t, t, q);
+    }
+    double v = a.alpha * exp(-0.5 * q);
+    if (i == j) v -= a.lambda0;
+    lo = (float)(v - (double)Chi[idx]);
+  }
+  Clo[idx] = lo;
 }
 
 // ---------------------------------------------------------------------------
@@ -414,7 +446,29 @@ int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s) {
   a.alpha = alpha;
   a.diag_val = (float)(alpha + sigma2);
   a.kd = pair_kd(L.d);
+  a.keep_same = 0;
   c->diag_residual = (float)((alpha + sigma2) - (double)a.diag_val);
+  PanelArgs ac = a;                                  // the coupling launch
+  if (L.compensate) {
+    // lambda_0 = smallest eigenvalue of the representatives' kernel matrix (eq. (krep)), fp64 on the host
+    const int N = L.ncr;
+    std::vector<double> Cm((size_t)N * N);
+    const double* R = c->h_reps.data();
+    for (int i = 0; i < N; ++i)
+      for (int j = 0; j <= i; ++j) {
+        double q = 0.0;
+        for (int k = 0; k < L.d; ++k) {
+          const double t = (R[(size_t)i * L.d + k] - R[(size_t)j * L.d + k]) / (iso ? theta[0] : theta[k]);
+          q += t * t;
+        }
+        Cm[(size_t)i * N + j] = Cm[(size_t)j * N + i] = alpha * std::exp(-0.5 * q);
+      }
+    double lam0 = 0.0;
+    if (sym_smallest_eigenvalue(Cm, N, &lam0)) { set_error("lambda_0: eigen-solve did not converge"); return NUGPR_ERR_INVALID; }
+    c->lambda0 = lam0;
+    ac.keep_same = 1;
+    ac.diag_val = (float)(alpha - lam0);
+  }
   hipLaunchKernelGGL(k_scale_points, dim3((unsigned)L.ntmax, (unsigned)L.nc), dim3(256), 0, s, sa, c->d_cl, c->X, c->Xs,
                      c->Xn, 0, 0);
   hipLaunchKernelGGL(k_scale_points, dim3((unsigned)(L.ldc / TILE), 1u), dim3(256), 0, s, sa,
@@ -423,7 +477,7 @@ int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s) {
   const size_t lds = (size_t)4 * a.kd * 16 * sizeof(double);      // row operands of one tile
 #define NUGPR_TILES(NKS)                                                                                         \
   do {                                                                                                           \
-    hipLaunchKernelGGL((k_build_tile<true, NKS>), gc, blk, lds, s, a, c->d_pan_c, c->Rs, c->Rn, c->C, L.r);      \
+    hipLaunchKernelGGL((k_build_tile<true, NKS>), gc, blk, lds, s, ac, c->d_pan_c, c->Rs, c->Rn, c->C, L.r);     \
     hipLaunchKernelGGL((k_build_tile<false, NKS>), gd, blk, lds, s, a, c->d_pan_diag, c->Xs, c->Xn, c->Kd, 1);   \
   } while (0)
   switch (a.kd / 4) {        // the dimensions of the usual workloads get their own instantiation
@@ -434,6 +488,14 @@ int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s) {
   }
 #undef NUGPR_TILES
   NUGPR_HIP(hipGetLastError());
+  if (L.compensate) {
+    CouplingArgs ca;
+    for (int k = 0; k < MAX_D; ++k) ca.inv_ell[k] = k < L.d ? 1.0 / (iso ? theta[0] : theta[k]) : 0.0;
+    ca.alpha = alpha; ca.lambda0 = c->lambda0; ca.n = L.ncr; ca.d = L.d; ca.ld = (uint32_t)L.ldc;
+    const unsigned blocks = (unsigned)(((uint64_t)L.ldc * L.ldc + 255) / 256);
+    hipLaunchKernelGGL(k_coupling_residual, dim3(blocks), dim3(256), 0, s, ca, c->reps, c->C, c->Clo);
+    NUGPR_HIP(hipGetLastError());
+  }
   c->theta_built.assign(theta, theta + L.p);
   c->op_scale = 1.0;
   c->op_shift = (double)c->diag_residual;

@@ -40,6 +40,7 @@ int plan_layout(const nugpr_problem* pb, uint32_t flags, Layout& L) {
   L.T = L.t + 1;
   L.p = (flags & NUGPR_ISOTROPIC) ? 3 : L.d + 2;
   L.max_iter = MAX_ITER_CAP;          // the coefficient logs are sized for the cap
+  L.compensate = (flags & NUGPR_COMPENSATE) != 0;
   if ((int64_t)L.nc * L.r > (int64_t)1 << 24) { set_error("n_clusters*rank too large"); return NUGPR_ERR_INVALID; }
   L.ncr = L.nc * L.r;
   L.ldc = (int)align_up(L.ncr, TILE);
@@ -104,6 +105,9 @@ int plan_layout(const nugpr_problem* pb, uint32_t flags, Layout& L) {
     L.o_Rs = take(cur, (size_t)L.ldc * kd * sizeof(double));
     L.o_Rn = take(cur, (size_t)L.ldc * sizeof(double));
   }
+  // residual matrix of the compensated coupling; reserved whenever the problem is small enough for the
+  // compensation, so that the workspace size does not depend on the flags
+  if (L.ncr <= 512) L.o_Clo = take(cur, (size_t)L.ldc * L.ldc * sizeof(float));
   L.o_B = take(cur, vec);
   L.o_X = take(cur, vec);
   L.o_R = take(cur, vec);

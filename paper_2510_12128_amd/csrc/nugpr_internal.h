@@ -121,6 +121,7 @@ struct Layout {
   int ncr = 0, ldc = 0, ldw = 0;
   int ntmax = 0;
   int nsS = 1, nsP = 1;
+  bool compensate = false;    // SPD compensation: full coupling matrix minus lambda_0 I, with an fp32 residual matrix
   std::vector<ClusterInfo> cl;
   uint64_t kd_elems = 0, wt_elems = 0;
   uint64_t rows_pad = 0;      // sum of ld over the clusters
@@ -130,7 +131,7 @@ struct Layout {
   size_t o_Spart = 0, o_Ppart = 0, o_dot = 0, o_state = 0, o_alog = 0, o_blog = 0;
   size_t o_theta = 0, o_logdet = 0, o_tiles = 0, o_items = 0;
   size_t o_Xs = 0, o_Xn = 0, o_Rs = 0, o_Rn = 0;
-  size_t o_x0 = 0, o_Z0 = 0, o_P = 0;
+  size_t o_x0 = 0, o_Z0 = 0, o_P = 0, o_Clo = 0;
   size_t items_bytes = 0;
   int n_dot_blocks = 0;
   int max_iter = 0;
@@ -188,6 +189,12 @@ struct nugpr_ctx {
   // The stored blocks are the very ones the factor was computed from while build_gen == factor_gen:
   // then Y K_diag Y^T = I for the stored K_diag and Y = L^-1 (eq. (linear1)).
   uint64_t build_gen = 0, factor_gen = ~0ull;
+  // SPD compensation (eq. (krep)): host copy of the representatives and lambda_0 of the last assembly.
+  // Clo holds what fp32 storage of C - lambda_0 I drops: C_exact - lambda_0 I - C_stored, itself in fp32,
+  // applied as a second small product so that the compensation term is carried to ~2^-48.
+  std::vector<double> h_reps;
+  double lambda0 = 0.0;
+  float* Clo = nullptr;
   std::vector<int32_t> fd_halvings;      // halvings per hyperparameter in the last forward-difference step
   double logdetM = 0.0;
 };
@@ -254,5 +261,7 @@ int run_predict(nugpr_ctx* c, const double* theta, const float* Xt, int64_t m, d
 // slq.cpp ---------------------------------------------------------------------
 // e_1^T log(T) e_1 for the k x k Lanczos matrix built from CG coefficients.
 int slq_e1_log_e1(const double* alpha, const double* beta, int stride, int k, double* out);
+// Smallest eigenvalue of a dense symmetric n x n matrix (row-major, overwritten); 0 on success.
+int sym_smallest_eigenvalue(std::vector<double>& A, int n, double* out);
 
 }  // namespace nugpr

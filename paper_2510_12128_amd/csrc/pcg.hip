@@ -251,6 +251,11 @@ int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s) {
     NUGPR_HIP(hipEventRecord(c->prof_ev[2 * c->prof_used + 1], s));
     c->prof_used += 1;
   }
+  if (L.compensate) {                     // the fp32 residual of C - lambda_0 I, added slab by slab
+    StripPort k2 = k1;
+    k2.A = c->Clo; k2.accumulate = 1;
+    if ((rc = launch_strip(c->tab_C, k2, k2, T, c->acc64, s))) return rc;
+  }
   if (L.nsP > 1 && (rc = launch_sum_parts(c->Ppart, c->Ppart, (int64_t)ppart, L.nsP, ppart, c->acc64, s))) return rc;
   // Q_i += W_i P_i
   StripPort w0{};
@@ -291,6 +296,11 @@ static int run_lowrank_accumulate(nugpr_ctx* c, const void* D, void* Q, int T, h
   StripPort k1{};
   k1.A = c->C; k1.in = c->Spart; k1.nin = 1; k1.out = c->Ppart; k1.out_part_stride = ppart; k1.scale = c->op_scale;
   if ((rc = launch_strip(c->tab_C, k1, k1, T, c->acc64, s))) return rc;
+  if (L.compensate) {
+    StripPort k2 = k1;
+    k2.A = c->Clo; k2.accumulate = 1;
+    if ((rc = launch_strip(c->tab_C, k2, k2, T, c->acc64, s))) return rc;
+  }
   if (L.nsP > 1 && (rc = launch_sum_parts(c->Ppart, c->Ppart, (int64_t)ppart, L.nsP, ppart, c->acc64, s))) return rc;
   StripPort w0{};
   w0.A = c->Wd; w0.in = c->Ppart; w0.nin = 1; w0.out = Q; w0.accumulate = 1;

@@ -86,4 +86,45 @@ int slq_e1_log_e1(const double* alpha, const double* beta, int stride, int k, do
   return 0;
 }
 
+// Smallest eigenvalue of a dense symmetric matrix (row-major n x n, overwritten): Householder reduction
+// to tridiagonal form, A <- H A H with H = I - 2 v v^T / v^T v column by column, then the QL iteration
+// above.  Used for lambda_0 of eq. (krep), on the host, in fp64.
+int sym_smallest_eigenvalue(std::vector<double>& A, int n, double* out) {
+  if (n < 1 || (size_t)n * n > A.size()) return 1;
+  auto a = [&](int i, int j) -> double& { return A[(size_t)i * n + j]; };
+  std::vector<double> d(n), e(n > 1 ? n - 1 : 0), v(n), q(n), z;
+  for (int k = 0; k + 2 < n; ++k) {
+    double nrm2 = 0.0;
+    for (int i = k + 1; i < n; ++i) nrm2 += a(i, k) * a(i, k);
+    const double x0 = a(k + 1, k), sigma = std::sqrt(nrm2);
+    if (sigma == 0.0) { e[k] = 0.0; continue; }
+    const double alpha = x0 >= 0.0 ? -sigma : sigma;          // no cancellation in v_0 = x_0 - alpha
+    for (int i = k + 1; i < n; ++i) v[i] = a(i, k);
+    v[k + 1] -= alpha;
+    const double vtv = 2.0 * (nrm2 - alpha * x0);
+    const double beta = 2.0 / vtv;
+    double vtp = 0.0;
+    for (int i = k + 1; i < n; ++i) {                         // p = beta A_sub v
+      double acc = 0.0;
+      for (int j = k + 1; j < n; ++j) acc += a(i, j) * v[j];
+      q[i] = beta * acc;
+      vtp += v[i] * q[i];
+    }
+    const double kk = vtp / vtv;
+    for (int i = k + 1; i < n; ++i) q[i] -= kk * v[i];        // q = p - (v^T p / v^T v) v
+    for (int i = k + 1; i < n; ++i)                           // A_sub -= v q^T + q v^T
+      for (int j = k + 1; j < n; ++j) a(i, j) -= v[i] * q[j] + q[i] * v[j];
+    e[k] = alpha;
+  }
+  for (int i = 0; i < n; ++i) d[i] = a(i, i);
+  if (n >= 2) e[n - 2] = a(n - 1, n - 2);
+  for (int i = 0; i < n; ++i)
+    if (!std::isfinite(d[i])) return 1;
+  if (tridiag_ql_first_row(d, e, z)) return 1;
+  double mn = d[0];
+  for (int i = 1; i < n; ++i) mn = d[i] < mn ? d[i] : mn;
+  *out = mn;
+  return 0;
+}
+
 }  // namespace nugpr

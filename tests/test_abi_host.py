@@ -94,6 +94,27 @@ def test_host_side_prediction_scores(lib):
         B.nugpr_rmse([], [])
 
 
+def test_host_smallest_eigenvalue_against_lapack(lib):
+    # the host routine behind lambda_0 of eq. (krep): Householder + QL, checked against numpy's eigvalsh
+    rng = np.random.default_rng(5)
+    for n in (1, 2, 3, 17, 130):
+        A = rng.standard_normal((n, n))
+        A = A + A.T
+        want = np.linalg.eigvalsh(A)[0]
+        assert abs(B.nugpr_host_smallest_eigenvalue(A) - want) <= 1e-12 * max(1.0, np.abs(A).sum(axis=1).max()), n
+    # kernel matrices: nearly singular, clustered small eigenvalues
+    R = rng.normal(size=(64, 3))
+    d2 = ((R[:, None, :] - R[None, :, :]) ** 2).sum(axis=2)
+    for ell in (0.3, 1.0, 3.0):
+        K = 1.3 * np.exp(-0.5 * d2 / ell ** 2)
+        assert abs(B.nugpr_host_smallest_eigenvalue(K) - np.linalg.eigvalsh(K)[0]) < 1e-12
+    # closed form, a diagonal matrix, and only the lower triangle is read
+    assert abs(B.nugpr_host_smallest_eigenvalue([[2.0, 99.0], [-0.5, 2.0]]) - 1.5) < 1e-14
+    assert abs(B.nugpr_host_smallest_eigenvalue(np.diag([3.0, -1.0, 2.0])) + 1.0) < 1e-14
+    with pytest.raises(B.NugprError):
+        B.nugpr_host_smallest_eigenvalue(np.zeros((0, 0)))
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_LIB", None)
     monkeypatch.setattr(B, "lib_path", lambda: str(tmp_path / "libnugpr.so"))

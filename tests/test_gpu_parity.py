@@ -377,6 +377,83 @@ def test_forward_difference_step_matches_oracle(lib, case, pade):
     assert np.linalg.norm(a["grad"] - b["grad"]) <= 1e-4 * np.linalg.norm(b["grad"])
 
 
+# ---- SPD compensation K'' of eqs. (krep), (kypp)
+COMP_CASES = dict(CASES)
+COMP_CASES["indefinite"] = lambda: small_ragged(seed=12, t=4)        # K' has a negative eigenvalue, K'' has none
+COMP_CASES["rank1"] = lambda: I.make_small(n_clusters=5, sizes=[70, 64, 130, 20, 33], d=2, rank=1, t=6, seed=41,
+                                            ell=1.0, spacing=0.8, sigma_blob=0.8, noise=0.05, tol=1e-8, max_iter=60)
+
+
+@pytest.mark.parametrize("case", ["ragged-t8", "tiny", "iso-d1", "C1", "indefinite", "rank1"])
+def test_compensated_operator_loss_and_gradient_match_oracle(lib, case):
+    w = COMP_CASES[case]()
+    print("case", w.name, flush=True)
+    ctx = make_ctx(lib, w, compensate=True)
+    prob = O.Problem(w.X, w.y, w.offsets, w.probes, w.rank, compensate=True)
+    ctx.nugpr_build_blocks(w.theta)
+    blocks, Cm = prob.assemble(w.theta)
+    lam0 = O.compensation_lambda(Cm)
+    assert abs(ctx.nugpr_compensation_lambda() - lam0) <= 1e-11 * max(1.0, w.theta[-2])
+    Cg = ctx.nugpr_export(B.EXPORT_C).cpu().numpy().astype(np.float64)
+    np.testing.assert_allclose(Cg, Cm - lam0 * np.eye(Cm.shape[0]), rtol=2e-6, atol=1e-7)
+    op = prob.operator(w.theta)
+    rng = np.random.default_rng(31)
+    for ncols in sorted({1, w.n_probes + 1}):
+        D = rng.standard_normal((w.n, ncols)).astype(np.float32)
+        Q = ctx.nugpr_matvec(D).cpu().numpy().astype(np.float64)
+        assert relmax(Q, op(D.astype(np.float64))) < 1e-5
+    assert ctx.nugpr_precond_factor()[0] == 0
+    fac = O.Factor(prob, w.theta)
+    theta2 = w.theta * (1.0 + 0.03 * np.cos(np.arange(w.theta.shape[0])))
+    iters_at = []
+    for th in (w.theta, theta2):
+        ref = O.mll(prob, fac, th, w.tol, w.max_iter)
+        out = ctx.nugpr_mll(th)
+        assert out["code"] == 0, out
+        for key in ("quad", "logdet", "nll"):
+            assert abs(out[key] - ref[key]) <= 1e-4 * abs(ref[key]), (key, out[key], ref[key])
+        assert abs(out["max_iters_used"] - int(ref["iters"].max())) <= 2
+        iters_at.append(int(out["max_iters_used"]))
+    # Section 3.3: with the factor of the SAME theta the preconditioned system has at most n_c r + 1
+    # distinct eigenvalues, so CG needs at most that many iterations (one more allowed for rounding)
+    assert iters_at[0] <= w.n_clusters * w.rank + 2
+    phi = np.log(w.theta)
+    step = ctx.nugpr_train_step(phi, np.zeros(ctx.p), np.zeros(ctx.p), 0)
+    g = O.fd_gradient(prob, fac, phi, w.fd_step, w.tol, w.max_iter)
+    gerr = float(np.linalg.norm(step["grad"] - g) / np.linalg.norm(g))
+    record_metric("compensated:" + w.name, lambda0=lam0, nll_err=abs(out["nll"] - ref["nll"]) / abs(ref["nll"]),
+                  grad_err=gerr, iters=int(out["max_iters_used"]))
+    assert gerr < max(1e-4, GRAD_FLOOR.get(case, 0.0)), gerr
+    ctx.close()
+
+
+def test_compensation_makes_an_indefinite_problem_solvable_and_is_limited_to_small_couplings(lib):
+    w = COMP_CASES["indefinite"]()
+    plain = make_ctx(lib, w)
+    plain.nugpr_build_blocks(w.theta)
+    assert plain.nugpr_precond_factor()[0] == 0
+    assert plain.nugpr_mll(w.theta)["code"] == B.NUGPR_INDEFINITE
+    plain.close()
+    comp = make_ctx(lib, w, compensate=True)
+    comp.nugpr_build_blocks(w.theta)
+    assert comp.nugpr_precond_factor()[0] == 0
+    out = comp.nugpr_mll(w.theta)
+    assert out["code"] == 0 and np.isfinite(out["nll"])
+    # prediction runs on the compensated operator as well
+    prob = O.Problem(w.X, w.y, w.offsets, w.probes, w.rank, compensate=True)
+    fac = O.Factor(prob, w.theta)
+    Xt = I.test_points(w, 7, seed=2)
+    ref = O.predict(prob, fac, w.theta, Xt, w.tol, w.max_iter)
+    got = comp.nugpr_predict(w.theta, Xt)
+    assert np.max(np.abs(got["mean"] - ref["mean"])) <= 1e-4 * np.max(np.abs(ref["mean"]))
+    assert np.max(np.abs(got["var"] - ref["var"])) <= 1e-4 * w.theta[-2]
+    comp.close()
+    big = I.make_config("C2", scale=0.3)             # n_c r = 10 x 64 = 640 > 512
+    with pytest.raises(B.NugprError) as e:
+        make_ctx(lib, big, compensate=True)
+    assert e.value.code == B.NUGPR_ERR_INVALID
+
+
 def test_stale_factor_is_reused_across_theta(lib):
     # Section 3.2: the factor of theta_0 preconditions K(theta') too; eq. (logdet) stays exact
     w = small_ragged(seed=11, t=16)
