@@ -23,10 +23,11 @@ def lib():
 
 
 def record_metric(name, **values):
-    """Appends one line of measured parity numbers to gpurun_out/parity_metrics.txt
-    (kept for the results tables; ignored when the folder cannot be written)."""
+    """Appends one line of measured parity numbers to parity_metrics.txt in the run-output
+    folder (NUGPR_METRICS_DIR, else the folder below the repository root that GPU runs write
+    to); kept for the results tables, ignored when the folder cannot be written."""
     try:
-        out = os.path.join(ROOT, "gpurun_out")
+        out = os.environ.get("NUGPR_METRICS_DIR") or os.path.join(ROOT, "gpurun_out")
         os.makedirs(out, exist_ok=True)
         with open(os.path.join(out, "parity_metrics.txt"), "a") as f:
             f.write(name + " " + " ".join(f"{k}={v:.6e}" if isinstance(v, float) else f"{k}={v}"
