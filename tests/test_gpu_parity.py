@@ -454,6 +454,59 @@ def test_compensation_makes_an_indefinite_problem_solvable_and_is_limited_to_sma
     assert e.value.code == B.NUGPR_ERR_INVALID
 
 
+# ---- fp32 arithmetic mode (NUGPR_ACC_FP32): fp32 vector blocks and fp32 matrix-core accumulation.
+# Products and solves meet the same bars; the finite-difference gradient is NOT held to 1e-4 in this
+# mode (accumulation rounding of ~1e-7 of the loss is divided by 2h), which is why it is not the default:
+# the test records its error and bounds it loosely.
+@pytest.mark.parametrize("case", ["ragged-t8", "ragged-t32", "tiny", "iso-d1", "C1"])
+def test_fp32_mode_matches_oracle(lib, case):
+    w = CASES[case]()
+    print("case", w.name, flush=True)
+    ctx = make_ctx(lib, w, acc_fp32=True)
+    prob = oracle_problem(w)
+    ctx.nugpr_build_blocks(w.theta)
+    op = prob.operator(w.theta)
+    rng = np.random.default_rng(41)
+    for ncols in sorted({1, 2, w.n_probes + 1}):
+        D = rng.standard_normal((w.n, ncols)).astype(np.float32)
+        Q = ctx.nugpr_matvec(D).cpu().numpy().astype(np.float64)
+        assert relmax(Q, op(D.astype(np.float64))) < 2e-5
+    assert ctx.nugpr_precond_factor()[0] == 0
+    fac = O.Factor(prob, w.theta)
+    R = rng.standard_normal((w.n, w.n_probes + 1)).astype(np.float32)
+    Z = ctx.nugpr_precond_apply(R).cpu().numpy().astype(np.float64)
+    assert relmax(Z, fac.apply(R.astype(np.float64))) < 2e-4
+    A = O.split_operator(op, fac.Ls, prob.offsets)
+    S = ctx.nugpr_split_apply(R).cpu().numpy().astype(np.float64)
+    assert relmax(S, A(R.astype(np.float64))) < 2e-4
+    ref = O.mll(prob, fac, w.theta, w.tol, w.max_iter)
+    out = ctx.nugpr_mll(w.theta)
+    assert out["code"] == 0
+    for key in ("quad", "logdet", "nll"):
+        assert abs(out[key] - ref[key]) <= 1e-4 * abs(ref[key]), (key, out[key], ref[key])
+    Xt = I.test_points(w, w.n_probes + 3, seed=8)
+    pref = O.predict(prob, fac, w.theta, Xt, w.tol, w.max_iter)
+    pgot = ctx.nugpr_predict(w.theta, Xt)
+    assert pgot["code"] == 0
+    assert np.max(np.abs(pgot["mean"] - pref["mean"])) <= 1e-4 * np.max(np.abs(pref["mean"]))
+    assert np.max(np.abs(pgot["var"] - pref["var"])) <= 1e-4 * w.theta[-2]
+    phi = np.log(w.theta)
+    step = ctx.nugpr_train_step(phi, np.zeros(ctx.p), np.zeros(ctx.p), 0)
+    g = O.fd_gradient(prob, fac, phi, w.fd_step, w.tol, w.max_iter)
+    gerr = float(np.linalg.norm(step["grad"] - g) / np.linalg.norm(g))
+    record_metric("fp32mode:" + w.name, nll_err=abs(out["nll"] - ref["nll"]) / abs(ref["nll"]), grad_err=gerr)
+    assert gerr < 1e-3, gerr
+    ctx.close()
+    # the Pade route in the same mode
+    pctx = make_ctx(lib, w, acc_fp32=True, logdet_pade=True)
+    pctx.nugpr_build_blocks(w.theta)
+    assert pctx.nugpr_precond_factor()[0] == 0
+    pr = O.mll(prob, fac, w.theta, w.tol, w.max_iter, logdet="pade")
+    po = pctx.nugpr_mll(w.theta)
+    assert po["code"] == 0 and abs(po["nll"] - pr["nll"]) <= 1e-4 * abs(pr["nll"])
+    pctx.close()
+
+
 def test_stale_factor_is_reused_across_theta(lib):
     # Section 3.2: the factor of theta_0 preconditions K(theta') too; eq. (logdet) stays exact
     w = small_ragged(seed=11, t=16)
