@@ -507,6 +507,77 @@ def test_fp32_mode_matches_oracle(lib, case):
     pctx.close()
 
 
+# ---- degenerate and extreme shapes: no probes, one cluster, rank = cluster size (exact covariance),
+# the largest dimension, a dimension that is no multiple of the matrix-core depth, clusters of one point
+DEGENERATE = {
+    "no-probes": (lambda: I.make_small(n_clusters=3, sizes=[70, 64, 30], d=2, rank=4, t=0, seed=51, ell=1.5, spacing=4.0,
+                                       sigma_blob=0.3, tol=1e-8, max_iter=60), False),
+    "one-cluster": (lambda: I.make_small(n_clusters=1, sizes=[150], d=3, rank=5, t=4, seed=52, ell=1.2, tol=1e-8,
+                                         max_iter=60), False),
+    "rank-is-size": (lambda: I.make_small(n_clusters=3, sizes=[12, 12, 12], d=2, rank=12, t=4, seed=53, ell=1.5,
+                                          spacing=2.0, sigma_blob=0.5, tol=1e-8, max_iter=80), False),
+    "d64": (lambda: I.make_small(n_clusters=2, sizes=[80, 50], d=64, rank=3, t=4, seed=54, ell=8.0, spacing=3.0,
+                                 sigma_blob=0.5, tol=1e-8, max_iter=60), True),
+    "d7-tiny-clusters": (lambda: I.make_small(n_clusters=3, sizes=[65, 1, 2], d=7, rank=1, t=3, seed=55, ell=2.5,
+                                              spacing=3.0, sigma_blob=0.5, tol=1e-8, max_iter=60), True),
+    "singletons": (lambda: I.make_small(n_clusters=6, sizes=[1, 1, 1, 1, 1, 1], d=2, rank=1, t=2, seed=56, ell=1.0,
+                                        spacing=1.5, sigma_blob=0.1, tol=1e-10, max_iter=60), False),
+}
+
+
+@pytest.mark.parametrize("case", sorted(DEGENERATE))
+def test_degenerate_shapes_match_oracle(lib, case):
+    mk, compensate = DEGENERATE[case]       # the strongly coupled ones are only definite with the compensation
+    w = mk()
+    print("case", case, w.name, flush=True)
+    ctx = make_ctx(lib, w, compensate=compensate)
+    prob = O.Problem(w.X, w.y, w.offsets, w.probes, w.rank, compensate=compensate)
+    ctx.nugpr_build_blocks(w.theta)
+    blocks, Cm = prob.assemble(w.theta)
+    for i in range(w.n_clusters):
+        Ki = ctx.nugpr_export(B.EXPORT_K, i).cpu().numpy().astype(np.float64)
+        np.testing.assert_allclose(Ki, blocks[i], rtol=2e-6, atol=1e-7)
+    op = prob.operator(w.theta)
+    rng = np.random.default_rng(61)
+    D = rng.standard_normal((w.n, w.n_probes + 1)).astype(np.float32)
+    Q = ctx.nugpr_matvec(D).cpu().numpy().astype(np.float64)
+    assert relmax(Q, op(D.astype(np.float64))) < 1e-5
+    assert ctx.nugpr_precond_factor()[0] == 0
+    fac = O.Factor(prob, w.theta)
+    if case == "rank-is-size":
+        # every point is a representative: K' is the exact covariance (Section 3.3)
+        ell, alpha, s2 = O.split_theta(w.theta, w.d)
+        Kex = O.rbf(prob.X, prob.X, ell, alpha) + s2 * np.eye(w.n)
+        assert relmax(Q, Kex @ D.astype(np.float64)) < 1e-5
+    code, X, iters, _, _ = ctx.nugpr_pcg_solve(fac.B.astype(np.float32))
+    assert code == 0
+    Xo = O.pcg(op, fac.apply, fac.B.astype(np.float32).astype(np.float64), w.tol, w.max_iter)[0]
+    Xg = X.cpu().numpy().astype(np.float64)
+    for c in range(w.n_probes + 1):
+        assert np.linalg.norm(Xg[:, c] - Xo[:, c]) <= 1e-4 * np.linalg.norm(Xo[:, c]), c
+    out = ctx.nugpr_mll(w.theta)
+    assert out["code"] == 0
+    if w.n_probes > 0:
+        ref = O.mll(prob, fac, w.theta, w.tol, w.max_iter)
+        for key in ("quad", "logdet", "nll"):
+            assert abs(out[key] - ref[key]) <= 1e-4 * abs(ref[key]) + 1e-9, (key, out[key], ref[key])
+        if case == "one-cluster":
+            # the preconditioner is the operator itself: one iteration in exact arithmetic, one more
+            # here to take the fp32 factor's 1e-6 residual below the 1e-8 tolerance
+            assert out["max_iters_used"] <= 2
+    else:
+        # no probes: the quadratic term is exact, the log-determinant is the preconditioner's part alone
+        quad = float(prob.y @ O.pcg(op, fac.apply, prob.y[:, None].copy(), w.tol, w.max_iter)[0][:, 0])
+        assert abs(out["quad"] - quad) <= 1e-4 * abs(quad)
+        assert abs(out["logdet"] - fac.logdetM) <= 1e-5 * abs(fac.logdetM) + 1e-4
+    Xt = I.test_points(w, 5, seed=3)
+    pref = O.predict(prob, fac, w.theta, Xt, w.tol, w.max_iter)
+    pgot = ctx.nugpr_predict(w.theta, Xt)
+    assert np.max(np.abs(pgot["mean"] - pref["mean"])) <= 1e-4 * max(np.max(np.abs(pref["mean"])), 1e-12)
+    assert np.max(np.abs(pgot["var"] - pref["var"])) <= 1e-4 * w.theta[-2]
+    ctx.close()
+
+
 def test_stale_factor_is_reused_across_theta(lib):
     # Section 3.2: the factor of theta_0 preconditions K(theta') too; eq. (logdet) stays exact
     w = small_ragged(seed=11, t=16)
