@@ -238,6 +238,8 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   if (e != hipSuccess) return fail(hip_fail(e, "hipHostMalloc(buf)"));
   std::memset(c->h_flags, 0, sizeof(HostFlags));
 
+  e = hipMemsetAsync(c->d_state, 0, sizeof(PcgState), s);         // counters in it start at zero
+  if (e != hipSuccess) return fail(hip_fail(e, "clear solver state"));
   e = hipMemcpyAsync(c->d_cl, L.cl.data(), sizeof(ClusterInfo) * L.nc, hipMemcpyHostToDevice, s);
   if (e != hipSuccess) return fail(hip_fail(e, "upload cluster table"));
   Tables t;

@@ -103,7 +103,7 @@ struct PcgState {
   int32_t n_active;
   int32_t indefinite;
   int32_t bad_cluster;    // Cholesky: lowest failing cluster index, or INT_MAX
-  int32_t pad_;
+  int32_t tail_count;     // workgroups of the end-of-solve report that are done (returns to 0)
 };
 
 // host-visible mirror (pinned)
@@ -112,6 +112,10 @@ struct HostFlags {
   int32_t indefinite;
   int32_t bad_cluster;
   int32_t pad_;
+  // Sequence numbers the device stores AFTER the data they announce (system-scope fence in between):
+  // the host polls them in pinned memory instead of paying a stream synchronisation's wake-up latency.
+  uint64_t seq;        // the three fields above belong to stop test number `seq`
+  uint64_t tail_seq;   // the end-of-solve record in the pinned buffer belongs to report number `tail_seq`
 };
 
 struct Layout {
@@ -177,6 +181,8 @@ struct nugpr_ctx {
   std::vector<hipEvent_t> prof_ev;       // start/stop pairs
   int prof_used = 0;                     // pairs recorded since the last read
   nugpr::HostFlags* h_flags = nullptr;   // pinned
+  uint64_t flag_seq = 0, tail_seq = 0;   // last numbers handed to the device
+  int expect_iters[2] = {1, 1};          // iterations the last solve of each system took (when to report early)
   double* h_buf = nullptr;               // pinned scratch for small device->host reads
   size_t h_buf_doubles = 0;
   float diag_residual = 0.f;             // (alpha + sigma^2) - float(alpha + sigma^2) of the stored blocks

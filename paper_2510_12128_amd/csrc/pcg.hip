@@ -183,7 +183,7 @@ __global__ __launch_bounds__(256) void k_update_d(VT* __restrict__ D, const VT* 
   }
 }
 
-__global__ void k_copy_flags(PcgState* __restrict__ st, HostFlags* __restrict__ out, int T) {
+__global__ void k_copy_flags(PcgState* __restrict__ st, HostFlags* __restrict__ out, int T, uint64_t seq) {
   int n_active = 0, indef = 0;
   for (int c = 0; c < T; ++c) { n_active += st->active[c]; indef |= st->indef[c]; }
   st->n_active = n_active;
@@ -191,6 +191,54 @@ __global__ void k_copy_flags(PcgState* __restrict__ st, HostFlags* __restrict__ 
   out->n_active = n_active;
   out->indefinite = indef;
   out->bad_cluster = st->bad_cluster;
+  __threadfence_system();
+  *reinterpret_cast<volatile uint64_t*>(&out->seq) = seq;
+}
+
+// End-of-solve report, written by the device straight into pinned host memory: the per-column state,
+// <b_c, x_c> summed from the per-workgroup partials (fixed order), and the first `rows` rows of the
+// alpha / beta logs.  One workgroup per column (each sums its column; they share the copies); the
+// workgroup that finishes last publishes the sequence number.
+__global__ __launch_bounds__(256) void k_pcg_tail(PcgState* __restrict__ st, const double* __restrict__ partial,
+                                                  int nblocks, int T, int want_bx, const double* __restrict__ alog,
+                                                  const double* __restrict__ blog, int rows,
+                                                  PcgState* __restrict__ h_state, double* __restrict__ h_bx,
+                                                  double* __restrict__ h_alog, double* __restrict__ h_blog,
+                                                  HostFlags* __restrict__ flags, uint64_t seq) {
+  __shared__ double red[256];
+  __shared__ int last;
+  const int tid = threadIdx.x, c = blockIdx.x;
+  if (want_bx) {
+    const double v = sum_partials(partial, nblocks, c, red, tid);
+    if (tid == 0) h_bx[c] = v;
+  }
+  const int words = (int)(sizeof(PcgState) / sizeof(int32_t));
+  const int32_t* src = reinterpret_cast<const int32_t*>(st);
+  int32_t* dst = reinterpret_cast<int32_t*>(h_state);
+  for (int i = c * 256 + tid; i < words; i += 256 * T) dst[i] = src[i];
+  const int cnt = rows * MAX_COLS;
+  for (int i = c * 256 + tid; i < cnt; i += 256 * T) { h_alog[i] = alog[i]; h_blog[i] = blog[i]; }
+  __threadfence_system();
+  __syncthreads();
+  if (tid == 0) last = (atomicAdd(&st->tail_count, 1) == T - 1);
+  __syncthreads();
+  if (last && tid == 0) {
+    st->tail_count = 0;
+    __threadfence_system();
+    *reinterpret_cast<volatile uint64_t*>(&flags->tail_seq) = seq;
+  }
+}
+
+// Waits until the device has stored `want` in a pinned sequence slot: a short poll (the usual case:
+// microseconds after the kernel ends), then an ordinary stream synchronisation.
+static int wait_seq(const volatile uint64_t* slot, uint64_t want, hipStream_t s) {
+  for (int spin = 0; spin < 200000; ++spin) {
+    if (*slot == want) return NUGPR_OK;
+    __builtin_ia32_pause();
+  }
+  NUGPR_HIP(hipStreamSynchronize(s));
+  if (*slot != want) { set_error("the device did not report the end of a solver step"); return NUGPR_ERR_HIP; }
+  return NUGPR_OK;
 }
 
 // start of a solve: X = 0, R = B, the alpha / beta logs cleared and, when the first preconditioned
@@ -446,6 +494,23 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
   // that start inactive (zero right-hand side) are skipped by every kernel on their own flag, and
   // the host learns the count at the first stop test.
   c->h_flags->n_active = 1;
+  const size_t cnt = (size_t)max_iter * MAX_COLS;
+  PcgState* hs = reinterpret_cast<PcgState*>(c->h_buf + 2 * cnt);
+  double* hdot = c->h_buf + 2 * cnt + (sizeof(PcgState) + sizeof(double) - 1) / sizeof(double);
+  const bool want_logs = alpha || beta;
+  // The end-of-solve report (k_pcg_tail) is issued INSIDE the iteration that is expected to be the last
+  // one, right behind its stop test, so that it is already on the host when the stop test says "done";
+  // a solve that ends earlier or later than the previous one of its kind gets the report after the loop.
+  const int expect = c->expect_iters[plain ? 1 : 0];
+  auto issue_tail = [&](int rows) -> int {
+    if (extras) hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, B, (const VT*)X, B, (const VT*)X, n, T, c->dotpart);
+    c->tail_seq += 1;
+    hipLaunchKernelGGL(k_pcg_tail, dim3(T), dim3(256), 0, s, c->d_state, c->dotpart, nb, T, extras ? 1 : 0, c->alog,
+                       c->blog, want_logs ? rows : 0, hs, hdot, c->h_buf, c->h_buf + cnt, c->h_flags, c->tail_seq);
+    NUGPR_HIP(hipGetLastError());
+    return NUGPR_OK;
+  };
+  bool tail_current = false;
   while (it < max_iter && c->h_flags->n_active > 0) {
     if ((rc = plain ? run_pade_q(c, D, Q, T, s) : run_matvec(c, D, Q, T, s))) return rc;
     hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, D, Q, D, Q, n, T, c->dotpart);
@@ -454,9 +519,15 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
     // stop test first: when every column has converged the preconditioner apply is not needed
     hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, R, R, R, R, n, T, c->dotpart);
     hipLaunchKernelGGL(k_pcg_check, dim3(T), dim3(256), 0, s, c->d_state, c->dotpart, nb, it, tol2);
-    hipLaunchKernelGGL(k_copy_flags, dim3(1), dim3(1), 0, s, c->d_state, c->h_flags, T);
+    c->flag_seq += 1;
+    hipLaunchKernelGGL(k_copy_flags, dim3(1), dim3(1), 0, s, c->d_state, c->h_flags, T, c->flag_seq);
     NUGPR_HIP(hipGetLastError());
-    NUGPR_HIP(hipStreamSynchronize(s));
+    tail_current = false;
+    if (it + 1 >= expect || it + 1 >= max_iter) {
+      if ((rc = issue_tail(it + 1))) return rc;
+      tail_current = true;
+    }
+    if ((rc = wait_seq(&c->h_flags->seq, c->flag_seq, s))) return rc;
     const int j = it++;
     if (c->h_flags->indefinite) indefinite = true;
     if (c->h_flags->n_active == 0 || it >= max_iter) break;
@@ -466,22 +537,9 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
     hipLaunchKernelGGL((k_update_d<VT>), dim3(eg), dim3(256), 0, s, D, Zr, c->d_state, n, T);
     NUGPR_HIP(hipGetLastError());
   }
-  // per-column records
-  // per-column records and (if asked for) the coefficient logs: one synchronisation for all of them
-  const size_t cnt = (size_t)max_iter * MAX_COLS;
-  PcgState* hs = reinterpret_cast<PcgState*>(c->h_buf + 2 * cnt);
-  NUGPR_HIP(hipMemcpyAsync(hs, c->d_state, sizeof(PcgState), hipMemcpyDeviceToHost, s));
-  double* hdot = c->h_buf + 2 * cnt + (sizeof(PcgState) + sizeof(double) - 1) / sizeof(double);
-  if (extras) {
-    hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, B, X, B, X, n, T, c->dotpart);
-    NUGPR_HIP(hipGetLastError());
-    NUGPR_HIP(hipMemcpyAsync(hdot, c->dotpart, (size_t)nb * MAX_COLS * sizeof(double), hipMemcpyDeviceToHost, s));
-  }
-  if (alpha || beta) {
-    NUGPR_HIP(hipMemcpyAsync(c->h_buf, c->alog, cnt * sizeof(double), hipMemcpyDeviceToHost, s));
-    NUGPR_HIP(hipMemcpyAsync(c->h_buf + cnt, c->blog, cnt * sizeof(double), hipMemcpyDeviceToHost, s));
-  }
-  NUGPR_HIP(hipStreamSynchronize(s));
+  c->expect_iters[plain ? 1 : 0] = it > 0 ? it : 1;
+  if (!tail_current && (rc = issue_tail(it))) return rc;
+  if ((rc = wait_seq(&c->h_flags->tail_seq, c->tail_seq, s))) return rc;
   bool all_conv = true;
   int mx = 0;
   for (int col = 0; col < T; ++col) {
@@ -493,18 +551,16 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
   if (max_it_used) *max_it_used = mx;
   if (extras) {
     for (int col = 0; col < T; ++col) {
-      double acc = 0.0;
-      for (int b = 0; b < nb; ++b) acc += hdot[(size_t)b * MAX_COLS + col];      // block order, as run_dot_col
-      extras->bx[col] = acc;
+      extras->bx[col] = hdot[col];
       extras->rho0[col] = hs->rho0[col];
     }
   }
   if (alpha || beta) {
     const double* ha = c->h_buf;
     for (int j = 0; j < max_iter; ++j)
-      for (int col = 0; col < T; ++col) {
-        if (alpha) alpha[(size_t)j * T + col] = ha[(size_t)j * MAX_COLS + col];
-        if (beta) beta[(size_t)j * T + col] = ha[cnt + (size_t)j * MAX_COLS + col];
+      for (int col = 0; col < T; ++col) {                 // rows past the last iteration were never written: zero
+        if (alpha) alpha[(size_t)j * T + col] = j < it ? ha[(size_t)j * MAX_COLS + col] : 0.0;
+        if (beta) beta[(size_t)j * T + col] = j < it ? ha[cnt + (size_t)j * MAX_COLS + col] : 0.0;
       }
   }
   if (indefinite) return NUGPR_INDEFINITE;
