@@ -383,6 +383,7 @@ int launch_factor(nugpr_ctx* c, hipStream_t s) {
   c->z0_ready = false;
   int rc = run_precond(c, c->Bv, c->Z0v, L.T, s);
   if (rc) return rc;
+  if ((rc = store_known_starts(c, s))) return rc;
   c->z0_ready = true;
   c->factor_gen = c->build_gen;
   return NUGPR_OK;

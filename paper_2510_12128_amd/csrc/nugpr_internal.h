@@ -104,6 +104,10 @@ struct PcgState {
   int32_t indefinite;
   int32_t bad_cluster;    // Cholesky: lowest failing cluster index, or INT_MAX
   int32_t tail_count;     // workgroups of the end-of-solve report that are done (returns to 0)
+  // <b, b> and <b, z_0> of the two right-hand-side blocks the context owns ([y | L Z] with z_0 = M^-1 b,
+  // and the probe block [0 | Z] with z_0 = b): they depend on the factor only and are taken with it
+  double known_bb[2][MAX_COLS];
+  double known_rz[2][MAX_COLS];
 };
 
 // host-visible mirror (pinned)
@@ -256,6 +260,7 @@ int run_pcg(nugpr_ctx* c, const void* B, void* X, int T, int32_t* iters, double*
 int run_split_op(nugpr_ctx* c, const void* D, void* out, int T, hipStream_t s);
 int run_dot2(nugpr_ctx* c, const void* A0, const void* B0, const void* A1, const void* B1, int T, double* out0,
              double* out1, hipStream_t s);
+int store_known_starts(nugpr_ctx* c, hipStream_t s);
 int run_dot_col(nugpr_ctx* c, const void* A, const void* B, int T, double* out_host, hipStream_t s);
 int to_internal(nugpr_ctx* c, const float* src, void* dst, int64_t count, hipStream_t s);
 int from_internal(nugpr_ctx* c, const void* src, float* dst, int64_t count, hipStream_t s);

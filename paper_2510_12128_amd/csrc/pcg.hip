@@ -92,6 +92,32 @@ __global__ __launch_bounds__(256) void k_pcg_begin(PcgState* __restrict__ st, co
   }
 }
 
+// the same from the values kept with the factor (which = 0: [y | L Z], 1: the probe block)
+__global__ void k_pcg_begin_known(PcgState* __restrict__ st, int which, int T) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= T) return;
+  const double bb = st->known_bb[which][c], rz = st->known_rz[which][c];
+  const bool act = bb > 0.0 && rz == rz;
+  st->bnorm2[c] = bb;
+  st->rho[c] = rz;
+  st->rho0[c] = rz;
+  st->alpha[c] = 0.0;
+  st->beta[c] = 0.0;
+  st->active[c] = act ? 1 : 0;
+  st->iters[c] = 0;
+  st->converged[c] = (bb == 0.0) ? 1 : 0;
+  st->indef[c] = 0;
+}
+
+__global__ __launch_bounds__(256) void k_store_known(PcgState* __restrict__ st, const double* __restrict__ partial,
+                                                     int nblocks, int which) {
+  __shared__ double red[256];
+  const int tid = threadIdx.x, c = blockIdx.x;
+  const double bb = sum_partials(partial, nblocks, c, red, tid);
+  const double rz = sum_partials(partial + (int64_t)nblocks * MAX_COLS, nblocks, c, red, tid);
+  if (tid == 0) { st->known_bb[which][c] = bb; st->known_rz[which][c] = rz; }
+}
+
 // alpha_c = rho_c / <d, K'd>_c for the active columns
 __global__ __launch_bounds__(256) void k_pcg_alpha(PcgState* __restrict__ st, const double* __restrict__ partial,
                                                    int nblocks, int iter, double* __restrict__ alog) {
@@ -151,10 +177,11 @@ __global__ __launch_bounds__(256) void k_pcg_beta(PcgState* __restrict__ st, con
 
 // X += D diag(alpha); R -= Q diag(alpha)   (alpha stays in fp64: rounding it to fp32 would
 // scale the whole step coherently)
+// (first step of a solve: X starts from zero and R from Rin = b, neither of which is read or written before)
 template <typename VT>
-__global__ __launch_bounds__(256) void k_update_xr(VT* __restrict__ X, VT* __restrict__ R,
+__global__ __launch_bounds__(256) void k_update_xr(VT* __restrict__ X, VT* R, const VT* Rin,
                                                    const VT* __restrict__ D, const VT* __restrict__ Q,
-                                                   const PcgState* __restrict__ st, int64_t n, int T) {
+                                                   const PcgState* __restrict__ st, int64_t n, int T, int first) {
   const int rpp = 256 / T;
   const int tid = threadIdx.x;
   const int myrow = tid / T, col = tid - myrow * T;
@@ -162,14 +189,14 @@ __global__ __launch_bounds__(256) void k_update_xr(VT* __restrict__ X, VT* __res
   const double a = st->alpha[col];
   for (int64_t r = (int64_t)blockIdx.x * rpp + myrow; r < n; r += (int64_t)gridDim.x * rpp) {
     const int64_t idx = r * T + col;
-    X[idx] = (VT)fma(a, (double)D[idx], (double)X[idx]);
-    R[idx] = (VT)fma(-a, (double)Q[idx], (double)R[idx]);
+    X[idx] = first ? (VT)(a * (double)D[idx]) : (VT)fma(a, (double)D[idx], (double)X[idx]);
+    R[idx] = (VT)fma(-a, (double)Q[idx], (double)Rin[idx]);
   }
 }
 
 // D = Z + D diag(beta) for active columns, 0 for stopped ones
 template <typename VT>
-__global__ __launch_bounds__(256) void k_update_d(VT* __restrict__ D, const VT* __restrict__ Z,
+__global__ __launch_bounds__(256) void k_update_d(VT* D, const VT* Din, const VT* __restrict__ Z,
                                                   const PcgState* __restrict__ st, int64_t n, int T) {
   const int rpp = 256 / T;
   const int tid = threadIdx.x;
@@ -179,7 +206,7 @@ __global__ __launch_bounds__(256) void k_update_d(VT* __restrict__ D, const VT* 
   const bool act = st->active[col] != 0;
   for (int64_t r = (int64_t)blockIdx.x * rpp + myrow; r < n; r += (int64_t)gridDim.x * rpp) {
     const int64_t idx = r * T + col;
-    D[idx] = act ? (VT)fma(bta, (double)D[idx], (double)Z[idx]) : (VT)0;
+    D[idx] = act ? (VT)fma(bta, (double)Din[idx], (double)Z[idx]) : (VT)0;
   }
 }
 
@@ -241,19 +268,18 @@ static int wait_seq(const volatile uint64_t* slot, uint64_t want, hipStream_t s)
   return NUGPR_OK;
 }
 
-// start of a solve: X = 0, R = B, the alpha / beta logs cleared and, when the first preconditioned
-// residual is already known (Z0 not null), D = Z0
+// start of a solve on a caller's right-hand sides: X = 0, R = B and, when the first direction is known
+// (Z0 not null), D = Z0.  (The alpha / beta logs need no clearing: every row the host reads is written
+// during the solve.)
 template <typename VT>
 __global__ void k_pcg_init(VT* __restrict__ X, VT* __restrict__ R, const VT* __restrict__ B,
-                           const VT* __restrict__ Z0, VT* __restrict__ D, int64_t count,
-                           double* __restrict__ alog, double* __restrict__ blog, int64_t nlog) {
+                           const VT* __restrict__ Z0, VT* __restrict__ D, int64_t count) {
   const int64_t i0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (int64_t)gridDim.x * blockDim.x;
   if (Z0) {
     for (int64_t i = i0; i < count; i += stride) { X[i] = (VT)0; R[i] = B[i]; D[i] = Z0[i]; }
   } else {
     for (int64_t i = i0; i < count; i += stride) { X[i] = (VT)0; R[i] = B[i]; }
   }
-  for (int64_t i = i0; i < nlog; i += stride) { alog[i] = 0.0; blog[i] = 0.0; }
 }
 
 template <typename SRC, typename DST>
@@ -480,14 +506,24 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
   // Without a preconditioner (the Pade system, already preconditioned) z = r throughout.
   const bool plain = system == PCG_PADE_Q;
   const VT* Zr = plain ? R : Z;
-  const bool known = plain || ((const void*)B == (const void*)c->Bv && T == L.T && c->z0_ready);
-  const VT* z0 = plain ? B : (const VT*)c->Z0v;
-  hipLaunchKernelGGL((k_pcg_init<VT>), dim3(1024), dim3(256), 0, s, X, R, B, known ? z0 : (const VT*)nullptr,
-                     D, n * T, c->alog, c->blog, (int64_t)max_iter * MAX_COLS);
-  if (!known && (rc = run_precond(c, R, D, T, s))) return rc;
-  hipLaunchKernelGGL((k_dot<2, VT>), dim3(nb), dim3(256), 0, s, R, R, R, D, n, T, c->dotpart);
-  hipLaunchKernelGGL(k_pcg_begin, dim3(T), dim3(256), 0, s, c->d_state, c->dotpart, nb);
+  // Solves on the two right-hand-side blocks the context owns start from values kept with the factor:
+  // z_0 = M^-1 b (or b itself for the Pade system), <b, b> and <b, z_0>.  Nothing is initialised then:
+  // the first update reads b in the place of r and writes x without reading it, and the first direction
+  // is z_0 where it lies.
+  const bool own = T == L.T && c->z0_ready && (const void*)B == (plain ? (const void*)c->Pv : (const void*)c->Bv);
+  const VT* Dcur = D;                    // the direction the operator is applied to
+  if (own) {
+    hipLaunchKernelGGL(k_pcg_begin_known, dim3(1), dim3(64), 0, s, c->d_state, plain ? 1 : 0, T);
+    Dcur = plain ? B : (const VT*)c->Z0v;
+  } else {
+    // x_0 = 0, r_0 = b, d_0 = z_0 = M^-1 r_0 written straight into D
+    hipLaunchKernelGGL((k_pcg_init<VT>), dim3(1024), dim3(256), 0, s, X, R, B, plain ? B : (const VT*)nullptr, D, n * T);
+    if (!plain && (rc = run_precond(c, R, D, T, s))) return rc;
+    hipLaunchKernelGGL((k_dot<2, VT>), dim3(nb), dim3(256), 0, s, (const VT*)R, (const VT*)R, (const VT*)R, (const VT*)D, n, T, c->dotpart);
+    hipLaunchKernelGGL(k_pcg_begin, dim3(T), dim3(256), 0, s, c->d_state, c->dotpart, nb);
+  }
   NUGPR_HIP(hipGetLastError());
+  bool first = own;
   int it = 0;
   bool indefinite = false;
   // The first iteration is issued without asking the device whether any column is active: columns
@@ -512,10 +548,12 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
   };
   bool tail_current = false;
   while (it < max_iter && c->h_flags->n_active > 0) {
-    if ((rc = plain ? run_pade_q(c, D, Q, T, s) : run_matvec(c, D, Q, T, s))) return rc;
-    hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, D, Q, D, Q, n, T, c->dotpart);
+    if ((rc = plain ? run_pade_q(c, Dcur, Q, T, s) : run_matvec(c, Dcur, Q, T, s))) return rc;
+    hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, Dcur, (const VT*)Q, Dcur, (const VT*)Q, n, T, c->dotpart);
     hipLaunchKernelGGL(k_pcg_alpha, dim3(T), dim3(256), 0, s, c->d_state, c->dotpart, nb, it, c->alog);
-    hipLaunchKernelGGL((k_update_xr<VT>), dim3(eg), dim3(256), 0, s, X, R, D, Q, c->d_state, n, T);
+    hipLaunchKernelGGL((k_update_xr<VT>), dim3(eg), dim3(256), 0, s, X, R, first ? B : (const VT*)R, Dcur, (const VT*)Q,
+                       c->d_state, n, T, first ? 1 : 0);
+    first = false;
     // stop test first: when every column has converged the preconditioner apply is not needed
     hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, R, R, R, R, n, T, c->dotpart);
     hipLaunchKernelGGL(k_pcg_check, dim3(T), dim3(256), 0, s, c->d_state, c->dotpart, nb, it, tol2);
@@ -534,8 +572,9 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
     if (!plain && (rc = run_precond(c, R, Z, T, s))) return rc;
     hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, (const VT*)R, Zr, (const VT*)R, Zr, n, T, c->dotpart);
     hipLaunchKernelGGL(k_pcg_beta, dim3(T), dim3(256), 0, s, c->d_state, c->dotpart, nb, j, c->blog);
-    hipLaunchKernelGGL((k_update_d<VT>), dim3(eg), dim3(256), 0, s, D, Zr, c->d_state, n, T);
+    hipLaunchKernelGGL((k_update_d<VT>), dim3(eg), dim3(256), 0, s, D, Dcur, Zr, c->d_state, n, T);
     NUGPR_HIP(hipGetLastError());
+    Dcur = D;
   }
   c->expect_iters[plain ? 1 : 0] = it > 0 ? it : 1;
   if (!tail_current && (rc = issue_tail(it))) return rc;
@@ -560,11 +599,33 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
     for (int j = 0; j < max_iter; ++j)
       for (int col = 0; col < T; ++col) {                 // rows past the last iteration were never written: zero
         if (alpha) alpha[(size_t)j * T + col] = j < it ? ha[(size_t)j * MAX_COLS + col] : 0.0;
-        if (beta) beta[(size_t)j * T + col] = j < it ? ha[cnt + (size_t)j * MAX_COLS + col] : 0.0;
+        // (no beta follows the last iteration)
+        if (beta) beta[(size_t)j * T + col] = j < it - 1 ? ha[cnt + (size_t)j * MAX_COLS + col] : 0.0;
       }
   }
   if (indefinite) return NUGPR_INDEFINITE;
   return all_conv ? NUGPR_OK : NUGPR_NOT_CONVERGED;
+}
+
+template <typename VT>
+static int store_known_t(nugpr_ctx* c, hipStream_t s) {
+  const Layout& L = c->L;
+  const int nb = L.n_dot_blocks;
+  const VT *B = (const VT*)c->Bv, *Z0 = (const VT*)c->Z0v, *P = (const VT*)c->Pv;
+  hipLaunchKernelGGL((k_dot<2, VT>), dim3(nb), dim3(256), 0, s, B, B, B, Z0, (int64_t)L.n, L.T, c->dotpart);
+  hipLaunchKernelGGL(k_store_known, dim3(L.T), dim3(256), 0, s, c->d_state, c->dotpart, nb, 0);
+  if (L.t > 0) {
+    hipLaunchKernelGGL((k_dot<2, VT>), dim3(nb), dim3(256), 0, s, P, P, P, P, (int64_t)L.n, L.T, c->dotpart);
+    hipLaunchKernelGGL(k_store_known, dim3(L.T), dim3(256), 0, s, c->d_state, c->dotpart, nb, 1);
+  }
+  NUGPR_HIP(hipGetLastError());
+  return NUGPR_OK;
+}
+
+// <b, b> and <b, z_0> of the context's own right-hand-side blocks, kept in the device state (called by the
+// factorisation once B, z_0 = M^-1 B and the probe block exist)
+int store_known_starts(nugpr_ctx* c, hipStream_t s) {
+  return c->acc64 ? store_known_t<double>(c, s) : store_known_t<float>(c, s);
 }
 
 int run_pcg(nugpr_ctx* c, const void* B, void* X, int T, int32_t* iters, double* alpha, double* beta,
