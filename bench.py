@@ -155,8 +155,12 @@ def main():
 
     n, r, nc = ctx.n, ctx.rank, ctx.nc
     sizes = np.diff(w.offsets).astype(np.float64)
-    kv_alg_bytes = 4.0 * (float((sizes ** 2).sum()) + 2.0 * n * r + float(nc * r) ** 2 + 2.0 * n * T)
     dom_bytes = ctx.nugpr_profile_bytes(T)
+    # one product K'.D with the default one-hot basis: the dominant launch (K_diag and C streamed once, D and
+    # the S slabs read, Q and the P slabs written) + the projection S = W^T D (D read again, 8 bytes of index
+    # per point) + the expansion Q += W P (Q read and written).  W itself is not streamed.
+    vs = 8.0 if args.acc == "fp64" else 4.0
+    kv_alg_bytes = dom_bytes + vs * 3.0 * n * T + 8.0 * n
     dom_avg_ms = dom_ms / max(dom_launches, 1)
     achieved = dom_bytes / (dom_avg_ms * 1e-3) / 1e9 if dom_launches else 0.0
 

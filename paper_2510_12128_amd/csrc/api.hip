@@ -218,6 +218,9 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   c->Uv = w + L.o_U;
   c->x0 = w + L.o_x0;
   c->Z0v = w + L.o_Z0;
+  c->assign = reinterpret_cast<int32_t*>(w + L.o_assign);
+  c->rep_ptr = reinterpret_cast<int32_t*>(w + L.o_rep_ptr);
+  c->rep_pts = reinterpret_cast<int32_t*>(w + L.o_rep_pts);
   c->Pv = w + L.o_P;
   c->Spart = w + L.o_Spart;
   c->Ppart = w + L.o_Ppart;
@@ -259,6 +262,23 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   if ((rc = launch_setup(c, pb->reps, pb->W, s))) return fail(rc);
   e = hipStreamSynchronize(s);
   if (e != hipSuccess) return fail(hip_fail(e, "sync after setup"));
+  if (!pb->W) {
+    // default basis: the points of every representative, in ascending order (counting sort on the host, once)
+    std::vector<int32_t> as((size_t)L.n), ptr((size_t)L.ncr + 1, 0), pts((size_t)L.n);
+    e = hipMemcpy(as.data(), c->assign, as.size() * sizeof(int32_t), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail(hip_fail(e, "copy the basis assignment to the host"));
+    for (int64_t p = 0; p < L.n; ++p) {
+      if (as[p] < 0 || as[p] >= L.ncr) { set_error("internal: basis assignment out of range"); return fail(NUGPR_ERR_INVALID); }
+      ptr[as[p] + 1] += 1;
+    }
+    for (int a = 0; a < L.ncr; ++a) ptr[a + 1] += ptr[a];
+    std::vector<int32_t> fill(ptr.begin(), ptr.end() - 1);
+    for (int64_t p = 0; p < L.n; ++p) pts[fill[as[p]]++] = (int32_t)p;
+    e = hipMemcpy(c->rep_ptr, ptr.data(), ptr.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(c->rep_pts, pts.data(), pts.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return fail(hip_fail(e, "upload the basis lists"));
+    c->onehot = true;
+  }
   if (L.compensate) {
     // lambda_0 is computed on the host from the representatives themselves, in fp64
     std::vector<float> hr((size_t)L.ncr * L.d);

@@ -323,7 +323,8 @@ __global__ void k_gather_reps(const ClusterInfo* __restrict__ cl, const float* _
 // plain double-precision loop would: ties and near-ties resolve identically everywhere.
 __global__ __launch_bounds__(256) void k_build_W(const ClusterInfo* __restrict__ cl, const float* __restrict__ X,
                                                  const float* __restrict__ reps, float* __restrict__ Wd,
-                                                 float* __restrict__ Wt, int r, int d, uint32_t ldw) {
+                                                 float* __restrict__ Wt, int32_t* __restrict__ assign, int r, int d,
+                                                 uint32_t ldw) {
 #pragma clang fp contract(off)
   const ClusterInfo c = cl[blockIdx.y];
   const int pl = blockIdx.x * blockDim.x + threadIdx.x;
@@ -341,6 +342,7 @@ __global__ __launch_bounds__(256) void k_build_W(const ClusterInfo* __restrict__
     }
     if (a == 0 || s < bestd) { bestd = s; best = a; }
   }
+  assign[p] = (int32_t)blockIdx.y * r + best;
   for (uint32_t a = 0; a < ldw; ++a) Wd[p * ldw + a] = ((int)a == best) ? 1.f : 0.f;
   for (int a = 0; a < r; ++a) Wt[c.wtoff + (uint64_t)a * c.ld + pl] = (a == best) ? 1.f : 0.f;
 }
@@ -421,7 +423,7 @@ int launch_setup(nugpr_ctx* c, const float* user_reps, const float* user_W, hipS
   if (user_W)
     hipLaunchKernelGGL(k_copy_W, grid, dim3(256), 0, s, c->d_cl, user_W, c->Wd, c->Wt, L.r, (uint32_t)L.ldw);
   else
-    hipLaunchKernelGGL(k_build_W, grid, dim3(256), 0, s, c->d_cl, c->X, c->reps, c->Wd, c->Wt, L.r, L.d,
+    hipLaunchKernelGGL(k_build_W, grid, dim3(256), 0, s, c->d_cl, c->X, c->reps, c->Wd, c->Wt, c->assign, L.r, L.d,
                        (uint32_t)L.ldw);
   NUGPR_HIP(hipGetLastError());
   return NUGPR_OK;

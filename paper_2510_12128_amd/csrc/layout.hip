@@ -108,6 +108,9 @@ int plan_layout(const nugpr_problem* pb, uint32_t flags, Layout& L) {
   // residual matrix of the compensated coupling; reserved whenever the problem is small enough for the
   // compensation, so that the workspace size does not depend on the flags
   if (L.ncr <= 512) L.o_Clo = take(cur, (size_t)L.ldc * L.ldc * sizeof(float));
+  L.o_assign = take(cur, (size_t)L.n * sizeof(int32_t));
+  L.o_rep_ptr = take(cur, ((size_t)L.ncr + 1) * sizeof(int32_t));
+  L.o_rep_pts = take(cur, (size_t)L.n * sizeof(int32_t));
   L.o_B = take(cur, vec);
   L.o_X = take(cur, vec);
   L.o_R = take(cur, vec);

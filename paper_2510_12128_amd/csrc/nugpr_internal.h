@@ -140,6 +140,7 @@ struct Layout {
   size_t o_theta = 0, o_logdet = 0, o_tiles = 0, o_items = 0;
   size_t o_Xs = 0, o_Xn = 0, o_Rs = 0, o_Rn = 0;
   size_t o_x0 = 0, o_Z0 = 0, o_P = 0, o_Clo = 0;
+  size_t o_assign = 0, o_rep_ptr = 0, o_rep_pts = 0;
   size_t items_bytes = 0;
   int n_dot_blocks = 0;
   int max_iter = 0;
@@ -170,6 +171,11 @@ struct nugpr_ctx {
   // sides; it depends on the factor only, so the factorisation computes it once
   void* Z0v = nullptr;
   bool z0_ready = false;
+  // Default (one-hot) basis: W^T D is a sum over each representative's points and W P a gather, so the
+  // dense W is not streamed.  assign[p]: row of C / S / P that point p belongs to; rep_ptr / rep_pts: the
+  // points of every such row in ascending order (CSR).
+  bool onehot = false;
+  int32_t *assign = nullptr, *rep_ptr = nullptr, *rep_pts = nullptr;
   void* Pv = nullptr;                    // [0 | Z]: the probes as a vector block (column 0 empty)
   void* x0 = nullptr;                    // K'^-1 y of a prediction call (one column, internal type)
   bool acc64 = true;                     // arithmetic mode of the operator applications

@@ -305,15 +305,15 @@ int from_internal(nugpr_ctx* c, const void* src, float* dst, int64_t count, hipS
 // ---------------------------------------------------------------------------
 // operator applications on internal vector blocks
 // ---------------------------------------------------------------------------
+static int run_project(nugpr_ctx* c, const void* D, int T, hipStream_t s);
+static int run_expand(nugpr_ctx* c, void* Q, int T, hipStream_t s);
+
 int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s) {
   const Layout& L = c->L;
   int rc;
-  const uint64_t spart = (uint64_t)L.ncr * T, ppart = (uint64_t)L.ncr * T;
-  // S_j = W_j^T D_j, computed in column slabs of W_j^T that are then added up
-  StripPort s0{};
-  s0.A = c->Wt; s0.in = D; s0.out = c->Spart; s0.nin = 1; s0.out_part_stride = spart;
-  if ((rc = launch_strip(c->tab_WtD, s0, s0, T, c->acc64, s))) return rc;
-  if (L.nsS > 1 && (rc = launch_sum_parts(c->Spart, c->Spart, (int64_t)spart, L.nsS, spart, c->acc64, s))) return rc;
+  const uint64_t ppart = (uint64_t)L.ncr * T;
+  // S_j = W_j^T D_j (dense W: in column slabs of W_j^T that are then added up)
+  if ((rc = run_project(c, D, T, s))) return rc;
   // Q_i = K_ii D_i   and   P = C_offdiag S (column slabs), one launch
   StripPort k0{}, k1{};
   k0.A = c->Kd; k0.in = D; k0.out = Q; k0.nin = 1; k0.scale = c->op_scale; k0.diag_add = c->op_shift;
@@ -332,9 +332,7 @@ int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s) {
   }
   if (L.nsP > 1 && (rc = launch_sum_parts(c->Ppart, c->Ppart, (int64_t)ppart, L.nsP, ppart, c->acc64, s))) return rc;
   // Q_i += W_i P_i
-  StripPort w0{};
-  w0.A = c->Wd; w0.in = c->Ppart; w0.nin = 1; w0.out = Q; w0.accumulate = 1;
-  return launch_strip(c->tab_WP, w0, w0, T, c->acc64, s);
+  return run_expand(c, Q, T, s);
 }
 
 // out = a * x  (elementwise over a vector block)
@@ -358,15 +356,90 @@ static int scaled_copy(void* out, const void* x, double a, int64_t count, hipStr
   return NUGPR_OK;
 }
 
-// Q += scale * W (C_offdiag (W^T D)): the low-rank part of the product on its own
-static int run_lowrank_accumulate(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s) {
+// One-hot basis (every point belongs to exactly one representative): S = W^T D is the sum of the rows of
+// D over each representative's points, taken in ascending point order; Q += W P adds row assign[p] of P to
+// row p.  Neither streams the dense W.
+template <typename VT>
+__global__ __launch_bounds__(256) void k_onehot_project(const VT* __restrict__ D, const int32_t* __restrict__ rep_ptr,
+                                                        const int32_t* __restrict__ rep_pts, VT* __restrict__ S,
+                                                        int ncr, int T) {
+  const int rpp = 256 / T;
+  const int tid = threadIdx.x;
+  const int myrow = tid / T, col = tid - myrow * T;
+  if (myrow >= rpp) return;
+  for (int a = blockIdx.x * rpp + myrow; a < ncr; a += gridDim.x * rpp) {
+    double s = 0.0;
+    const int q1 = rep_ptr[a + 1];
+    // eight gathers in flight at a time; the additions stay in ascending point order
+    for (int q = rep_ptr[a]; q < q1; q += 8) {
+      int idx[8];
+      double v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) idx[j] = rep_pts[q + j < q1 ? q + j : q1 - 1];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = (double)D[(int64_t)idx[j] * T + col];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) s += q + j < q1 ? v[j] : 0.0;
+    }
+    S[(int64_t)a * T + col] = (VT)s;
+  }
+}
+
+template <typename VT>
+__global__ __launch_bounds__(256) void k_onehot_expand(VT* __restrict__ Q, const VT* __restrict__ P,
+                                                       const int32_t* __restrict__ assign, int64_t n, int T) {
+  const int rpp = 256 / T;
+  const int tid = threadIdx.x;
+  const int myrow = tid / T, col = tid - myrow * T;
+  if (myrow >= rpp) return;
+  for (int64_t p = (int64_t)blockIdx.x * rpp + myrow; p < n; p += (int64_t)gridDim.x * rpp) {
+    const int64_t idx = p * T + col;
+    Q[idx] = (VT)((double)Q[idx] + (double)P[(int64_t)assign[p] * T + col]);
+  }
+}
+
+static int elementwise_grid(int64_t n, int T);
+
+// S = W^T D into the first slab of Spart (summed over the column slabs when W is dense)
+static int run_project(nugpr_ctx* c, const void* D, int T, hipStream_t s) {
   const Layout& L = c->L;
+  if (c->onehot) {
+    const int grid = elementwise_grid(L.ncr, T);
+    if (c->acc64) hipLaunchKernelGGL((k_onehot_project<double>), dim3(grid), dim3(256), 0, s, (const double*)D, c->rep_ptr, c->rep_pts, (double*)c->Spart, L.ncr, T);
+    else hipLaunchKernelGGL((k_onehot_project<float>), dim3(grid), dim3(256), 0, s, (const float*)D, c->rep_ptr, c->rep_pts, (float*)c->Spart, L.ncr, T);
+    NUGPR_HIP(hipGetLastError());
+    return NUGPR_OK;
+  }
   int rc;
-  const uint64_t spart = (uint64_t)L.ncr * T, ppart = (uint64_t)L.ncr * T;
+  const uint64_t spart = (uint64_t)L.ncr * T;
   StripPort s0{};
   s0.A = c->Wt; s0.in = D; s0.out = c->Spart; s0.nin = 1; s0.out_part_stride = spart;
   if ((rc = launch_strip(c->tab_WtD, s0, s0, T, c->acc64, s))) return rc;
   if (L.nsS > 1 && (rc = launch_sum_parts(c->Spart, c->Spart, (int64_t)spart, L.nsS, spart, c->acc64, s))) return rc;
+  return NUGPR_OK;
+}
+
+// Q += W P with P the first slab of Ppart
+static int run_expand(nugpr_ctx* c, void* Q, int T, hipStream_t s) {
+  const Layout& L = c->L;
+  if (c->onehot) {
+    const int grid = elementwise_grid(L.n, T);
+    if (c->acc64) hipLaunchKernelGGL((k_onehot_expand<double>), dim3(grid), dim3(256), 0, s, (double*)Q, (const double*)c->Ppart, c->assign, (int64_t)L.n, T);
+    else hipLaunchKernelGGL((k_onehot_expand<float>), dim3(grid), dim3(256), 0, s, (float*)Q, (const float*)c->Ppart, c->assign, (int64_t)L.n, T);
+    NUGPR_HIP(hipGetLastError());
+    return NUGPR_OK;
+  }
+  StripPort w0{};
+  w0.A = c->Wd; w0.in = c->Ppart; w0.nin = 1; w0.out = Q; w0.accumulate = 1;
+  return launch_strip(c->tab_WP, w0, w0, T, c->acc64, s);
+}
+
+// Q += scale * W (C_offdiag (W^T D)): the low-rank part of the product on its own
+static int run_lowrank_accumulate(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s) {
+  const Layout& L = c->L;
+  int rc;
+  const uint64_t ppart = (uint64_t)L.ncr * T;
+  if ((rc = run_project(c, D, T, s))) return rc;
   StripPort k1{};
   k1.A = c->C; k1.in = c->Spart; k1.nin = 1; k1.out = c->Ppart; k1.out_part_stride = ppart; k1.scale = c->op_scale;
   if ((rc = launch_strip(c->tab_C, k1, k1, T, c->acc64, s))) return rc;
@@ -376,9 +449,7 @@ static int run_lowrank_accumulate(nugpr_ctx* c, const void* D, void* Q, int T, h
     if ((rc = launch_strip(c->tab_C, k2, k2, T, c->acc64, s))) return rc;
   }
   if (L.nsP > 1 && (rc = launch_sum_parts(c->Ppart, c->Ppart, (int64_t)ppart, L.nsP, ppart, c->acc64, s))) return rc;
-  StripPort w0{};
-  w0.A = c->Wd; w0.in = c->Ppart; w0.nin = 1; w0.out = Q; w0.accumulate = 1;
-  return launch_strip(c->tab_WP, w0, w0, T, c->acc64, s);
+  return run_expand(c, Q, T, s);
 }
 
 // out = A D with A = Y K' Y^T, Y = L^-1 (the paper's R^-T K' R^-1, eq. (RKR)).  Scratch: Vv, Uv.

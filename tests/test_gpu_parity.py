@@ -578,6 +578,58 @@ def test_degenerate_shapes_match_oracle(lib, case):
     ctx.close()
 
 
+def test_user_supplied_representatives_and_dense_basis(lib):
+    # reps and W given by the caller (Section 3.3 leaves their choice open): soft, normalised weights instead of
+    # the default one-hot basis, so the dense W^T D and W P products run instead of their one-hot forms
+    w = small_ragged(seed=3, t=8)
+    rng = np.random.default_rng(71)
+    r = w.rank
+    reps, Ws = [], []
+    for i in range(w.n_clusters):
+        Xi = w.X[w.offsets[i]:w.offsets[i + 1]].astype(np.float64)
+        Ri = Xi[rng.choice(Xi.shape[0], r, replace=False)]
+        d2 = ((Xi[:, None, :] - Ri[None, :, :]) ** 2).sum(-1)
+        Wi = np.exp(-0.5 * d2 / 0.3 ** 2)
+        Wi /= Wi.sum(axis=1, keepdims=True)
+        reps.append(Ri.astype(np.float32))
+        Ws.append(Wi.astype(np.float32))
+    reps = np.concatenate(reps)
+    W = np.concatenate(Ws)
+    prob = O.Problem(w.X, w.y, w.offsets, w.probes, r, reps=reps, Ws=[x.astype(np.float64) for x in Ws])
+    assert np.linalg.eigvalsh(prob.dense(w.theta))[0] > 0.0
+    ctx = make_ctx(lib, w, reps=reps, W=W)
+    assert np.array_equal(ctx.nugpr_export(B.EXPORT_REPS).cpu().numpy(), reps)
+    for i in range(w.n_clusters):
+        assert np.array_equal(ctx.nugpr_export(B.EXPORT_W, i).cpu().numpy(), Ws[i])
+    ctx.nugpr_build_blocks(w.theta)
+    op = prob.operator(w.theta)
+    rng2 = np.random.default_rng(72)
+    for ncols in (1, w.n_probes + 1):
+        D = rng2.standard_normal((w.n, ncols)).astype(np.float32)
+        Q = ctx.nugpr_matvec(D).cpu().numpy().astype(np.float64)
+        assert relmax(Q, op(D.astype(np.float64))) < 1e-5
+    assert ctx.nugpr_precond_factor()[0] == 0
+    fac = O.Factor(prob, w.theta)
+    ref = O.mll(prob, fac, w.theta, w.tol, w.max_iter)
+    out = ctx.nugpr_mll(w.theta)
+    assert out["code"] == 0
+    for key in ("quad", "logdet", "nll"):
+        assert abs(out[key] - ref[key]) <= 1e-4 * abs(ref[key]), (key, out[key], ref[key])
+    A = O.split_operator(op, fac.Ls, prob.offsets)
+    ctx.nugpr_build_blocks(w.theta)
+    assert ctx.nugpr_precond_factor()[0] == 0           # stored blocks = factored blocks: eq. (linear1) route
+    R = rng2.standard_normal((w.n, w.n_probes + 1)).astype(np.float32)
+    S = ctx.nugpr_split_apply(R).cpu().numpy().astype(np.float64)
+    assert relmax(S, A(R.astype(np.float64))) < 1e-4
+    phi = np.log(w.theta)
+    step = ctx.nugpr_train_step(phi, np.zeros(ctx.p), np.zeros(ctx.p), 0)
+    g = O.fd_gradient(prob, fac, phi, w.fd_step, w.tol, w.max_iter)
+    gerr = float(np.linalg.norm(step["grad"] - g) / np.linalg.norm(g))
+    record_metric("user-basis", nll_err=abs(out["nll"] - ref["nll"]) / abs(ref["nll"]), grad_err=gerr)
+    assert gerr < 1e-4, gerr
+    ctx.close()
+
+
 def test_stale_factor_is_reused_across_theta(lib):
     # Section 3.2: the factor of theta_0 preconditions K(theta') too; eq. (logdet) stays exact
     w = small_ragged(seed=11, t=16)
