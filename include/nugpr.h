@@ -20,9 +20,13 @@
  *     nugpr_workspace_bytes() bytes (256-byte aligned).  The library allocates
  *     no device memory.  It never frees caller memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
- *     GPU work is enqueued there.  Calls that return host scalars
- *     (precond_factor, pcg_solve, mll, train_step, export) synchronise that
- *     stream before returning; build_blocks, matvec and precond_apply do not.
+ *     GPU work is enqueued there.  Calls with host outputs return when those
+ *     are complete: precond_factor, pcg_solve, predict, export and profile_read
+ *     synchronise the stream; mll and train_step wait for the device's own
+ *     end-of-solve report in pinned memory (every kernel they enqueued has
+ *     finished its work by then; later work on the same stream is ordered
+ *     behind it as usual).  build_blocks, matvec, precond_apply, split_apply
+ *     and copy_probe only enqueue.
  *   - Return value: 0 = NUGPR_OK; negative = caller / runtime error (nothing
  *     useful was computed); positive = numerical status (outputs are written).
  *     No exception, abort or exit crosses this boundary.
