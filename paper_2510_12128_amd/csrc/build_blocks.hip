@@ -142,18 +142,18 @@ __device__ __forceinline__ void kernel_values(const double (&arg)[W], double alp
 // at the rate of the vector ALU and do not overlap with it, and a wave that alternates arithmetic
 // with bursts of stores stalls on the store path; long-lived workgroups that walk along a tile row
 // measured 30 % slower than the sum of their parts.  Short workgroups leave the overlap to the
-// hardware: while some wait for operands or drain their stores, others compute (three to four fit
-// on a compute unit).  Consecutive workgroups take neighbouring tiles of a row, so the row
+// hardware: while some wait for operands or drain their stores, others compute (seven fit on a
+// compute unit: registers are capped for that, and the staging area holds one 16-row group at a time).  Consecutive workgroups take neighbouring tiles of a row, so the row
 // operands they share stay in L2.  The exponential uses full-rate instructions only, and the masks
 // run on the tiles that need them.
 // NKS = kd / 4 when positive; NKS = 0 handles any kd with a loop over the coordinate groups.
 template <bool COUPLING, int NKS>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(7, 7)))
 void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const double* __restrict__ S,
                   const double* __restrict__ N, float* __restrict__ out_base, int r) {
   extern __shared__ __attribute__((aligned(16))) double sA[];      // 4 * kd * 16 doubles: row operands
   __shared__ double sNr[TILE];
-  __shared__ __attribute__((aligned(16))) float sT[4][TILE * ST_LD];
+  __shared__ __attribute__((aligned(16))) float sT[4][16 * ST_LD];      // per wave: one 16-row group in transit
 
   const BuildItem cur = items[blockIdx.x];
   const int tr = cur.tr, tc = cur.tc0;
@@ -217,19 +217,19 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
   const float dv = a.diag_val;
   const double alpha = a.alpha;
   float* __restrict__ sTw = &sT[wave][0];
-  // staging: this lane writes rows 16 ti + 4 kk + i, column m; it reads rows 16 k + lane / 4, columns
-  // 4 (lane % 4) .. + 3 for the store of the tile's own rows
+  // staging of one 16-row group: this lane writes rows 4 kk + i, column m; it reads row lane / 4,
+  // columns 4 (lane % 4) .. + 3 for the store of the tile's own rows
   float* __restrict__ st_w = sTw + (4 * kk) * ST_LD + m;
   const float4* __restrict__ st_r = reinterpret_cast<const float4*>(sTw + (lane >> 2) * ST_LD + 4 * (lane & 3));
   const uint64_t ld64 = ld;
   const int q = q0 + 16 * wave + m;
-  // the tile itself: rows p0 + 16 k + lane / 4, this wave's 16 columns (64 bytes a row)
+  // the tile itself: rows p0 + 16 ti + lane / 4, this wave's 16 columns (64 bytes a row)
   float* __restrict__ od = out + (uint64_t)(p0 + (lane >> 2)) * ld64 + q0 + 16 * wave + 4 * (lane & 3);
   // its mirror image: row q, columns p0 + 16 ti + 4 kk .. + 3; a tile on the diagonal is its own mirror
   // image, entry for entry, and is simply written twice
   float* __restrict__ om = out + (uint64_t)q * ld64 + p0 + 4 * kk;
 
-  // the sixteen entries of this lane: masked (EDGE) or not
+  // the sixteen entries of this lane, one 16-row group at a time: masked (EDGE) or not
   auto entries = [&](auto edge_c) {
     constexpr bool EDGE = decltype(edge_c)::value;
 #pragma unroll
@@ -256,9 +256,18 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
             if (p == q && p < total) x[i] = dv;
           }
         }
-        st_w[(16 * ti + i) * ST_LD] = x[i];
+        st_w[i * ST_LD] = x[i];
       }
       *reinterpret_cast<float4*>(om + 16 * ti) = make_float4(x[0], x[1], x[2], x[3]);
+      // The staging rows are wave-private and the LDS serves one wave's accesses in order: the read below
+      // sees this group's writes, and the next group's writes come after it.
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      const float4 rowv = *st_r;
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      *reinterpret_cast<float4*>(od + (uint64_t)(16 * ti) * ld64) = rowv;
     }
   };
   // tiles that can hold dropped or replaced entries: on the diagonal, at the ragged end, or (coupling)
@@ -267,11 +276,6 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
                     (COUPLING && (q0 + TILE - 1) / r >= p0 / r);
   if (edge) entries(std::true_type());
   else entries(std::false_type());
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-  for (int k = 0; k < 4; ++k) *reinterpret_cast<float4*>(od + (uint64_t)(16 * k) * ld64) = st_r[k * (16 * ST_LD / 4)];
 }
 
 // What fp32 storage of the compensated coupling matrix drops (eq. (krep)): every entry of
