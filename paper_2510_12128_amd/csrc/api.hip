@@ -98,6 +98,7 @@ void build_tables(const Layout& L, Tables& t) {
       const uint64_t a_off = c.koff + (uint64_t)s * TILE * c.ld;
       const uint32_t row = c.row0 + s * TILE;
       t.KC.push_back(make_item(a_off, c.ld, nrows, 0, c.b, c.row0, row, s * TILE, 0, 0, 0, 1.f));
+      t.KC.back().blocked = 1;
       t.WP.push_back(make_item((uint64_t)row * L.ldw, (uint32_t)L.ldw, nrows, 0, r, (uint32_t)i * r, row, 0, 0, 0, 0, 0.f));
       t.lowG.push_back(make_item(a_off, c.ld, nrows, 0, s * TILE + nrows, c.row0, row, s * TILE, 0, 0, 1, 0.f));
       t.upG.push_back(make_item(a_off, c.ld, nrows, s * TILE, c.b, c.row0, row, s * TILE, 0, 0, 2, 0.f));
@@ -114,6 +115,7 @@ void build_tables(const Layout& L, Tables& t) {
         const uint32_t ce = std::min<uint32_t>(std::min<uint32_t>((k + 1) * cpp, chunks) * TILE, ncr);
         t.KC.push_back(make_item((uint64_t)rs * TILE * L.ldc, (uint32_t)L.ldc, nrows, cb, std::max(cb, ce), 0,
                                  rs * TILE, 0, k, 1, 0, 0.f));
+        t.KC.back().blocked = 1;
       }
     }
   }

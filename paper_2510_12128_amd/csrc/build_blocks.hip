@@ -222,11 +222,14 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
   const float4* __restrict__ st_r = reinterpret_cast<const float4*>(sTw + (lane >> 2) * ST_LD + 4 * (lane & 3));
   const uint64_t ld64 = ld;
   const int q = q0 + 16 * wave + m;
-  // the tile itself: rows p0 + 16 ti + lane / 4, this wave's 16 columns (64 bytes a row)
-  float* __restrict__ od = out + (uint64_t)(p0 + (lane >> 2)) * ld64 + q0 + 16 * wave + 4 * (lane & 3);
-  // its mirror image: row q, columns p0 + 16 ti + 4 kk .. + 3; a tile on the diagonal is its own mirror
-  // image, entry for entry, and is simply written twice
-  float* __restrict__ om = out + (uint64_t)q * ld64 + p0 + 4 * kk;
+  // Blocked storage (blocked_index): strip tr, column blocks 2 tc and 2 tc + 1 hold the tile, 32 floats a row.
+  // The tile itself: rows 16 ti + lane / 4, this wave's 16 columns = half a row of block 2 tc + wave / 2
+  float* __restrict__ od = out + (uint64_t)tr * TILE * ld64 + (uint64_t)(2 * tc + (wave >> 1)) * (TILE * BLK_COLS) +
+                           (lane >> 2) * BLK_COLS + 16 * (wave & 1) + 4 * (lane & 3);
+  // its mirror image (strip tc, column blocks 2 tr, 2 tr + 1): row 16 wave + m, columns 16 ti + 4 kk .. + 3 of
+  // the tile; a tile on the diagonal is its own mirror image, entry for entry, and is simply written twice
+  float* __restrict__ om = out + (uint64_t)tc * TILE * ld64 + (uint64_t)(2 * tr) * (TILE * BLK_COLS) +
+                           (16 * wave + m) * BLK_COLS + 4 * kk;
 
   // the sixteen entries of this lane, one 16-row group at a time: masked (EDGE) or not
   auto entries = [&](auto edge_c) {
@@ -257,7 +260,7 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
         }
         st_w[i * ST_LD] = x[i];
       }
-      *reinterpret_cast<float4*>(om + 16 * ti) = make_float4(x[0], x[1], x[2], x[3]);
+      *reinterpret_cast<float4*>(om + (ti >> 1) * (TILE * BLK_COLS) + 16 * (ti & 1)) = make_float4(x[0], x[1], x[2], x[3]);
       // The staging rows are wave-private and the LDS serves one wave's accesses in order: the read below
       // sees this group's writes, and the next group's writes come after it.
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -266,7 +269,7 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
       const float4 rowv = *st_r;
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
-      *reinterpret_cast<float4*>(od + (uint64_t)(16 * ti) * ld64) = rowv;
+      *reinterpret_cast<float4*>(od + (16 * ti) * BLK_COLS) = rowv;
     }
   };
   // tiles that can hold dropped or replaced entries: on the diagonal, at the ragged end, or (coupling)
@@ -301,9 +304,9 @@ __global__ __launch_bounds__(256) void k_coupling_residual(CouplingArgs a, const
     }
     double v = a.alpha * exp(-0.5 * q);
     if (i == j) v -= a.lambda0;
-    lo = (float)(v - (double)Chi[idx]);
+    lo = (float)(v - (double)Chi[blocked_index(a.ld, i, j)]);
   }
-  Clo[idx] = lo;
+  Clo[blocked_index(a.ld, i, j)] = lo;             // same blocked storage as the matrix it completes
 }
 
 // ---------------------------------------------------------------------------
@@ -369,12 +372,12 @@ __global__ void k_fill(float* __restrict__ p, uint64_t n, float v) {
 // dense export with optional lower-triangle mask
 template <typename ST>
 __global__ void k_export(const ST* __restrict__ src, uint64_t lds, float* __restrict__ dst, int64_t ldd,
-                         int rows, int cols, int lower_only) {
+                         int rows, int cols, int lower_only, int blocked) {
   const int64_t total = (int64_t)rows * cols;
   for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
        idx += (int64_t)gridDim.x * blockDim.x) {
     const int p = (int)(idx / cols), q = (int)(idx - (int64_t)p * cols);
-    float v = (float)src[(uint64_t)p * lds + q];
+    float v = (float)src[blocked ? blocked_index((uint32_t)lds, p, q) : (uint64_t)p * lds + q];
     if (lower_only && q > p) v = 0.f;
     dst[(int64_t)p * ldd + q] = v;
   }
@@ -535,10 +538,10 @@ int launch_export(nugpr_ctx* c, int what, int index, float* dst, int64_t ld, hip
   } else { set_error("unknown export selector"); return NUGPR_ERR_INVALID; }
   if (ld < cols) { set_error("ld smaller than the number of columns"); return NUGPR_ERR_INVALID; }
   if (what == 5 && c->acc64)
-    hipLaunchKernelGGL((k_export<double>), dim3(2048), dim3(256), 0, s, (const double*)c->Bv, lds, dst, ld, rows, cols, lower);
+    hipLaunchKernelGGL((k_export<double>), dim3(2048), dim3(256), 0, s, (const double*)c->Bv, lds, dst, ld, rows, cols, lower, 0);
   else
     hipLaunchKernelGGL((k_export<float>), dim3(2048), dim3(256), 0, s, what == 5 ? (const float*)c->Bv : src, lds, dst, ld,
-                       rows, cols, lower);
+                       rows, cols, lower, (what == 0 || what == 3) ? 1 : 0);     // K_ii and C are stored blocked
   NUGPR_HIP(hipGetLastError());
   NUGPR_HIP(hipStreamSynchronize(s));
   return NUGPR_OK;

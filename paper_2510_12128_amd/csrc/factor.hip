@@ -165,14 +165,14 @@ __global__ __launch_bounds__(256) void k_potrf_update(const ClusterInfo* __restr
   const uint64_t tile_off = (uint64_t)(mt * TILE) * c.ld + (uint64_t)k * TILE;
   if (mt != k) {
     for_each_acc(acc, tid, [&](int r, int q, float v) {
-      L[tile_off + (uint64_t)r * c.ld + q] = A[tile_off + (uint64_t)r * c.ld + q] - v;
+      L[tile_off + (uint64_t)r * c.ld + q] = A[blocked_index(c.ld, mt * TILE + r, k * TILE + q)] - v;
     });
     return;
   }
   // ---- diagonal tile: factor in LDS; rows/cols past the cluster end behave as identity ----
   const int valid = min(TILE, b - k * TILE);
   for_each_acc(acc, tid, [&](int r, int q, float v) {
-    float x = A[tile_off + (uint64_t)r * c.ld + q] - v;
+    float x = A[blocked_index(c.ld, k * TILE + r, k * TILE + q)] - v;
     if (r >= valid || q >= valid) x = (r == q) ? 1.f : 0.f;
     sT[r][q] = x;
   });

@@ -82,7 +82,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   const int nrows = (int)it.nrows;
   const int lr = wave * 16 + m;                               // local row this lane loads
   const int lrc = lr < nrows ? lr : nrows - 1;
+  // this lane's four matrix elements of 16-column step s of the chunk that starts at column cc
+  // (row-major, or 64 x 32 blocks: see blocked_index; cc is a multiple of 64)
   const float* __restrict__ Arow = pt.A + it.a_off + (uint64_t)lrc * (uint64_t)it.lda + 4 * kg;
+  const float* __restrict__ Ablk = pt.A + it.a_off + (uint64_t)lrc * BLK_COLS + 4 * kg;
+  const bool blocked = it.blocked != 0;
+  auto Aaddr = [&](const int cc, const int s) -> const float* {
+    return blocked ? Ablk + (uint64_t)((cc >> 5) + (s >> 1)) * (TILE * BLK_COLS) + 16 * (s & 1) : Arow + cc + 16 * s;
+  };
   const int c_begin = (int)it.c_begin, c_end = (int)it.c_end;
   const int nchunks = c_end > c_begin ? (c_end - c_begin + CHUNK - 1) / CHUNK : 0;
   // columns this lane's row keeps: [q_lo, q_hi)
@@ -207,9 +214,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   if (nchunks > 0) {
 #pragma unroll
     for (int p = 0; p < NPRE; ++p) {
-      const float* __restrict__ Ap = Arow + min(c_begin + p * CHUNK, c_last);
+      const int cp = min(c_begin + p * CHUNK, c_last);
 #pragma unroll
-      for (int s = 0; s < NL; ++s) areg[p][s] = *reinterpret_cast<const float4*>(Ap + 16 * s);
+      for (int s = 0; s < NL; ++s) areg[p][s] = *reinterpret_cast<const float4*>(Aaddr(cp, s));
     }
     load_in(c_begin, inreg);
     store_in(0, inreg);
@@ -221,11 +228,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     const int buf = ch & 1;
     const int c = c_begin + ch * CHUNK;
     load_in(min(c + CHUNK, c_last), inreg);
-    const float* __restrict__ An = Arow + min(c + NPRE * CHUNK, c_last);
+    const int cn = min(c + NPRE * CHUNK, c_last);
     // chunk with elements outside the item's column range or on the wrong side of the diagonal
     const bool masked = (c >= mask_from || c < mask_upto);
 #pragma unroll
-    for (int s = 0; s < NL; ++s) step(areg[SET][s], An + 16 * s, masked, c + 16 * s + 4 * kg, buf, s);
+    for (int s = 0; s < NL; ++s) step(areg[SET][s], Aaddr(cn, s), masked, c + 16 * s + 4 * kg, buf, s);
     if constexpr (!ACC64) {
       // fold this chunk's short chains into the fp64 sums and restart them
       if (NG > 0) {
@@ -345,10 +352,15 @@ __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(2))) void k
     // ---- loader ----
     // matrix: for consumer wave w and step s, lane (m, kg) fetches A[16 w + m][c + 16 s + 4 kg .. + 3]
     // (rows past the strip's last one re-read it; the padded leading dimension keeps the columns in bounds)
+    // (blocked storage: a chunk of RCH = 32 columns is one 64 x 32 block, rows 32 floats apart)
+    static_assert(RCH == BLK_COLS, "the ring kernel reads one storage block per chunk");
+    const bool blocked = it.blocked != 0;
     const float* __restrict__ Ab = pt.A + it.a_off + 4 * kg;
+    const uint64_t rstride = blocked ? (uint64_t)BLK_COLS : (uint64_t)it.lda;
+    const uint64_t cmul = blocked ? (uint64_t)TILE : 1u;        // a block of 32 columns starts 64 * 32 floats after the last
     uint64_t rowoff[4];
 #pragma unroll
-    for (int w = 0; w < 4; ++w) rowoff[w] = (uint64_t)min(16 * w + m, nrows - 1) * (uint64_t)it.lda;
+    for (int w = 0; w < 4; ++w) rowoff[w] = (uint64_t)min(16 * w + m, nrows - 1) * rstride;
     const unsigned char* __restrict__ vbytes = reinterpret_cast<const unsigned char*>(vin);
     auto issue = [&](const int ch) {
       const int c = c_begin + ch * RCH;
@@ -357,7 +369,7 @@ __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(2))) void k
       for (int w = 0; w < 4; ++w)
 #pragma unroll
         for (int s = 0; s < NSTEP; ++s)
-          __builtin_amdgcn_global_load_lds(Ab + rowoff[w] + c + 16 * s, st + (w * NSTEP + s) * 1024, 16, 0, 0);
+          __builtin_amdgcn_global_load_lds(Ab + rowoff[w] + (uint64_t)c * cmul + 16 * s, st + (w * NSTEP + s) * 1024, 16, 0, 0);
       // vector slab: rows in_row0 + c .., T columns, contiguous; 16-byte pieces past its last valid byte
       // re-read the last valid piece (the consumers drop those rows)
       const uint64_t slab0 = (uint64_t)(it.in_row0 + (uint32_t)c) * (uint64_t)T * 8u;
