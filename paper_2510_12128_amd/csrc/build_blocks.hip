@@ -222,14 +222,16 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
   const float4* __restrict__ st_r = reinterpret_cast<const float4*>(sTw + (lane >> 2) * ST_LD + 4 * (lane & 3));
   const uint64_t ld64 = ld;
   const int q = q0 + 16 * wave + m;
-  // Blocked storage (blocked_index): strip tr, column blocks 2 tc and 2 tc + 1 hold the tile, 32 floats a row.
-  // The tile itself: rows 16 ti + lane / 4, this wave's 16 columns = half a row of block 2 tc + wave / 2
+  // Blocked storage (blocked_index): strip tr, column blocks 2 tc and 2 tc + 1 hold the tile, each as eight
+  // 16 x 16 fragments of 1 KiB.  The tile itself: row group ti, this wave's 16 columns = fragment
+  // (ti, wave % 2) of block 2 tc + wave / 2; lane l holds row l / 4, columns 4 (l % 4) .. + 3: float4 number l
   float* __restrict__ od = out + (uint64_t)tr * TILE * ld64 + (uint64_t)(2 * tc + (wave >> 1)) * (TILE * BLK_COLS) +
-                           (lane >> 2) * BLK_COLS + 16 * (wave & 1) + 4 * (lane & 3);
-  // its mirror image (strip tc, column blocks 2 tr, 2 tr + 1): row 16 wave + m, columns 16 ti + 4 kk .. + 3 of
-  // the tile; a tile on the diagonal is its own mirror image, entry for entry, and is simply written twice
+                           (wave & 1) * FRAG + 4 * lane;
+  // its mirror image (strip tc): rows 16 wave + m, columns 16 ti + 4 kk .. + 3 of the tile = fragment
+  // (wave, ti % 2) of block 2 tr + ti / 2, row m, columns 4 kk ..; a tile on the diagonal is its own mirror
+  // image, entry for entry, and is simply written twice
   float* __restrict__ om = out + (uint64_t)tc * TILE * ld64 + (uint64_t)(2 * tr) * (TILE * BLK_COLS) +
-                           (16 * wave + m) * BLK_COLS + 4 * kk;
+                           (2 * wave) * FRAG + m * 16 + 4 * kk;
 
   // the sixteen entries of this lane, one 16-row group at a time: masked (EDGE) or not
   auto entries = [&](auto edge_c) {
@@ -260,7 +262,7 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
         }
         st_w[i * ST_LD] = x[i];
       }
-      *reinterpret_cast<float4*>(om + (ti >> 1) * (TILE * BLK_COLS) + 16 * (ti & 1)) = make_float4(x[0], x[1], x[2], x[3]);
+      *reinterpret_cast<float4*>(om + (ti >> 1) * (TILE * BLK_COLS) + (ti & 1) * FRAG) = make_float4(x[0], x[1], x[2], x[3]);
       // The staging rows are wave-private and the LDS serves one wave's accesses in order: the read below
       // sees this group's writes, and the next group's writes come after it.
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -269,7 +271,7 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
       const float4 rowv = *st_r;
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
-      *reinterpret_cast<float4*>(od + (16 * ti) * BLK_COLS) = rowv;
+      *reinterpret_cast<float4*>(od + (2 * ti) * FRAG) = rowv;
     }
   };
   // tiles that can hold dropped or replaced entries: on the diagonal, at the ragged end, or (coupling)

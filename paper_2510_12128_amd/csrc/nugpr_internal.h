@@ -44,14 +44,19 @@ struct BuildItem {
 static_assert(sizeof(BuildItem) == 32, "BuildItem is read as four 8-byte words");
 
 // Storage of the matrices that only the streaming kernels read in bulk (K_diag and the coupling matrix):
-// 64-row strips, each cut into blocks of 32 columns stored one after the other (64 x 32 fp32 = 8 KiB,
-// row-major inside).  One pipeline stage of a strip is then ONE contiguous 8 KiB run instead of 64 pieces
-// of 128 bytes a leading dimension apart, and a 64 x 64 tile of the assembly is two such runs.
-// ld is a multiple of 64.  Element (row, col) of a matrix with leading dimension ld:
+// 64-row strips, each cut into blocks of 32 columns stored one after the other (64 x 32 fp32 = 8 KiB).
+// Inside a block the order is that of the matrix-core operand fragments: eight fragments of 16 rows x 16
+// columns (fragment (w, s) = rows 16 w .., columns 16 s ..), each 1 KiB, row-major inside.  Every memory
+// instruction of the kernels that touch these matrices (a wave loading the operand of one 16-column step,
+// the assembly storing a 16 x 16 piece of a tile or of its mirror image) then covers ONE contiguous 1 KiB,
+// and one pipeline stage of a strip is one contiguous 8 KiB run.  ld is a multiple of 64.
+// Element (row, col) of a matrix with leading dimension ld:
 constexpr int BLK_COLS = 32;
+constexpr int FRAG = 256;                   // floats in a 16 x 16 fragment
 __host__ __device__ inline uint64_t blocked_index(uint32_t ld, uint32_t row, uint32_t col) {
+  const uint32_t r = row % TILE, c = col % BLK_COLS;
   return (uint64_t)(row / TILE) * TILE * ld + (uint64_t)(col / BLK_COLS) * (TILE * BLK_COLS) +
-         (uint64_t)(row % TILE) * BLK_COLS + (col % BLK_COLS);
+         (uint64_t)(((r / 16) * 2 + c / 16) * FRAG + (r % 16) * 16 + c % 16);
 }
 
 // ---------------------------------------------------------------------------
@@ -70,7 +75,7 @@ struct StripItem {
   uint8_t port;          // 0 / 1: which (matrix, in, out) triple of the launch
   uint8_t mode;          // 0 full, 1 lower triangle (col <= row), 2 upper triangle (col >= row)
   float diag_add;        // 1 for square diagonal blocks: out += port.diag_add * in[row]; else 0
-  uint32_t blocked;      // 1: the matrix is stored in 64-row x 32-column blocks (blocked_index), 0: row-major
+  uint32_t blocked;      // 1: the matrix is stored in blocks of operand fragments (blocked_index), 0: row-major
 };
 static_assert(sizeof(StripItem) == 48, "StripItem layout");
 

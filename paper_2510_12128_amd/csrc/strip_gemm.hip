@@ -85,10 +85,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   // this lane's four matrix elements of 16-column step s of the chunk that starts at column cc
   // (row-major, or 64 x 32 blocks: see blocked_index; cc is a multiple of 64)
   const float* __restrict__ Arow = pt.A + it.a_off + (uint64_t)lrc * (uint64_t)it.lda + 4 * kg;
-  const float* __restrict__ Ablk = pt.A + it.a_off + (uint64_t)lrc * BLK_COLS + 4 * kg;
+  // blocked: fragment (row group, s % 2) of block cc / 32 + s / 2, row lrc % 16, columns 4 kg ..
+  const float* __restrict__ Ablk = pt.A + it.a_off + (uint64_t)((lrc >> 4) * 2) * FRAG + (lrc & 15) * 16 + 4 * kg;
   const bool blocked = it.blocked != 0;
   auto Aaddr = [&](const int cc, const int s) -> const float* {
-    return blocked ? Ablk + (uint64_t)((cc >> 5) + (s >> 1)) * (TILE * BLK_COLS) + 16 * (s & 1) : Arow + cc + 16 * s;
+    return blocked ? Ablk + (uint64_t)((cc >> 5) + (s >> 1)) * (TILE * BLK_COLS) + (s & 1) * FRAG : Arow + cc + 16 * s;
   };
   const int c_begin = (int)it.c_begin, c_end = (int)it.c_end;
   const int nchunks = c_end > c_begin ? (c_end - c_begin + CHUNK - 1) / CHUNK : 0;
@@ -352,15 +353,19 @@ __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(2))) void k
     // ---- loader ----
     // matrix: for consumer wave w and step s, lane (m, kg) fetches A[16 w + m][c + 16 s + 4 kg .. + 3]
     // (rows past the strip's last one re-read it; the padded leading dimension keeps the columns in bounds)
-    // (blocked storage: a chunk of RCH = 32 columns is one 64 x 32 block, rows 32 floats apart)
+    // (blocked storage: a chunk of RCH = 32 columns is one block, and the operand of (w, s) one 1 KiB
+    // fragment of it: float4 number 4 m + kg)
     static_assert(RCH == BLK_COLS, "the ring kernel reads one storage block per chunk");
     const bool blocked = it.blocked != 0;
     const float* __restrict__ Ab = pt.A + it.a_off + 4 * kg;
-    const uint64_t rstride = blocked ? (uint64_t)BLK_COLS : (uint64_t)it.lda;
     const uint64_t cmul = blocked ? (uint64_t)TILE : 1u;        // a block of 32 columns starts 64 * 32 floats after the last
+    const int smul = blocked ? FRAG : 16;                      // step s of a chunk: the next fragment / 16 columns on
     uint64_t rowoff[4];
 #pragma unroll
-    for (int w = 0; w < 4; ++w) rowoff[w] = (uint64_t)min(16 * w + m, nrows - 1) * rstride;
+    for (int w = 0; w < 4; ++w) {
+      const int rw = min(16 * w + m, nrows - 1);
+      rowoff[w] = blocked ? (uint64_t)((rw >> 4) * 2) * FRAG + (uint64_t)(rw & 15) * 16 : (uint64_t)rw * (uint64_t)it.lda;
+    }
     const unsigned char* __restrict__ vbytes = reinterpret_cast<const unsigned char*>(vin);
     auto issue = [&](const int ch) {
       const int c = c_begin + ch * RCH;
@@ -369,7 +374,7 @@ __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(2))) void k
       for (int w = 0; w < 4; ++w)
 #pragma unroll
         for (int s = 0; s < NSTEP; ++s)
-          __builtin_amdgcn_global_load_lds(Ab + rowoff[w] + (uint64_t)c * cmul + 16 * s, st + (w * NSTEP + s) * 1024, 16, 0, 0);
+          __builtin_amdgcn_global_load_lds(Ab + rowoff[w] + (uint64_t)c * cmul + s * smul, st + (w * NSTEP + s) * 1024, 16, 0, 0);
       // vector slab: rows in_row0 + c .., T columns, contiguous; 16-byte pieces past its last valid byte
       // re-read the last valid piece (the consumers drop those rows)
       const uint64_t slab0 = (uint64_t)(it.in_row0 + (uint32_t)c) * (uint64_t)T * 8u;
