@@ -25,11 +25,11 @@
 namespace nugpr {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
-constexpr int KS = 16;          // contraction depth per LDS stage
+constexpr int KS = 32;          // contraction depth per LDS stage (two 16-deep halves per thread)
 constexpr int SP = KS + 1;      // padded LDS row
 
-struct Frag {          // one thread's share of a 64 x 16 operand stage
-  float v[4];
+struct Frag {          // one thread's share of a 64 x 32 operand stage: four elements of each 16-deep half
+  float v[8];
 };
 
 // Logical operand Op[r][k]; memory is base[r*ld + k] (TRANS = false) or base[k*ld + r].
@@ -38,28 +38,32 @@ template <bool TRANS>
 __device__ __forceinline__ Frag fetch(const float* __restrict__ base, uint32_t ld, int r0, int k0, int rmax,
                                       int tri, int tid) {
   Frag f;
-  if (!TRANS) {
-    const int r = r0 + (tid >> 2), k = k0 + (tid & 3) * 4;
-    if (r < rmax) {
-      const float4 x = *reinterpret_cast<const float4*>(base + (uint64_t)r * ld + k);
-      f.v[0] = x.x; f.v[1] = x.y; f.v[2] = x.z; f.v[3] = x.w;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    float* v = f.v + 4 * h;
+    if (!TRANS) {
+      const int r = r0 + (tid >> 2), k = k0 + 16 * h + (tid & 3) * 4;
+      if (r < rmax) {
+        const float4 x = *reinterpret_cast<const float4*>(base + (uint64_t)r * ld + k);
+        v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+      } else {
+        v[0] = v[1] = v[2] = v[3] = 0.f;
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (tri == 1 && k + j > r) v[j] = 0.f;
+        if (tri == 2 && k + j < r) v[j] = 0.f;
+      }
     } else {
-      f.v[0] = f.v[1] = f.v[2] = f.v[3] = 0.f;
-    }
+      const int k = k0 + 16 * h + (tid >> 4), r = r0 + (tid & 15) * 4;
+      const float4 x = *reinterpret_cast<const float4*>(base + (uint64_t)k * ld + r);
+      v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if (tri == 1 && k + j > r) f.v[j] = 0.f;
-      if (tri == 2 && k + j < r) f.v[j] = 0.f;
-    }
-  } else {
-    const int k = k0 + (tid >> 4), r = r0 + (tid & 15) * 4;
-    const float4 x = *reinterpret_cast<const float4*>(base + (uint64_t)k * ld + r);
-    f.v[0] = x.x; f.v[1] = x.y; f.v[2] = x.z; f.v[3] = x.w;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if (r + j >= rmax) f.v[j] = 0.f;
-      if (tri == 1 && k > r + j) f.v[j] = 0.f;
-      if (tri == 2 && k < r + j) f.v[j] = 0.f;
+      for (int j = 0; j < 4; ++j) {
+        if (r + j >= rmax) v[j] = 0.f;
+        if (tri == 1 && k > r + j) v[j] = 0.f;
+        if (tri == 2 && k < r + j) v[j] = 0.f;
+      }
     }
   }
   return f;
@@ -67,14 +71,17 @@ __device__ __forceinline__ Frag fetch(const float* __restrict__ base, uint32_t l
 
 template <bool TRANS>
 __device__ __forceinline__ void commit(float (*s)[SP], const Frag& f, int tid) {
-  if (!TRANS) {
-    const int r = tid >> 2, k = (tid & 3) * 4;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) s[r][k + j] = f.v[j];
-  } else {
-    const int k = tid >> 4, r = (tid & 15) * 4;
+  for (int h = 0; h < 2; ++h) {
+    if (!TRANS) {
+      const int r = tid >> 2, k = 16 * h + (tid & 3) * 4;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) s[r + j][k] = f.v[j];
+      for (int j = 0; j < 4; ++j) s[r][k + j] = f.v[4 * h + j];
+    } else {
+      const int k = 16 * h + (tid >> 4), r = (tid & 15) * 4;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) s[r + j][k] = f.v[4 * h + j];
+    }
   }
 }
 
@@ -86,7 +93,7 @@ struct Operand {
   int tri;
 };
 
-// acc[i][j] += OpA[64 x K] * OpB[64 x K]^T over k in [k0, k1), k0/k1 multiples of 16.
+// acc[i][j] += OpA[64 x K] * OpB[64 x K]^T over k in [k0, k1), k0/k1 multiples of 32 (all callers pass tile boundaries).
 template <bool TA, bool TB>
 __device__ __forceinline__ void tile_gemm(v4f (&acc)[2][2], const Operand& A, const Operand& B, int k0, int k1,
                                           float (*sA)[SP], float (*sB)[SP], int tid) {
@@ -177,33 +184,67 @@ __global__ __launch_bounds__(256) void k_potrf_update(const ClusterInfo* __restr
     sT[r][q] = x;
   });
   __syncthreads();
+  // Right-looking elimination with ONE barrier per pivot: column j is left unscaled (its entries are read as
+  // a_ij a_cj / d_j by the update) and the division by sqrt(d_j) is applied to all columns in a pass at the
+  // end; d_j = sT[j][j] is final once pivot j - 1 has been processed and is not touched afterwards.
   bool bad = false;
-  for (int j = 0; j < TILE; ++j) {
+  for (int j = 0; j < TILE - 1; ++j) {
     float dj = sT[j][j];
     if (!(dj > 0.f) || !(dj < INFINITY)) { bad = true; dj = 1.f; }
-    const float sj = sqrtf(dj);
-    const float inv = 1.f / sj;
-    __syncthreads();                       // everyone has read the pivot
-    if (tid > j && tid < TILE) sT[tid][j] *= inv;
-    if (tid == j) sT[j][j] = sj;
-    __syncthreads();
+    const float rd = 1.f / dj;
     const int i = tid >> 2;                // trailing update, row i, columns j < cc <= i
     if (i > j) {
-      const float lij = sT[i][j];
+      const float lij = sT[i][j] * rd;
       for (int cc = j + 1 + (tid & 3); cc <= i; cc += 4) sT[i][cc] = fmaf(-lij, sT[cc][j], sT[i][cc]);
     }
     __syncthreads();
   }
+  {
+    const float dl = sT[TILE - 1][TILE - 1];
+    if (!(dl > 0.f) || !(dl < INFINITY)) bad = true;
+  }
+  __syncthreads();
+  // scaling pass: L_ij = a_ij / sqrt(d_j), L_jj = sqrt(d_j) (non-positive pivots behave as 1, as above);
+  // the diagonal is read before anything is written
+  {
+    const int i = tid >> 2;
+    float col[TILE / 4];
+#pragma unroll
+    for (int u = 0; u < TILE / 4; ++u) {
+      const int j = 4 * u + (tid & 3);
+      float dj = sT[j][j];
+      if (!(dj > 0.f) || !(dj < INFINITY)) dj = 1.f;
+      const float sj = sqrtf(dj);
+      col[u] = j < i ? sT[i][j] / sj : (j == i ? sj : 0.f);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < TILE / 4; ++u) {
+      const int j = 4 * u + (tid & 3);
+      if (j <= i) sT[i][j] = col[u];
+    }
+  }
+  __syncthreads();
   if (bad && tid == 0) atomicMin(&st->bad_cluster, (int)blockIdx.y);
-  // ---- inverse of the lower-triangular tile, one column per thread ----
-  if (tid < TILE) {
-    const int cc = tid;
-    for (int i = 0; i < cc; ++i) sI[i][cc] = 0.f;
-    sI[cc][cc] = 1.f / sT[cc][cc];
+  // ---- inverse of the lower-triangular tile: column cc by forward substitution, four lanes per column
+  // sharing each row's sum (lanes 4 cc .. 4 cc + 3 sit in one wave) ----
+  {
+    const int cc = tid >> 2, part = tid & 3;
+    if (part == 0) {
+      for (int i = 0; i < cc; ++i) sI[i][cc] = 0.f;
+      sI[cc][cc] = 1.f / sT[cc][cc];
+    }
     for (int i = cc + 1; i < TILE; ++i) {
-      float s = 0.f;
-      for (int j = cc; j < i; ++j) s = fmaf(sT[i][j], sI[j][cc], s);
-      sI[i][cc] = -s / sT[i][i];
+      // the four lanes of a column run the same iterations, so the shuffles stay inside active lanes; the
+      // column's earlier entries were written by this wave, whose LDS accesses are served in order
+      float sacc = 0.f;
+      for (int j = cc + part; j < i; j += 4) sacc = fmaf(sT[i][j], sI[j][cc], sacc);
+      sacc += __shfl_xor(sacc, 1);
+      sacc += __shfl_xor(sacc, 2);
+      if (part == 0) sI[i][cc] = -sacc / sT[i][i];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
   }
   __syncthreads();
