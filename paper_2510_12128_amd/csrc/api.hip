@@ -103,6 +103,7 @@ void build_tables(const Layout& L, Tables& t) {
       t.lowG.push_back(make_item(a_off, c.ld, nrows, 0, s * TILE + nrows, c.row0, row, s * TILE, 0, 0, 1, 0.f));
       t.upG.push_back(make_item(a_off, c.ld, nrows, s * TILE, c.b, c.row0, row, s * TILE, 0, 0, 2, 0.f));
       t.lowL.push_back(make_item(a_off, c.ld, nrows, 0, s * TILE + nrows, c.row0, row, s * TILE, 0, 0, 1, 0.f));
+      t.lowG.back().blocked = t.upG.back().blocked = t.lowL.back().blocked = 1;     // L and L^-1 are stored blocked too
     }
   }
   // P = C S: strips over the n_c r rows of C, columns split into nsP slabs

@@ -543,7 +543,7 @@ int launch_export(nugpr_ctx* c, int what, int index, float* dst, int64_t ld, hip
     hipLaunchKernelGGL((k_export<double>), dim3(2048), dim3(256), 0, s, (const double*)c->Bv, lds, dst, ld, rows, cols, lower, 0);
   else
     hipLaunchKernelGGL((k_export<float>), dim3(2048), dim3(256), 0, s, what == 5 ? (const float*)c->Bv : src, lds, dst, ld,
-                       rows, cols, lower, (what == 0 || what == 3) ? 1 : 0);     // K_ii and C are stored blocked
+                       rows, cols, lower, what <= 3 ? 1 : 0);     // K_ii, L_i, L_i^-1 and C are stored blocked
   NUGPR_HIP(hipGetLastError());
   NUGPR_HIP(hipStreamSynchronize(s));
   return NUGPR_OK;

@@ -32,7 +32,9 @@ struct Frag {          // one thread's share of a 64 x 32 operand stage: four el
   float v[8];
 };
 
-// Logical operand Op[r][k]; memory is base[r*ld + k] (TRANS = false) or base[k*ld + r].
+// Logical operand Op[r][k]; memory is element (r, k) (TRANS = false) or (k, r) of a matrix stored in blocks of
+// 16 x 16 fragments (blocked_index): the four elements a thread loads are consecutive in a fragment row, and the
+// 64 threads of a wave load one whole fragment, 1 KiB in one piece.
 // tri: 0 none, 1 keep k <= r, 2 keep k >= r (r, k are coordinates inside the same square block).
 template <bool TRANS>
 __device__ __forceinline__ Frag fetch(const float* __restrict__ base, uint32_t ld, int r0, int k0, int rmax,
@@ -44,7 +46,7 @@ __device__ __forceinline__ Frag fetch(const float* __restrict__ base, uint32_t l
     if (!TRANS) {
       const int r = r0 + (tid >> 2), k = k0 + 16 * h + (tid & 3) * 4;
       if (r < rmax) {
-        const float4 x = *reinterpret_cast<const float4*>(base + (uint64_t)r * ld + k);
+        const float4 x = *reinterpret_cast<const float4*>(base + blocked_index(ld, r, k));
         v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
       } else {
         v[0] = v[1] = v[2] = v[3] = 0.f;
@@ -56,7 +58,7 @@ __device__ __forceinline__ Frag fetch(const float* __restrict__ base, uint32_t l
       }
     } else {
       const int k = k0 + 16 * h + (tid >> 4), r = r0 + (tid & 15) * 4;
-      const float4 x = *reinterpret_cast<const float4*>(base + (uint64_t)k * ld + r);
+      const float4 x = *reinterpret_cast<const float4*>(base + blocked_index(ld, k, r));
       v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -169,10 +171,10 @@ __global__ __launch_bounds__(256) void k_potrf_update(const ClusterInfo* __restr
   Operand oa{L, c.ld, mt * TILE, b, 0};
   Operand ob{L, c.ld, k * TILE, b, 0};
   tile_gemm<false, false>(acc, oa, ob, 0, k * TILE, sA, sB, tid);
-  const uint64_t tile_off = (uint64_t)(mt * TILE) * c.ld + (uint64_t)k * TILE;
   if (mt != k) {
     for_each_acc(acc, tid, [&](int r, int q, float v) {
-      L[tile_off + (uint64_t)r * c.ld + q] = A[blocked_index(c.ld, mt * TILE + r, k * TILE + q)] - v;
+      const uint64_t at = blocked_index(c.ld, mt * TILE + r, k * TILE + q);
+      L[at] = A[at] - v;
     });
     return;
   }
@@ -251,8 +253,9 @@ __global__ __launch_bounds__(256) void k_potrf_update(const ClusterInfo* __restr
   float* Y = G + c.koff;
   for (int idx = tid; idx < TILE * TILE; idx += 256) {
     const int r = idx >> 6, q = idx & 63;
-    L[tile_off + (uint64_t)r * c.ld + q] = (q <= r) ? sT[r][q] : 0.f;
-    Y[tile_off + (uint64_t)r * c.ld + q] = (q <= r) ? sI[r][q] : 0.f;
+    const uint64_t at = blocked_index(c.ld, k * TILE + r, k * TILE + q);
+    L[at] = (q <= r) ? sT[r][q] : 0.f;
+    Y[at] = (q <= r) ? sI[r][q] : 0.f;
   }
 }
 
@@ -273,8 +276,7 @@ __global__ __launch_bounds__(256) void k_potrf_trsm(const ClusterInfo* __restric
   Operand ob{Y, c.ld, k * TILE, (int)c.ld, 1};          // Y_kk[c][j], lower triangular
   tile_gemm<false, false>(acc, oa, ob, k * TILE, (k + 1) * TILE, sA, sB, tid);
   __syncthreads();
-  const uint64_t tile_off = (uint64_t)(mt * TILE) * c.ld + (uint64_t)k * TILE;
-  for_each_acc(acc, tid, [&](int r, int q, float v) { L[tile_off + (uint64_t)r * c.ld + q] = v; });
+  for_each_acc(acc, tid, [&](int r, int q, float v) { L[blocked_index(c.ld, mt * TILE + r, k * TILE + q)] = v; });
 }
 
 // ---------------------------------------------------------------------------
@@ -301,10 +303,10 @@ __global__ __launch_bounds__(256) void k_trtri_stage1(const ClusterInfo* __restr
   for_each_acc(acc, tid, [&](int r, int q, float v) { sT[r][q] = v; });
   __syncthreads();
   // mirror block: rows = columns of T (tile tn), columns = rows of T (tile tm)
-  const uint64_t off = (uint64_t)(tn * TILE) * c.ld + (uint64_t)tm * TILE;
+
   for (int idx = tid; idx < TILE * TILE; idx += 256) {
     const int q = idx >> 6, r = idx & 63;
-    Y[off + (uint64_t)q * c.ld + r] = sT[r][q];
+    Y[blocked_index(c.ld, tn * TILE + q, tm * TILE + r)] = sT[r][q];
   }
 }
 
@@ -324,8 +326,7 @@ __global__ __launch_bounds__(256) void k_trtri_stage2(const ClusterInfo* __restr
   Operand oa{Y, c.ld, tm * TILE, (int)c.b, 1};          // Y22[m][k], nonzero for k <= m
   Operand ob{Y, c.ld, tn * TILE, (int)c.ld, 0};         // OpB[n][k] = T[k][n], read from the mirror block
   tile_gemm<false, false>(acc, oa, ob, mid * TILE, (tm + 1) * TILE, sA, sB, tid);
-  const uint64_t off = (uint64_t)(tm * TILE) * c.ld + (uint64_t)tn * TILE;
-  for_each_acc(acc, tid, [&](int r, int q, float v) { Y[off + (uint64_t)r * c.ld + q] = -v; });
+  for_each_acc(acc, tid, [&](int r, int q, float v) { Y[blocked_index(c.ld, tm * TILE + r, tn * TILE + q)] = -v; });
 }
 
 // upper triangle <- transpose of the lower triangle (tile list of the assembly kernels)
@@ -337,16 +338,15 @@ __global__ __launch_bounds__(256) void k_mirror(const ClusterInfo* __restrict__ 
   const ClusterInfo c = cl[ci];
   float* Y = G + c.koff;
   const int tid = threadIdx.x;
-  const uint64_t src = (uint64_t)(tr * TILE) * c.ld + (uint64_t)tc * TILE;
-  const uint64_t dst = (uint64_t)(tc * TILE) * c.ld + (uint64_t)tr * TILE;
+
   for (int idx = tid; idx < TILE * TILE; idx += 256) {
     const int r = idx >> 6, q = idx & 63;
-    sT[r][q] = Y[src + (uint64_t)r * c.ld + q];
+    sT[r][q] = Y[blocked_index(c.ld, tr * TILE + r, tc * TILE + q)];
   }
   __syncthreads();
   for (int idx = tid; idx < TILE * TILE; idx += 256) {
     const int r = idx >> 6, q = idx & 63;      // element (r, q) of the destination tile
-    if (tr != tc || q > r) Y[dst + (uint64_t)r * c.ld + q] = sT[q][r];
+    if (tr != tc || q > r) Y[blocked_index(c.ld, tc * TILE + r, tr * TILE + q)] = sT[q][r];
   }
 }
 
@@ -357,7 +357,7 @@ __global__ __launch_bounds__(256) void k_logdet(const ClusterInfo* __restrict__ 
   const ClusterInfo c = cl[blockIdx.x];
   const float* Y = G + c.koff;
   double s = 0.0;
-  for (uint32_t p = threadIdx.x; p < c.b; p += 256) s += log((double)Y[(uint64_t)p * c.ld + p]);
+  for (uint32_t p = threadIdx.x; p < c.b; p += 256) s += log((double)Y[blocked_index(c.ld, p, p)]);
   red[threadIdx.x] = s;
   __syncthreads();
   for (int w = 128; w > 0; w >>= 1) {
