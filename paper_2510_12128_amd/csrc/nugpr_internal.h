@@ -283,7 +283,6 @@ int run_split_op(nugpr_ctx* c, const void* D, void* out, int T, hipStream_t s);
 int run_dot2(nugpr_ctx* c, const void* A0, const void* B0, const void* A1, const void* B1, int T, double* out0,
              double* out1, hipStream_t s);
 int store_known_starts(nugpr_ctx* c, hipStream_t s);
-int run_dot_col(nugpr_ctx* c, const void* A, const void* B, int T, double* out_host, hipStream_t s);
 int to_internal(nugpr_ctx* c, const float* src, void* dst, int64_t count, hipStream_t s);
 int from_internal(nugpr_ctx* c, const void* src, float* dst, int64_t count, hipStream_t s);
 

@@ -509,28 +509,6 @@ static int elementwise_grid(int64_t n, int T) {
 }
 
 template <typename VT>
-static int dot_col_t(nugpr_ctx* c, const VT* A, const VT* B, int T, double* out_host, hipStream_t s) {
-  const Layout& L = c->L;
-  const int nb = L.n_dot_blocks;
-  hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, A, B, A, B, (int64_t)L.n, T, c->dotpart);
-  NUGPR_HIP(hipGetLastError());
-  // small: add the partials on the host in block order
-  NUGPR_HIP(hipMemcpyAsync(c->h_buf, c->dotpart, (size_t)nb * MAX_COLS * sizeof(double), hipMemcpyDeviceToHost, s));
-  NUGPR_HIP(hipStreamSynchronize(s));
-  for (int col = 0; col < T; ++col) {
-    double acc = 0.0;
-    for (int b = 0; b < nb; ++b) acc += c->h_buf[(size_t)b * MAX_COLS + col];
-    out_host[col] = acc;
-  }
-  return NUGPR_OK;
-}
-
-int run_dot_col(nugpr_ctx* c, const void* A, const void* B, int T, double* out_host, hipStream_t s) {
-  if (c->acc64) return dot_col_t<double>(c, (const double*)A, (const double*)B, T, out_host, s);
-  return dot_col_t<float>(c, (const float*)A, (const float*)B, T, out_host, s);
-}
-
-template <typename VT>
 static int dot2_t(nugpr_ctx* c, const VT* A0, const VT* B0, const VT* A1, const VT* B1, int T, double* out0,
                   double* out1, hipStream_t s) {
   const Layout& L = c->L;
@@ -563,17 +541,12 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
                  int* max_it_used, hipStream_t s, PcgExtras* extras, int system) {
   const Layout& L = c->L;
   const int64_t n = L.n;
-  const size_t bytes = (size_t)n * T * sizeof(VT);
   const int nb = L.n_dot_blocks;
   const int eg = elementwise_grid(n, T);
   const double tol2 = c->params.tol * c->params.tol;
   const int max_iter = c->params.max_iter;
   int rc;
   VT *R = (VT*)c->Rv, *Z = (VT*)c->Zv, *D = (VT*)c->Dv, *Q = (VT*)c->Qv;
-  (void)bytes;
-  // x_0 = 0, r_0 = B, cleared coefficient logs: one launch
-  // d_0 = z_0 = M^-1 r_0, written straight into D; for the context's own right-hand sides it was
-  // computed with the factor
   // Without a preconditioner (the Pade system, already preconditioned) z = r throughout.
   const bool plain = system == PCG_PADE_Q;
   const VT* Zr = plain ? R : Z;

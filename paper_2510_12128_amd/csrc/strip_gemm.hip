@@ -335,7 +335,7 @@ __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(2))) void k
 #if __HIP_DEVICE_COMPILE__
   typedef RingCfg<NG, RCH, STAGES_> Cfg;
   constexpr int NSTEP = Cfg::NSTEP;
-  constexpr int NCOLM = Cfg::NCOLM, STAGES = Cfg::STAGES;
+  constexpr int STAGES = Cfg::STAGES;
   extern __shared__ __attribute__((aligned(16))) unsigned char ring[];
 
   const StripItem it = a.items[blockIdx.x];
