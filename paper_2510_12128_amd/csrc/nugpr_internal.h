@@ -120,6 +120,8 @@ struct PcgState {
   int32_t indefinite;
   int32_t bad_cluster;    // Cholesky: lowest failing cluster index, or INT_MAX
   int32_t tail_count;     // workgroups of the end-of-solve report that are done (returns to 0)
+  int32_t check_count;    // workgroups of the stop test that are done (returns to 0)
+  int32_t pad_;
   // <b, b> and <b, z_0> of the two right-hand-side blocks the context owns ([y | L Z] with z_0 = M^-1 b,
   // and the probe block [0 | Z] with z_0 = b): they depend on the factor only and are taken with it
   double known_bb[2][MAX_COLS];

@@ -69,7 +69,7 @@ __device__ __forceinline__ double sum_partials(const double* __restrict__ partia
 
 // The three scalar kernels run one workgroup per column (grid = T); the cross-column
 // bookkeeping (how many columns are still active, did any meet negative curvature) is
-// gathered by k_copy_flags, which runs after them on the same stream.
+// gathered by the last workgroup of the stop test (k_pcg_check).
 
 // start of a solve: ||b||^2 and rho_0 = <r_0, z_0>
 __global__ __launch_bounds__(256) void k_pcg_begin(PcgState* __restrict__ st, const double* __restrict__ partial,
@@ -135,21 +135,46 @@ __global__ __launch_bounds__(256) void k_pcg_alpha(PcgState* __restrict__ st, co
   }
 }
 
-// after the update: stop test on ||r_c|| (columns that meet it are frozen)
+// after the update: stop test on ||r_c|| (columns that meet it are frozen).  The workgroup that finishes
+// last gathers the cross-column bookkeeping (how many columns are still active, did any meet negative
+// curvature) and publishes it to the host: the flags, a system-scope fence, then the sequence number.
 __global__ __launch_bounds__(256) void k_pcg_check(PcgState* __restrict__ st, const double* __restrict__ partial,
-                                                   int nblocks, int iter, double tol2) {
+                                                   int nblocks, int iter, double tol2, int T,
+                                                   HostFlags* __restrict__ out, uint64_t seq) {
   __shared__ double red[256];
+  __shared__ int last;
   const int tid = threadIdx.x, c = blockIdx.x;
   const double rr = sum_partials(partial, nblocks, c, red, tid);
-  if (tid == 0 && st->active[c]) {
-    st->iters[c] = iter + 1;
-    if (rr <= tol2 * st->bnorm2[c]) {
-      st->active[c] = 0;
-      st->converged[c] = 1;
-    } else if (!(rr == rr)) {                // NaN residual: stop this column
-      st->active[c] = 0;
-      st->indef[c] = 1;
+  if (tid == 0) {
+    if (st->active[c]) {
+      st->iters[c] = iter + 1;
+      if (rr <= tol2 * st->bnorm2[c]) {
+        st->active[c] = 0;
+        st->converged[c] = 1;
+      } else if (!(rr == rr)) {                // NaN residual: stop this column
+        st->active[c] = 0;
+        st->indef[c] = 1;
+      }
     }
+    __threadfence();
+    last = (atomicAdd(&st->check_count, 1) == T - 1);
+  }
+  __syncthreads();
+  if (last && tid == 0) {
+    __threadfence();
+    int n_active = 0, indef = 0;
+    for (int k = 0; k < T; ++k) {
+      n_active += *reinterpret_cast<volatile int32_t*>(&st->active[k]);
+      indef |= *reinterpret_cast<volatile int32_t*>(&st->indef[k]);
+    }
+    st->check_count = 0;
+    st->n_active = n_active;
+    st->indefinite = indef;
+    out->n_active = n_active;
+    out->indefinite = indef;
+    out->bad_cluster = st->bad_cluster;
+    __threadfence_system();
+    *reinterpret_cast<volatile uint64_t*>(&out->seq) = seq;
   }
 }
 
@@ -175,22 +200,46 @@ __global__ __launch_bounds__(256) void k_pcg_beta(PcgState* __restrict__ st, con
   }
 }
 
-// X += D diag(alpha); R -= Q diag(alpha)   (alpha stays in fp64: rounding it to fp32 would
-// scale the whole step coherently)
-// (first step of a solve: X starts from zero and R from Rin = b, neither of which is read or written before)
+// X += D diag(alpha); R -= Q diag(alpha)   (alpha stays in fp64: rounding it to fp32 would scale the whole
+// step coherently).  In the first step of a solve X starts from zero and R from Rin = b, neither of which is
+// read or written before.  The update is fused with the two reductions that follow it: partial[0] = per-workgroup sums of r_new^2
+// (the stop test) and, when B is given, partial[1] = sums of b x_new (the quadratic form of the end-of-solve
+// report).  Rows are split among the workgroups as in k_dot, so the sums are those k_dot would produce.
 template <typename VT>
-__global__ __launch_bounds__(256) void k_update_xr(VT* __restrict__ X, VT* R, const VT* Rin,
-                                                   const VT* __restrict__ D, const VT* __restrict__ Q,
-                                                   const PcgState* __restrict__ st, int64_t n, int T, int first) {
+__global__ __launch_bounds__(256) void k_update_xr_dots(VT* __restrict__ X, VT* R, const VT* Rin,
+                                                        const VT* __restrict__ D, const VT* __restrict__ Q,
+                                                        const VT* __restrict__ B, const PcgState* __restrict__ st,
+                                                        int64_t n, int T, int first, double* __restrict__ partial) {
+  __shared__ double red[2][256];
   const int rpp = 256 / T;
   const int tid = threadIdx.x;
   const int myrow = tid / T, col = tid - myrow * T;
-  if (myrow >= rpp) return;
-  const double a = st->alpha[col];
-  for (int64_t r = (int64_t)blockIdx.x * rpp + myrow; r < n; r += (int64_t)gridDim.x * rpp) {
-    const int64_t idx = r * T + col;
-    X[idx] = first ? (VT)(a * (double)D[idx]) : (VT)fma(a, (double)D[idx], (double)X[idx]);
-    R[idx] = (VT)fma(-a, (double)Q[idx], (double)Rin[idx]);
+  const bool live = myrow < rpp;
+  const int64_t rows_per_block = (n + gridDim.x - 1) / gridDim.x;
+  const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
+  const int64_t r1 = r0 + rows_per_block < n ? r0 + rows_per_block : n;
+  double s0 = 0.0, s1 = 0.0;
+  if (live) {
+    const double a = st->alpha[col];
+    for (int64_t r = r0 + myrow; r < r1; r += rpp) {
+      const int64_t idx = r * T + col;
+      const VT xn = first ? (VT)(a * (double)D[idx]) : (VT)fma(a, (double)D[idx], (double)X[idx]);
+      const VT rn = (VT)fma(-a, (double)Q[idx], (double)Rin[idx]);
+      X[idx] = xn;
+      R[idx] = rn;
+      s0 = fma((double)rn, (double)rn, s0);
+      if (B) s1 = fma((double)B[idx], (double)xn, s1);
+    }
+  }
+  red[0][tid] = s0;
+  red[1][tid] = s1;
+  __syncthreads();
+  if (tid < T) {
+    for (int w = 0; w < 2; ++w) {
+      double sacc = 0.0;
+      for (int k = 0; k < rpp; ++k) sacc += red[w][k * T + tid];
+      partial[((int64_t)w * gridDim.x + blockIdx.x) * MAX_COLS + tid] = sacc;
+    }
   }
 }
 
@@ -208,18 +257,6 @@ __global__ __launch_bounds__(256) void k_update_d(VT* D, const VT* Din, const VT
     const int64_t idx = r * T + col;
     D[idx] = act ? (VT)fma(bta, (double)Din[idx], (double)Z[idx]) : (VT)0;
   }
-}
-
-__global__ void k_copy_flags(PcgState* __restrict__ st, HostFlags* __restrict__ out, int T, uint64_t seq) {
-  int n_active = 0, indef = 0;
-  for (int c = 0; c < T; ++c) { n_active += st->active[c]; indef |= st->indef[c]; }
-  st->n_active = n_active;
-  st->indefinite = indef;
-  out->n_active = n_active;
-  out->indefinite = indef;
-  out->bad_cluster = st->bad_cluster;
-  __threadfence_system();
-  *reinterpret_cast<volatile uint64_t*>(&out->seq) = seq;
 }
 
 // End-of-solve report, written by the device straight into pinned host memory: the per-column state,
@@ -582,10 +619,12 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
   // one, right behind its stop test, so that it is already on the host when the stop test says "done";
   // a solve that ends earlier or later than the previous one of its kind gets the report after the loop.
   const int expect = c->expect_iters[plain ? 1 : 0];
-  auto issue_tail = [&](int rows) -> int {
-    if (extras) hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, B, (const VT*)X, B, (const VT*)X, n, T, c->dotpart);
+  // (its <b, x> sums were left in the second partial set by the update kernel of the same iteration)
+  auto issue_tail = [&](int rows, bool bx_ready) -> int {
+    if (extras && !bx_ready)
+      hipLaunchKernelGGL((k_dot<2, VT>), dim3(nb), dim3(256), 0, s, B, (const VT*)X, B, (const VT*)X, n, T, c->dotpart);
     c->tail_seq += 1;
-    hipLaunchKernelGGL(k_pcg_tail, dim3(T), dim3(256), 0, s, c->d_state, c->dotpart, nb, T, extras ? 1 : 0, c->alog,
+    hipLaunchKernelGGL(k_pcg_tail, dim3(T), dim3(256), 0, s, c->d_state, c->dotpart + (size_t)nb * MAX_COLS, nb, T, extras ? 1 : 0, c->alog,
                        c->blog, want_logs ? rows : 0, hs, hdot, c->h_buf, c->h_buf + cnt, c->h_flags, c->tail_seq);
     NUGPR_HIP(hipGetLastError());
     return NUGPR_OK;
@@ -595,18 +634,20 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
     if ((rc = plain ? run_pade_q(c, Dcur, Q, T, s) : run_matvec(c, Dcur, Q, T, s))) return rc;
     hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, Dcur, (const VT*)Q, Dcur, (const VT*)Q, n, T, c->dotpart);
     hipLaunchKernelGGL(k_pcg_alpha, dim3(T), dim3(256), 0, s, c->d_state, c->dotpart, nb, it, c->alog);
-    hipLaunchKernelGGL((k_update_xr<VT>), dim3(eg), dim3(256), 0, s, X, R, first ? B : (const VT*)R, Dcur, (const VT*)Q,
-                       c->d_state, n, T, first ? 1 : 0);
+    // the update, fused with ||r||^2 for the stop test and, in the iteration expected to be the last, <b, x>
+    const bool report = it + 1 >= expect || it + 1 >= max_iter;
+    hipLaunchKernelGGL((k_update_xr_dots<VT>), dim3(nb), dim3(256), 0, s, X, R, first ? B : (const VT*)R, Dcur,
+                       (const VT*)Q, (report && extras) ? B : (const VT*)nullptr, c->d_state, n, T, first ? 1 : 0,
+                       c->dotpart);
     first = false;
     // stop test first: when every column has converged the preconditioner apply is not needed
-    hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, R, R, R, R, n, T, c->dotpart);
-    hipLaunchKernelGGL(k_pcg_check, dim3(T), dim3(256), 0, s, c->d_state, c->dotpart, nb, it, tol2);
     c->flag_seq += 1;
-    hipLaunchKernelGGL(k_copy_flags, dim3(1), dim3(1), 0, s, c->d_state, c->h_flags, T, c->flag_seq);
+    hipLaunchKernelGGL(k_pcg_check, dim3(T), dim3(256), 0, s, c->d_state, c->dotpart, nb, it, tol2, T, c->h_flags,
+                       c->flag_seq);
     NUGPR_HIP(hipGetLastError());
     tail_current = false;
-    if (it + 1 >= expect || it + 1 >= max_iter) {
-      if ((rc = issue_tail(it + 1))) return rc;
+    if (report) {
+      if ((rc = issue_tail(it + 1, true))) return rc;
       tail_current = true;
     }
     if ((rc = wait_seq(&c->h_flags->seq, c->flag_seq, s))) return rc;
@@ -621,7 +662,7 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
     Dcur = D;
   }
   c->expect_iters[plain ? 1 : 0] = it > 0 ? it : 1;
-  if (!tail_current && (rc = issue_tail(it))) return rc;
+  if (!tail_current && (rc = issue_tail(it, false))) return rc;
   if ((rc = wait_seq(&c->h_flags->tail_seq, c->tail_seq, s))) return rc;
   bool all_conv = true;
   int mx = 0;
