@@ -221,6 +221,7 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   c->Uv = w + L.o_U;
   c->x0 = w + L.o_x0;
   c->Z0v = w + L.o_Z0;
+  c->S0v = w + L.o_S0;
   c->assign = reinterpret_cast<int32_t*>(w + L.o_assign);
   c->rep_ptr = reinterpret_cast<int32_t*>(w + L.o_rep_ptr);
   c->rep_pts = reinterpret_cast<int32_t*>(w + L.o_rep_pts);

@@ -157,7 +157,7 @@ struct Layout {
   size_t o_Spart = 0, o_Ppart = 0, o_dot = 0, o_state = 0, o_alog = 0, o_blog = 0;
   size_t o_theta = 0, o_logdet = 0, o_tiles = 0, o_items = 0;
   size_t o_Xs = 0, o_Xn = 0, o_Rs = 0, o_Rn = 0;
-  size_t o_x0 = 0, o_Z0 = 0, o_P = 0, o_Clo = 0;
+  size_t o_x0 = 0, o_Z0 = 0, o_P = 0, o_Clo = 0, o_S0 = 0;
   size_t o_assign = 0, o_rep_ptr = 0, o_rep_pts = 0;
   size_t items_bytes = 0;
   int n_dot_blocks = 0;
@@ -188,6 +188,7 @@ struct nugpr_ctx {
   // M^-1 [y | L Z]: the first preconditioned residual of every solve on the context's own right-hand
   // sides; it depends on the factor only, so the factorisation computes it once
   void* Z0v = nullptr;
+  void* S0v = nullptr;                   // W^T z_0: the projection the first product of such a solve needs
   bool z0_ready = false;
   // Default (one-hot) basis: W^T D is a sum over each representative's points and W P a gather, so the
   // dense W is not streamed.  assign[p]: row of C / S / P that point p belongs to; rep_ptr / rep_pts: the

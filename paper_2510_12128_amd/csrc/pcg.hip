@@ -349,12 +349,14 @@ int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s) {
   const Layout& L = c->L;
   int rc;
   const uint64_t ppart = (uint64_t)L.ncr * T;
-  // S_j = W_j^T D_j (dense W: in column slabs of W_j^T that are then added up)
-  if ((rc = run_project(c, D, T, s))) return rc;
+  // S_j = W_j^T D_j (dense W: in column slabs of W_j^T that are then added up); the projection of z_0, the
+  // first direction of every solve on the context's own right-hand sides, is kept with the factor
+  const bool s_known = D == c->Z0v && T == L.T && c->z0_ready;
+  if (!s_known && (rc = run_project(c, D, T, s))) return rc;
   // Q_i = K_ii D_i   and   P = C_offdiag S (column slabs), one launch
   StripPort k0{}, k1{};
   k0.A = c->Kd; k0.in = D; k0.out = Q; k0.nin = 1; k0.scale = c->op_scale; k0.diag_add = c->op_shift;
-  k1.A = c->C; k1.in = c->Spart; k1.nin = 1; k1.out = c->Ppart; k1.out_part_stride = ppart; k1.scale = c->op_scale;
+  k1.A = c->C; k1.in = s_known ? c->S0v : c->Spart; k1.nin = 1; k1.out = c->Ppart; k1.out_part_stride = ppart; k1.scale = c->op_scale;
   const bool timed = c->prof_on && (size_t)(2 * c->prof_used + 1) < c->prof_ev.size();
   if (timed) NUGPR_HIP(hipEventRecord(c->prof_ev[2 * c->prof_used], s));
   if ((rc = launch_strip(c->tab_KC, k0, k1, T, c->acc64, s))) return rc;
@@ -704,6 +706,10 @@ static int store_known_t(nugpr_ctx* c, hipStream_t s) {
     hipLaunchKernelGGL(k_store_known, dim3(L.T), dim3(256), 0, s, c->d_state, c->dotpart, nb, 1);
   }
   NUGPR_HIP(hipGetLastError());
+  // W^T z_0
+  int rc = run_project(c, c->Z0v, L.T, s);
+  if (rc) return rc;
+  NUGPR_HIP(hipMemcpyAsync(c->S0v, c->Spart, (size_t)L.ncr * L.T * sizeof(VT), hipMemcpyDeviceToDevice, s));
   return NUGPR_OK;
 }
 
