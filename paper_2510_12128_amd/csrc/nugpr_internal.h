@@ -266,7 +266,10 @@ int launch_factor(nugpr_ctx* c, hipStream_t s);
 
 // pcg.hip ---------------------------------------------------------------------
 // (vector blocks are the context's internal type: fp64 when acc64, else fp32)
-int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s);
+// (dq_partial: if not null and the basis is one-hot, the per-workgroup sums of <d, q> per column are left
+// there by the product's last kernel, in the layout of the solver's dot products; returns 1 in *dq_done then)
+int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s, double* dq_partial = nullptr,
+               bool* dq_done = nullptr);
 int run_precond(nugpr_ctx* c, const void* R, void* Z, int T, hipStream_t s);
 // What a loss evaluation needs besides the solution, fetched with the solve's last synchronisation:
 // <b_c, x_c> per column and rho_0 = <r_0, M^-1 r_0>.

@@ -343,9 +343,9 @@ int from_internal(nugpr_ctx* c, const void* src, float* dst, int64_t count, hipS
 // operator applications on internal vector blocks
 // ---------------------------------------------------------------------------
 static int run_project(nugpr_ctx* c, const void* D, int T, hipStream_t s);
-static int run_expand(nugpr_ctx* c, void* Q, int T, hipStream_t s);
+static int run_expand(nugpr_ctx* c, void* Q, int T, hipStream_t s, const void* D = nullptr, double* dq_partial = nullptr);
 
-int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s) {
+int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s, double* dq_partial, bool* dq_done) {
   const Layout& L = c->L;
   int rc;
   const uint64_t ppart = (uint64_t)L.ncr * T;
@@ -370,8 +370,10 @@ int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s) {
     if ((rc = launch_strip(c->tab_C, k2, k2, T, c->acc64, s))) return rc;
   }
   if (L.nsP > 1 && (rc = launch_sum_parts(c->Ppart, c->Ppart, (int64_t)ppart, L.nsP, ppart, c->acc64, s))) return rc;
-  // Q_i += W_i P_i
-  return run_expand(c, Q, T, s);
+  // Q_i += W_i P_i (and, on request, the partial sums of <d, q> in the same pass)
+  const bool fuse = dq_partial && c->onehot;
+  if (dq_done) *dq_done = fuse;
+  return run_expand(c, Q, T, s, fuse ? D : nullptr, fuse ? dq_partial : nullptr);
 }
 
 // out = a * x  (elementwise over a vector block)
@@ -437,6 +439,39 @@ __global__ __launch_bounds__(256) void k_onehot_expand(VT* __restrict__ Q, const
   }
 }
 
+// the same with the reduction that follows a product in the solver: partial = per-workgroup sums of d q_new
+// per column, rows split among the workgroups as in k_dot
+template <typename VT>
+__global__ __launch_bounds__(256) void k_onehot_expand_dot(VT* __restrict__ Q, const VT* __restrict__ P,
+                                                           const int32_t* __restrict__ assign,
+                                                           const VT* __restrict__ D, int64_t n, int T,
+                                                           double* __restrict__ partial) {
+  __shared__ double red[256];
+  const int rpp = 256 / T;
+  const int tid = threadIdx.x;
+  const int myrow = tid / T, col = tid - myrow * T;
+  const bool live = myrow < rpp;
+  const int64_t rows_per_block = (n + gridDim.x - 1) / gridDim.x;
+  const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
+  const int64_t r1 = r0 + rows_per_block < n ? r0 + rows_per_block : n;
+  double s0 = 0.0;
+  if (live) {
+    for (int64_t p = r0 + myrow; p < r1; p += rpp) {
+      const int64_t idx = p * T + col;
+      const VT qn = (VT)((double)Q[idx] + (double)P[(int64_t)assign[p] * T + col]);
+      Q[idx] = qn;
+      s0 = fma((double)D[idx], (double)qn, s0);
+    }
+  }
+  red[tid] = s0;
+  __syncthreads();
+  if (tid < T) {
+    double sacc = 0.0;
+    for (int k = 0; k < rpp; ++k) sacc += red[k * T + tid];
+    partial[(int64_t)blockIdx.x * MAX_COLS + tid] = sacc;
+  }
+}
+
 static int elementwise_grid(int64_t n, int T);
 
 // S = W^T D into the first slab of Spart (summed over the column slabs when W is dense)
@@ -459,8 +494,15 @@ static int run_project(nugpr_ctx* c, const void* D, int T, hipStream_t s) {
 }
 
 // Q += W P with P the first slab of Ppart
-static int run_expand(nugpr_ctx* c, void* Q, int T, hipStream_t s) {
+static int run_expand(nugpr_ctx* c, void* Q, int T, hipStream_t s, const void* D, double* dq_partial) {
   const Layout& L = c->L;
+  if (c->onehot && dq_partial) {
+    const int nb = L.n_dot_blocks;
+    if (c->acc64) hipLaunchKernelGGL((k_onehot_expand_dot<double>), dim3(nb), dim3(256), 0, s, (double*)Q, (const double*)c->Ppart, c->assign, (const double*)D, (int64_t)L.n, T, dq_partial);
+    else hipLaunchKernelGGL((k_onehot_expand_dot<float>), dim3(nb), dim3(256), 0, s, (float*)Q, (const float*)c->Ppart, c->assign, (const float*)D, (int64_t)L.n, T, dq_partial);
+    NUGPR_HIP(hipGetLastError());
+    return NUGPR_OK;
+  }
   if (c->onehot) {
     const int grid = elementwise_grid(L.n, T);
     if (c->acc64) hipLaunchKernelGGL((k_onehot_expand<double>), dim3(grid), dim3(256), 0, s, (double*)Q, (const double*)c->Ppart, c->assign, (int64_t)L.n, T);
@@ -633,8 +675,10 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
   };
   bool tail_current = false;
   while (it < max_iter && c->h_flags->n_active > 0) {
-    if ((rc = plain ? run_pade_q(c, Dcur, Q, T, s) : run_matvec(c, Dcur, Q, T, s))) return rc;
-    hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, Dcur, (const VT*)Q, Dcur, (const VT*)Q, n, T, c->dotpart);
+    bool dq_done = false;
+    if ((rc = plain ? run_pade_q(c, Dcur, Q, T, s) : run_matvec(c, Dcur, Q, T, s, c->dotpart, &dq_done))) return rc;
+    if (!dq_done)
+      hipLaunchKernelGGL((k_dot<1, VT>), dim3(nb), dim3(256), 0, s, Dcur, (const VT*)Q, Dcur, (const VT*)Q, n, T, c->dotpart);
     hipLaunchKernelGGL(k_pcg_alpha, dim3(T), dim3(256), 0, s, c->d_state, c->dotpart, nb, it, c->alog);
     // the update, fused with ||r||^2 for the stop test and, in the iteration expected to be the last, <b, x>
     const bool report = it + 1 >= expect || it + 1 >= max_iter;
