@@ -577,6 +577,19 @@ int nugpr_train_step(nugpr_ctx* c, double* log_theta, double* adam_m, double* ad
   worst = std::max(worst, rc);
   *nll0 = r0.nll;
   const bool forward = (c->params.flags & NUGPR_FD_FORWARD) != 0;
+  // A forward quotient takes both of its losses by the same route, so that what the fp32 factor
+  // contributes to each cancels: the split-preconditioned operator of the Pade log-determinant goes
+  // through the identity relation on the factored blocks (base loss, alpha, sigma^2) but through the
+  // streamed blocks after a lengthscale has changed, and the lengthscale quotients therefore get a base
+  // loss of their own, evaluated on the factored blocks by the streamed route.
+  nugpr_mll_result r0_general = r0;
+  if (forward && (c->params.flags & NUGPR_LOGDET_PADE) && !(c->params.flags & NUGPR_NO_SHORTCUTS)) {
+    c->general_route = true;
+    rc = mll_impl(c, theta.data(), &r0_general, true, stream);
+    c->general_route = false;
+    if (rc < 0 || rc == NUGPR_INDEFINITE) return rc;
+    worst = std::max(worst, rc);
+  }
   for (int k = 0; forward && k < p; ++k) {
     // Forward quotient on theta_i, step halved until two consecutive quotients agree (Section 3.1);
     // the gradient with respect to log(theta_i) is theta_i times it.
@@ -592,7 +605,7 @@ int nugpr_train_step(nugpr_ctx* c, double* log_theta, double* adam_m, double* ad
       theta[i] = t0;
       if (rc < 0 || rc == NUGPR_INDEFINITE) return rc;
       worst = std::max(worst, rc);
-      g = (r1.nll - r0.nll) / delta;
+      g = (r1.nll - (k < 2 ? r0.nll : r0_general.nll)) / delta;
       halv = e;
       if (e > 0 && std::fabs(g - g_prev) <= c->params.fd_threshold * std::fabs(g)) break;
       g_prev = g;

@@ -224,6 +224,7 @@ struct nugpr_ctx {
   // The stored blocks are the very ones the factor was computed from while build_gen == factor_gen:
   // then Y K_diag Y^T = I for the stored K_diag and Y = L^-1 (eq. (linear1)).
   uint64_t build_gen = 0, factor_gen = ~0ull;
+  bool general_route = false;   // take the streamed-K_diag route even where the identity relation holds
   // SPD compensation (eq. (krep)): host copy of the representatives and lambda_0 of the last assembly.
   // Clo holds what fp32 storage of C - lambda_0 I drops: C_exact - lambda_0 I - C_stored, itself in fp32,
   // applied as a second small product so that the compensation term is carried to ~2^-48.
