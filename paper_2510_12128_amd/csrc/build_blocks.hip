@@ -74,8 +74,14 @@ __global__ __launch_bounds__(256) void k_scale_points(const ScaleArgs a, const C
   if (sub == 0) N[pr] = nrm;
 }
 
+// 2^f on [-1/2, 1/2]: degree-6 interpolant at the Chebyshev nodes (near-minimax), relative error
+// < 2.6e-9, a twentieth of the fp32 rounding that follows
+constexpr int EXP2_TERMS = 7;
+static const double EXP2_COEF[EXP2_TERMS] = {1.0, 0.69314720670283259, 0.2402265092228876, 0.055503272266703242,
+                                             0.009618056678524561, 0.0013400428177608545, 0.00015461444698568769};
+
 struct PanelArgs {
-  double alpha;
+  double coef[EXP2_TERMS];   // alpha times the coefficients of 2^f
   float diag_val;       // diagonal entries: float(alpha + sigma^2); coupling under compensation: float(alpha - lambda_0)
   int keep_same;        // coupling: keep the entries between representatives of one cluster (compensation)
   int32_t kd;           // coordinates per point in the scaled array (multiple of 4)
@@ -83,48 +89,32 @@ struct PanelArgs {
 
 constexpr int ST_LD = 20;            // row stride of the staging area (floats): rows stay 16-byte aligned
 
-// alpha * 2^(-a) for a >= 0 (up to rounding), rounded once to fp32.
-// a = n + r with n = rint(a) by the 1.5 * 2^52 trick (n also lands in the low word of the
-// sum), 2^-r = 2^f, f = n - a in [-1/2, 1/2], by a degree-7 polynomial; the factor 2^-n is a
-// subtraction in the exponent field.  Arguments above 900 give 2^-900 alpha, which rounds to zero like the true
-// value does.  Only full-rate vector instructions are used.
+// alpha * 2^a for a <= 0 (up to rounding), rounded once to fp32.
+// a = n + f with n = rint(a) by the 1.5 * 2^52 trick (n also lands, in two's complement, in the low word
+// of the sum) and f = a - n in [-1/2, 1/2]; alpha 2^f by a degree-6 polynomial whose coefficients arrive
+// already multiplied by alpha; the factor 2^n is applied to the fp32 value (exact, except where the
+// result is subnormal or vanishes, as the true value does).  Arguments below -900 are taken as -900.
+// Only full-rate vector instructions are used.
 // W values at a time, step by step across all of them: a dependent fp64 instruction can issue only
 // every other slot, so W independent chains keep the vector ALU busy where one leaves it half idle.
 template <int W>
-__device__ __forceinline__ void kernel_values(const double (&arg)[W], double alpha, float (&out)[W]) {
+__device__ __forceinline__ void kernel_values(const double (&arg)[W], const double (&co)[EXP2_TERMS], float (&out)[W]) {
   constexpr double MAGIC = 6755399441055744.0;            // 1.5 * 2^52
   double a[W], big[W], f[W], p[W];
 #pragma unroll
-  for (int j = 0; j < W; ++j) a[j] = fmin(arg[j], 900.0);
+  for (int j = 0; j < W; ++j) a[j] = fmax(arg[j], -900.0);
 #pragma unroll
   for (int j = 0; j < W; ++j) big[j] = a[j] + MAGIC;
 #pragma unroll
-  for (int j = 0; j < W; ++j) f[j] = (big[j] - MAGIC) - a[j];
-  // 2^f on [-1/2, 1/2]: degree-7 interpolant at the Chebyshev nodes (near-minimax), relative error
-  // < 6e-11, a thousandth of the fp32 rounding that follows
-  constexpr double C0 = 0.99999999995956157, C1 = 0.69314718055683477, C2 = 0.24022651213499499,
-                   C3 = 0.055504109063197353, C4 = 0.0096180256132207473, C5 = 0.0013333478477891695,
-                   C6 = 0.00015469729234889767, C7 = 1.5303699899644103e-05;
+  for (int j = 0; j < W; ++j) f[j] = a[j] - (big[j] - MAGIC);
 #pragma unroll
-  for (int j = 0; j < W; ++j) p[j] = fma(C7, f[j], C6);
+  for (int j = 0; j < W; ++j) p[j] = fma(co[6], f[j], co[5]);
 #pragma unroll
-  for (int j = 0; j < W; ++j) p[j] = fma(p[j], f[j], C5);
+  for (int k = 4; k >= 0; --k)
 #pragma unroll
-  for (int j = 0; j < W; ++j) p[j] = fma(p[j], f[j], C4);
+    for (int j = 0; j < W; ++j) p[j] = fma(p[j], f[j], co[k]);
 #pragma unroll
-  for (int j = 0; j < W; ++j) p[j] = fma(p[j], f[j], C3);
-#pragma unroll
-  for (int j = 0; j < W; ++j) p[j] = fma(p[j], f[j], C2);
-#pragma unroll
-  for (int j = 0; j < W; ++j) p[j] = fma(p[j], f[j], C1);
-#pragma unroll
-  for (int j = 0; j < W; ++j) p[j] = fma(p[j], f[j], C0);
-#pragma unroll
-  for (int j = 0; j < W; ++j) {
-    const int n = __double2loint(big[j]);
-    const double scaled = __hiloint2double(__double2hiint(p[j]) - (n << 20), __double2loint(p[j]));
-    out[j] = (float)(alpha * scaled);
-  }
+  for (int j = 0; j < W; ++j) out[j] = ldexpf((float)p[j], __double2loint(big[j]));
 }
 
 // One workgroup = one 64 x 64 tile (tr, tc), tc <= tr, of one square symmetric matrix (a cluster's
@@ -147,11 +137,11 @@ __device__ __forceinline__ void kernel_values(const double (&arg)[W], double alp
 // run on the tiles that need them.
 // NKS = kd / 4 when positive; NKS = 0 handles any kd with a loop over the coordinate groups.
 template <bool COUPLING, int NKS>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(7, 7)))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(COUPLING ? 6 : 7, 7)))
 void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const double* __restrict__ S,
                   const double* __restrict__ N, float* __restrict__ out_base, int r) {
   extern __shared__ __attribute__((aligned(16))) double sA[];      // 4 * kd * 16 doubles: row operands
-  __shared__ double sNr[TILE];
+  __shared__ __attribute__((aligned(32))) double sNr[TILE];
   __shared__ __attribute__((aligned(16))) float sT[4][16 * ST_LD];      // per wave: one 16-row group in transit
 
   const BuildItem cur = items[blockIdx.x];
@@ -159,7 +149,8 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
   const int total = (int)cur.total;
   const uint32_t ld = cur.ld, prow = cur.prow;
   float* __restrict__ out = out_base + cur.out_off;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform: lives in a scalar register
   const int m = lane & 15, kk = lane >> 4;
   const int kd = a.kd, nks = NKS > 0 ? NKS : kd / 4;
   const int p0 = tr * TILE, q0 = tc * TILE;
@@ -178,26 +169,33 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) bv[ks] = Sc[ks * 64];
   }
-  const double nc = N[qg + m];
+  const double nc = (N + qg)[(uint32_t)m];
   {
     constexpr int NCA = NKS > 0 ? NKS : MAX_D / 4;              // row operand elements per thread (4 kd 16 / 256)
     const double* __restrict__ Sg = S + (uint64_t)((prow + p0) >> 4) * gstride;
     const int n_a = 4 * (int)gstride;
     double ra[NCA];
-    const double rr = N[prow + p0 + (tid & (TILE - 1))];
+    const double rr = (N + (prow + p0))[(uint32_t)(tid & (TILE - 1))];
 #pragma unroll
-    for (int j = 0; j < NCA; ++j) ra[j] = Sg[min(tid + 256 * j, n_a - 1)];
+    for (int j = 0; j < NCA; ++j)                 // (byte offsets in 32 bits: n_a is at most 4096)
+      ra[j] = *reinterpret_cast<const double*>(reinterpret_cast<const char*>(Sg) +
+                                               (uint32_t)(min(tid + 256 * j, n_a - 1) << 3));
     if (tid < TILE) sNr[tid] = rr;
-    // the row operands (4 groups x kd coordinates x 16 points, already in operand order)
+    // the row operands (4 groups x kd coordinates x 16 points, already in operand order), doubled
 #pragma unroll
     for (int j = 0; j < NCA; ++j)
-      if (tid + 256 * j < n_a) sA[tid + 256 * j] = ra[j];
+      if (tid + 256 * j < n_a) sA[tid + 256 * j] = 2.0 * ra[j];
   }
   __syncthreads();
 
+  // the accumulators start at -(|x_p|^2 + |x_q|^2) and the row operands carry a factor 2: what comes
+  // out is -|x_p - x_q|^2 in the scaled coordinates, the exponent of 2 for the entry
   v4d acc[4];
 #pragma unroll
-  for (int ti = 0; ti < 4; ++ti) acc[ti] = (v4d){0.0, 0.0, 0.0, 0.0};
+  for (int ti = 0; ti < 4; ++ti) {
+    const double4 nr = *reinterpret_cast<const double4*>(&sNr[16 * ti + 4 * kk]);
+    acc[ti] = (v4d){-nr.x - nc, -nr.y - nc, -nr.z - nc, -nr.w - nc};
+  }
   if (NKS > 0) {
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks)
@@ -214,7 +212,6 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
   }
 
   const float dv = a.diag_val;
-  const double alpha = a.alpha;
   float* __restrict__ sTw = &sT[wave][0];
   // staging of one 16-row group: this lane writes rows 4 kk + i, column m; it reads row lane / 4,
   // columns 4 (lane % 4) .. + 3 for the store of the tile's own rows
@@ -225,13 +222,16 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
   // Blocked storage (blocked_index): strip tr, column blocks 2 tc and 2 tc + 1 hold the tile, each as eight
   // 16 x 16 fragments of 1 KiB.  The tile itself: row group ti, this wave's 16 columns = fragment
   // (ti, wave % 2) of block 2 tc + wave / 2; lane l holds row l / 4, columns 4 (l % 4) .. + 3: float4 number l
+  // (wave-uniform base + a 32-bit lane offset: the store takes the base from scalar registers)
   float* __restrict__ od = out + (uint64_t)tr * TILE * ld64 + (uint64_t)(2 * tc + (wave >> 1)) * (TILE * BLK_COLS) +
-                           (wave & 1) * FRAG + 4 * lane;
+                           (wave & 1) * FRAG;
+  const uint32_t od_lane = 4u * (uint32_t)lane;
   // its mirror image (strip tc): rows 16 wave + m, columns 16 ti + 4 kk .. + 3 of the tile = fragment
   // (wave, ti % 2) of block 2 tr + ti / 2, row m, columns 4 kk ..; a tile on the diagonal is its own mirror
   // image, entry for entry, and is simply written twice
   float* __restrict__ om = out + (uint64_t)tc * TILE * ld64 + (uint64_t)(2 * tr) * (TILE * BLK_COLS) +
-                           (2 * wave) * FRAG + m * 16 + 4 * kk;
+                           (2 * wave) * FRAG;
+  const uint32_t om_lane = (uint32_t)(m * 16 + 4 * kk);
 
   // the sixteen entries of this lane, one 16-row group at a time: masked (EDGE) or not
   auto entries = [&](auto edge_c) {
@@ -241,8 +241,8 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
       float x[4];
       double arg[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) arg[i] = fma(-2.0, acc[ti][i], sNr[16 * ti + 4 * kk + i] + nc);
-      kernel_values<4>(arg, alpha, x);
+      for (int i = 0; i < 4; ++i) arg[i] = acc[ti][i];
+      kernel_values<4>(arg, a.coef, x);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int row = 16 * ti + 4 * kk + i;
@@ -262,7 +262,7 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
         }
         st_w[i * ST_LD] = x[i];
       }
-      *reinterpret_cast<float4*>(om + (ti >> 1) * (TILE * BLK_COLS) + (ti & 1) * FRAG) = make_float4(x[0], x[1], x[2], x[3]);
+      *reinterpret_cast<float4*>(om + (ti >> 1) * (TILE * BLK_COLS) + (ti & 1) * FRAG + om_lane) = make_float4(x[0], x[1], x[2], x[3]);
       // The staging rows are wave-private and the LDS serves one wave's accesses in order: the read below
       // sees this group's writes, and the next group's writes come after it.
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -271,7 +271,7 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
       const float4 rowv = *st_r;
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
-      *reinterpret_cast<float4*>(od + (2 * ti) * FRAG) = rowv;
+      *reinterpret_cast<float4*>(od + (2 * ti) * FRAG + od_lane) = rowv;
     }
   };
   // tiles that can hold dropped or replaced entries: on the diagonal, at the ragged end, or (coupling)
@@ -453,7 +453,7 @@ int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s) {
   }
   sa.d = L.d;
   PanelArgs a;
-  a.alpha = alpha;
+  for (int k = 0; k < EXP2_TERMS; ++k) a.coef[k] = alpha * EXP2_COEF[k];
   a.diag_val = (float)(alpha + sigma2);
   a.kd = pair_kd(L.d);
   a.keep_same = 0;
