@@ -98,7 +98,7 @@ void build_tables(const Layout& L, Tables& t) {
       const uint64_t a_off = c.koff + (uint64_t)s * TILE * c.ld;
       const uint32_t row = c.row0 + s * TILE;
       t.KC.push_back(make_item(a_off, c.ld, nrows, 0, c.b, c.row0, row, s * TILE, 0, 0, 0, 1.f));
-      t.KC.back().blocked = 1;
+      t.KC.back().blocked = c.nt >= 2 ? 3 : 1;      // K_ii is symmetric: its strips pair up tile by tile
       t.WP.push_back(make_item((uint64_t)row * L.ldw, (uint32_t)L.ldw, nrows, 0, r, (uint32_t)i * r, row, 0, 0, 0, 0, 0.f));
       t.lowG.push_back(make_item(a_off, c.ld, nrows, 0, s * TILE + nrows, c.row0, row, s * TILE, 0, 0, 1, 0.f));
       t.upG.push_back(make_item(a_off, c.ld, nrows, s * TILE, c.b, c.row0, row, s * TILE, 0, 0, 2, 0.f));
@@ -136,6 +136,8 @@ void build_tables(const Layout& L, Tables& t) {
 int upload_table(const std::vector<StripItem>& v, StripItem*& cursor, StripTable& tab, hipStream_t s) {
   tab.dev = cursor;
   tab.count = (int)v.size();
+  tab.sym = false;
+  for (const StripItem& it : v) tab.sym = tab.sym || (it.blocked & 2u) != 0;
   if (!v.empty())
     NUGPR_HIP(hipMemcpyAsync(cursor, v.data(), v.size() * sizeof(StripItem), hipMemcpyHostToDevice, s));
   cursor += v.size();

@@ -75,7 +75,8 @@ struct StripItem {
   uint8_t port;          // 0 / 1: which (matrix, in, out) triple of the launch
   uint8_t mode;          // 0 full, 1 lower triangle (col <= row), 2 upper triangle (col >= row)
   float diag_add;        // 1 for square diagonal blocks: out += port.diag_add * in[row]; else 0
-  uint32_t blocked;      // 1: the matrix is stored in blocks of operand fragments (blocked_index), 0: row-major
+  uint32_t blocked;      // bit 0: the matrix is stored in blocks of operand fragments (blocked_index), else row-major;
+                         // bit 1: full strip of a symmetric square block, upper tiles read as transposed lower ones
 };
 static_assert(sizeof(StripItem) == 48, "StripItem layout");
 
@@ -101,6 +102,7 @@ struct StripArgs {
 struct StripTable {
   StripItem* dev = nullptr;
   int count = 0;
+  bool sym = false;      // some items are strips of symmetric blocks (StripItem::blocked bit 1)
 };
 
 // ---------------------------------------------------------------------------

@@ -330,7 +330,7 @@ struct RingCfg {
   static constexpr int LDS_BYTES = STAGES * STAGE_BYTES + 512;             // + slack for reads of unused columns
 };
 
-template <int NG, int RCH, int STAGES_>
+template <int NG, int RCH, int STAGES_, bool SYM>
 __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(2))) void k_strip_ring(const StripArgs a) {
 #if __HIP_DEVICE_COMPILE__
   typedef RingCfg<NG, RCH, STAGES_> Cfg;
@@ -347,7 +347,23 @@ __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(2))) void k
   const int m = lane & 15, kg = lane >> 4;
   const int nrows = (int)it.nrows;
   const int c_begin = (int)it.c_begin, c_end = (int)it.c_end;
-  const int nchunks = c_end > c_begin ? (c_end - c_begin + RCH - 1) / RCH : 0;
+  // Strips of a symmetric square block (flag bit 1, c_begin = 0): strip j of nt visits the 64-column tiles
+  // in the order p = (t - j) mod nt, t = 0 .. nt - 1, and takes tile (j, p) from its own rows when p <= j
+  // but as the transpose of tile (p, j), from strip p's rows, when p > j.  Strip p visits tile (p, j) at
+  // the same step t, so the two workgroups (dealt to the same die, started together) ask for the same
+  // 16 KiB at about the same time and the die's L2 fetches it from HBM once: the lower triangles are
+  // streamed, the upper ones never leave memory.
+  const bool sym = SYM && (it.blocked & 2u) != 0;
+  const int jt = (int)(it.row_in_block >> 6), ntile = (c_end + TILE - 1) >> 6;
+  const int nchunks = sym ? 2 * ntile : (c_end > c_begin ? (c_end - c_begin + RCH - 1) / RCH : 0);
+  // chunk ch: first column c of the product it covers; p > jt marks a transposed tile
+  auto locate = [&](const int ch, int& c, int& p) {
+    if (!sym) { c = c_begin + ch * RCH; p = 0; return false; }
+    p = (ch >> 1) - jt;
+    p += p < 0 ? ntile : 0;
+    c = TILE * p + RCH * (ch & 1);
+    return p > jt;
+  };
 
   if (wave == 4) {
     // ---- loader ----
@@ -367,18 +383,37 @@ __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(2))) void k
       rowoff[w] = blocked ? (uint64_t)((rw >> 4) * 2) * FRAG + (uint64_t)(rw & 15) * 16 : (uint64_t)rw * (uint64_t)it.lda;
     }
     const unsigned char* __restrict__ vbytes = reinterpret_cast<const unsigned char*>(vin);
+    // transposed tiles: the operand of (w, s) is fragment (2 half + s, w % 2) of column block 2 jt + w / 2
+    // of strip p, whole (every fragment of the padded block exists); lane l fetches the piece (row
+    // 4 ((l / 4) % 4) + l / 16, columns 4 (l % 4) .. + 3), which puts element (4 kg + i, m) of the fragment
+    // at float 64 i + 16 kg + m: the consumers read their four values with unit stride across the wave
+    const float* __restrict__ At = pt.A + it.a_off + (uint64_t)(2 * jt) * (TILE * BLK_COLS) +
+                                   (((lane >> 2) & 3) * 4 + (lane >> 4)) * 16 + (lane & 3) * 4;
     auto issue = [&](const int ch) {
-      const int c = c_begin + ch * RCH;
+      int c, p;
+      const bool tr = locate(ch, c, p);
       unsigned char* st = ring + (ch % STAGES) * Cfg::STAGE_BYTES;
+      if (SYM && tr) {
+        const float* __restrict__ Ap = At + (uint64_t)(p - jt) * TILE * (uint64_t)it.lda + (ch & 1) * (4 * FRAG);
 #pragma unroll
-      for (int w = 0; w < 4; ++w)
+        for (int w = 0; w < 4; ++w)
 #pragma unroll
-        for (int s = 0; s < NSTEP; ++s)
-          __builtin_amdgcn_global_load_lds(Ab + rowoff[w] + (uint64_t)c * cmul + s * smul, st + (w * NSTEP + s) * 1024, 16, 0, 0);
+          for (int s = 0; s < NSTEP; ++s)
+            __builtin_amdgcn_global_load_lds(Ap + (w >> 1) * (TILE * BLK_COLS) + (2 * s + (w & 1)) * FRAG,
+                                             st + (w * NSTEP + s) * 1024, 16, 0, 0);
+      } else {
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+#pragma unroll
+          for (int s = 0; s < NSTEP; ++s)
+            __builtin_amdgcn_global_load_lds(Ab + rowoff[w] + (uint64_t)c * cmul + s * smul, st + (w * NSTEP + s) * 1024, 16, 0, 0);
+      }
       // vector slab: rows in_row0 + c .., T columns, contiguous; 16-byte pieces past its last valid byte
-      // re-read the last valid piece (the consumers drop those rows)
-      const uint64_t slab0 = (uint64_t)(it.in_row0 + (uint32_t)c) * (uint64_t)T * 8u;
-      const int valid = min(RCH, c_end - c) * T * 8;                    // > 0
+      // re-read the last valid piece (the consumers drop those rows).  A chunk that lies wholly past the
+      // last column (second half of a ragged last tile) reads the last row instead and is dropped whole.
+      const int c_slab = min(c, c_end - 1);
+      const uint64_t slab0 = (uint64_t)(it.in_row0 + (uint32_t)c_slab) * (uint64_t)T * 8u;
+      const int valid = min(RCH, c_end - c_slab) * T * 8;               // > 0
       const int last_piece = ((valid - 1) >> 4) << 4;
 #pragma unroll
       for (int i = 0; i < Cfg::NSLAB; ++i) {
@@ -416,17 +451,22 @@ __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(2))) void k
   double daccy = 0.0;
 
   for (int ch = 0; ch < nchunks; ++ch) {
-    const int c = c_begin + ch * RCH;
+    int c, p_tile;
+    const bool tr = locate(ch, c, p_tile);
     __builtin_amdgcn_s_barrier();                             // chunk ch is in its stage
     const unsigned char* st = ring + (ch % STAGES) * Cfg::STAGE_BYTES;
     const float4* __restrict__ sAw = reinterpret_cast<const float4*>(st) + wave * (64 * NSTEP) + lane;
+    const float* __restrict__ sAt = reinterpret_cast<const float*>(st) + wave * (256 * NSTEP) + lane;
     const double* __restrict__ sV = reinterpret_cast<const double*>(st + Cfg::A_BYTES);
     // chunks that can hold dropped elements: past the last column, or touching the diagonal tile
     const bool masked = c + RCH > c_end || (it.mode == 1 && c + RCH > rib) || (it.mode == 2 && c < rib + TILE);
     const int kvalid = c_end - c;                             // vector rows of this chunk that exist
 #pragma unroll
     for (int s = 0; s < NSTEP; ++s) {
-      float4 av = sAw[s * 64];
+      // the operand: float4 number `lane` of the (wave, s) fragment, or, for a transposed tile, four floats 64 apart
+      float4 av;
+      if (SYM && tr) av = make_float4(sAt[s * 256], sAt[s * 256 + 64], sAt[s * 256 + 128], sAt[s * 256 + 192]);
+      else av = sAw[s * 64];
       const int k0 = 16 * s + 4 * kg;                         // chunk-local column of av.x
       const double* __restrict__ vr = sV + k0 * T;
       double y[4], b[NG][4];
@@ -548,17 +588,30 @@ int launch_strip(const StripTable& tab, const StripPort& p0, const StripPort& p1
   const int ng = (T - 1 + 15) / 16;
   // the ring kernels use more than the default 64 KiB of dynamic LDS: raise their limit once
   static const hipError_t ring_attr = []() {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_strip_ring<1, RING1_CH, RING1_ST>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, Ring1::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_strip_ring<2, RING2_CH, RING2_ST>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, Ring2::LDS_BYTES);
+    const void* k1[2] = {reinterpret_cast<const void*>(&k_strip_ring<1, RING1_CH, RING1_ST, false>),
+                         reinterpret_cast<const void*>(&k_strip_ring<1, RING1_CH, RING1_ST, true>)};
+    const void* k2[2] = {reinterpret_cast<const void*>(&k_strip_ring<2, RING2_CH, RING2_ST, false>),
+                         reinterpret_cast<const void*>(&k_strip_ring<2, RING2_CH, RING2_ST, true>)};
+    for (int v = 0; v < 2; ++v) {
+      hipError_t e = hipFuncSetAttribute(k1[v], hipFuncAttributeMaxDynamicSharedMemorySize, Ring1::LDS_BYTES);
+      if (e != hipSuccess) return e;
+      e = hipFuncSetAttribute(k2[v], hipFuncAttributeMaxDynamicSharedMemorySize, Ring2::LDS_BYTES);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
   }();
   NUGPR_HIP(ring_attr);
-  if (acc64 && ng == 1)
-    hipLaunchKernelGGL((k_strip_ring<1, RING1_CH, RING1_ST>), dim3(tab.count), dim3(320), Ring1::LDS_BYTES, s, a);
+  // tables with strips of symmetric blocks take the instantiation that pairs their tiles; the others keep
+  // the plain loop
+  const dim3 grid(tab.count), block(320);
+  if (acc64 && ng == 1 && tab.sym)
+    hipLaunchKernelGGL((k_strip_ring<1, RING1_CH, RING1_ST, true>), grid, block, Ring1::LDS_BYTES, s, a);
+  else if (acc64 && ng == 1)
+    hipLaunchKernelGGL((k_strip_ring<1, RING1_CH, RING1_ST, false>), grid, block, Ring1::LDS_BYTES, s, a);
+  else if (acc64 && ng == 2 && tab.sym)
+    hipLaunchKernelGGL((k_strip_ring<2, RING2_CH, RING2_ST, true>), grid, block, Ring2::LDS_BYTES, s, a);
   else if (acc64 && ng == 2)
-    hipLaunchKernelGGL((k_strip_ring<2, RING2_CH, RING2_ST>), dim3(tab.count), dim3(320), Ring2::LDS_BYTES, s, a);
+    hipLaunchKernelGGL((k_strip_ring<2, RING2_CH, RING2_ST, false>), grid, block, Ring2::LDS_BYTES, s, a);
   else if (acc64) launch_typed<true>(ng, dim3(tab.count), s, a);
   else launch_typed<false>(ng, dim3(tab.count), s, a);
   NUGPR_HIP(hipGetLastError());
