@@ -588,28 +588,24 @@ int launch_strip(const StripTable& tab, const StripPort& p0, const StripPort& p1
   const int ng = (T - 1 + 15) / 16;
   // the ring kernels use more than the default 64 KiB of dynamic LDS: raise their limit once
   static const hipError_t ring_attr = []() {
-    const void* k1[2] = {reinterpret_cast<const void*>(&k_strip_ring<1, RING1_CH, RING1_ST, false>),
-                         reinterpret_cast<const void*>(&k_strip_ring<1, RING1_CH, RING1_ST, true>)};
-    const void* k2[2] = {reinterpret_cast<const void*>(&k_strip_ring<2, RING2_CH, RING2_ST, false>),
-                         reinterpret_cast<const void*>(&k_strip_ring<2, RING2_CH, RING2_ST, true>)};
-    for (int v = 0; v < 2; ++v) {
-      hipError_t e = hipFuncSetAttribute(k1[v], hipFuncAttributeMaxDynamicSharedMemorySize, Ring1::LDS_BYTES);
-      if (e != hipSuccess) return e;
-      e = hipFuncSetAttribute(k2[v], hipFuncAttributeMaxDynamicSharedMemorySize, Ring2::LDS_BYTES);
-      if (e != hipSuccess) return e;
-    }
-    return hipSuccess;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_strip_ring<1, RING1_CH, RING1_ST, false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, Ring1::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_strip_ring<1, RING1_CH, RING1_ST, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, Ring1::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_strip_ring<2, RING2_CH, RING2_ST, false>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, Ring2::LDS_BYTES);
   }();
   NUGPR_HIP(ring_attr);
-  // tables with strips of symmetric blocks take the instantiation that pairs their tiles; the others keep
-  // the plain loop
+  // Tables with strips of symmetric blocks take the instantiation that pairs their tiles, the others the
+  // plain loop.  With two column groups (T > 17) the launch is bound by the matrix cores, the pairing
+  // saves nothing and its operand read costs 6 %: those launches read every strip whole.
   const dim3 grid(tab.count), block(320);
   if (acc64 && ng == 1 && tab.sym)
     hipLaunchKernelGGL((k_strip_ring<1, RING1_CH, RING1_ST, true>), grid, block, Ring1::LDS_BYTES, s, a);
   else if (acc64 && ng == 1)
     hipLaunchKernelGGL((k_strip_ring<1, RING1_CH, RING1_ST, false>), grid, block, Ring1::LDS_BYTES, s, a);
-  else if (acc64 && ng == 2 && tab.sym)
-    hipLaunchKernelGGL((k_strip_ring<2, RING2_CH, RING2_ST, true>), grid, block, Ring2::LDS_BYTES, s, a);
   else if (acc64 && ng == 2)
     hipLaunchKernelGGL((k_strip_ring<2, RING2_CH, RING2_ST, false>), grid, block, Ring2::LDS_BYTES, s, a);
   else if (acc64) launch_typed<true>(ng, dim3(tab.count), s, a);
