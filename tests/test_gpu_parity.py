@@ -35,6 +35,9 @@ CASES = {
     "ragged-t8": lambda: small_ragged(t=8),
     "ragged-t16": lambda: small_ragged(seed=4, t=16),
     "ragged-t32": lambda: small_ragged(seed=5, t=32, sizes=[300, 65, 257], spacing=6.5),
+    # cluster sizes whose last 64-column tile is more than half full, exactly half full, and one column wide:
+    # the strips of a diagonal block walk their tiles in a rotating order and read the upper ones transposed
+    "ragged-halves": lambda: small_ragged(seed=6, t=16, sizes=[104, 242, 160, 321], spacing=6.0),
     "tiny": lambda: I.make_small(n_clusters=3, sizes=[8, 12, 5], d=2, rank=2, t=4, seed=7, ell=1.5,
                                  spacing=3.5, sigma_blob=0.3, tol=1e-6, max_iter=50),
     "iso-d1": lambda: I.make_small(n_clusters=2, sizes=[90, 40], d=1, rank=3, t=3, seed=8, ell=0.8,
@@ -79,7 +82,7 @@ def test_build_blocks_matches_oracle(lib, case):
     ctx.close()
 
 
-@pytest.mark.parametrize("case", ["ragged-t8", "ragged-t16", "ragged-t32", "tiny", "iso-d1", "C1-wide"])
+@pytest.mark.parametrize("case", ["ragged-t8", "ragged-t16", "ragged-t32", "ragged-halves", "tiny", "iso-d1", "C1-wide"])
 def test_matvec_matches_oracle(lib, case):
     w = CASES[case]()
     print("case", w.name, flush=True)
@@ -124,7 +127,7 @@ def test_precond_factor_and_apply_match_oracle(lib, case):
     ctx.close()
 
 
-@pytest.mark.parametrize("case", ["ragged-t8", "ragged-t16", "ragged-t32", "tiny", "iso-d1", "C1", "C1-wide"])
+@pytest.mark.parametrize("case", ["ragged-t8", "ragged-t16", "ragged-t32", "ragged-halves", "tiny", "iso-d1", "C1", "C1-wide"])
 def test_pcg_solve_and_mll_match_oracle(lib, case):
     w = CASES[case]()
     print("case", w.name, flush=True)
