@@ -149,18 +149,36 @@ __device__ __forceinline__ void for_each_acc(v4f (&acc)[2][2], int tid, F f) {
         f(wy * 32 + 16 * i + 4 * (lane >> 4) + v, wx * 32 + 16 * j + (lane & 15), acc[i][j][v]);
 }
 
+// Workgroup -> (cluster, item) for a launch of `per` items for each of `nc` clusters: a 1-D grid of
+// die_grid(per, nc) workgroups.  Workgroups go round-robin to the 8 dies, each with an L2 of its own: with
+// the cluster as the slow index of a plain grid the tiles of one cluster, which all read the same panel,
+// would be spread over every die and the panel fetched eight times.  Here die d takes the clusters d,
+// d + 8, .. one after the other (the grid is rounded up to whole groups of 8 clusters; workgroups that
+// fall past the last cluster return at once).
+constexpr int NUM_DIES = 8;
+static inline unsigned die_grid(int per, int nc) { return (unsigned)per * NUM_DIES * ((nc + NUM_DIES - 1) / NUM_DIES); }
+__device__ __forceinline__ bool die_local_item(int per, int nc, int& cluster, int& item) {
+  const int id = (int)blockIdx.x;
+  const int die = id % NUM_DIES, slot = id / NUM_DIES;
+  cluster = die + NUM_DIES * (slot / per);
+  item = slot % per;
+  return cluster < nc;
+}
+
 // ---------------------------------------------------------------------------
 // Cholesky, step k
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_potrf_update(const ClusterInfo* __restrict__ cl, const float* __restrict__ Kd,
                                                       float* __restrict__ Lf, float* __restrict__ G, int k,
-                                                      PcgState* __restrict__ st) {
+                                                      int per, int nc, PcgState* __restrict__ st) {
   __shared__ float sA[TILE][SP];
   __shared__ float sB[TILE][SP];
   __shared__ float sT[TILE][TILE + 1];
   __shared__ float sI[TILE][TILE + 1];
-  const ClusterInfo c = cl[blockIdx.y];
-  const int mt = k + (int)blockIdx.x;
+  int ci, item;
+  if (!die_local_item(per, nc, ci, item)) return;
+  const ClusterInfo c = cl[ci];
+  const int mt = k + item;
   if (mt >= (int)c.nt) return;
   const int tid = threadIdx.x;
   const int b = (int)c.b;
@@ -227,7 +245,7 @@ __global__ __launch_bounds__(256) void k_potrf_update(const ClusterInfo* __restr
     }
   }
   __syncthreads();
-  if (bad && tid == 0) atomicMin(&st->bad_cluster, (int)blockIdx.y);
+  if (bad && tid == 0) atomicMin(&st->bad_cluster, ci);
   // ---- inverse of the lower-triangular tile: column cc by forward substitution, four lanes per column
   // sharing each row's sum (lanes 4 cc .. 4 cc + 3 sit in one wave) ----
   {
@@ -261,11 +279,13 @@ __global__ __launch_bounds__(256) void k_potrf_update(const ClusterInfo* __restr
 
 // tiles below the diagonal: L[m,k] <- L[m,k] * inv(L[k,k])^T
 __global__ __launch_bounds__(256) void k_potrf_trsm(const ClusterInfo* __restrict__ cl, float* __restrict__ Lf,
-                                                    const float* __restrict__ G, int k) {
+                                                    const float* __restrict__ G, int k, int per, int nc) {
   __shared__ float sA[TILE][SP];
   __shared__ float sB[TILE][SP];
-  const ClusterInfo c = cl[blockIdx.y];
-  const int mt = k + 1 + (int)blockIdx.x;
+  int ci, item;
+  if (!die_local_item(per, nc, ci, item)) return;
+  const ClusterInfo c = cl[ci];
+  const int mt = k + 1 + item;
   if (mt >= (int)c.nt) return;
   const int tid = threadIdx.x;
   float* L = Lf + c.koff;
@@ -284,13 +304,16 @@ __global__ __launch_bounds__(256) void k_potrf_trsm(const ClusterInfo* __restric
 // ---------------------------------------------------------------------------
 // stage 1: T = L21 * Y11, stored transposed in the mirror block (upper triangle of G)
 __global__ __launch_bounds__(256) void k_trtri_stage1(const ClusterInfo* __restrict__ cl, const float* __restrict__ Lf,
-                                                      float* __restrict__ G, int half) {
+                                                      float* __restrict__ G, int half, int per, int nc) {
   __shared__ float sA[TILE][SP];
   __shared__ float sB[TILE][SP];
   __shared__ float sT[TILE][TILE + 1];
-  const ClusterInfo c = cl[blockIdx.z];
-  const int start = (int)blockIdx.y * 2 * half, mid = start + half;
-  const int tm = mid + (int)blockIdx.x / half, tn = start + (int)blockIdx.x % half;
+  int ci, item;
+  if (!die_local_item(per, nc, ci, item)) return;
+  const ClusterInfo c = cl[ci];
+  const int node = item / (half * half), within = item % (half * half);
+  const int start = node * 2 * half, mid = start + half;
+  const int tm = mid + within / half, tn = start + within % half;
   if (mid >= (int)c.nt || tm >= (int)c.nt) return;
   const int tid = threadIdx.x;
   const float* L = Lf + c.koff;
@@ -312,12 +335,15 @@ __global__ __launch_bounds__(256) void k_trtri_stage1(const ClusterInfo* __restr
 
 // stage 2: Y21 = -Y22 * T
 __global__ __launch_bounds__(256) void k_trtri_stage2(const ClusterInfo* __restrict__ cl, float* __restrict__ G,
-                                                      int half) {
+                                                      int half, int per, int nc) {
   __shared__ float sA[TILE][SP];
   __shared__ float sB[TILE][SP];
-  const ClusterInfo c = cl[blockIdx.z];
-  const int start = (int)blockIdx.y * 2 * half, mid = start + half;
-  const int tm = mid + (int)blockIdx.x / half, tn = start + (int)blockIdx.x % half;
+  int ci, item;
+  if (!die_local_item(per, nc, ci, item)) return;
+  const ClusterInfo c = cl[ci];
+  const int node = item / (half * half), within = item % (half * half);
+  const int start = node * 2 * half, mid = start + half;
+  const int tm = mid + within / half, tn = start + within % half;
   if (mid >= (int)c.nt || tm >= (int)c.nt) return;
   const int tid = threadIdx.x;
   float* Y = G + c.koff;
@@ -392,16 +418,18 @@ int launch_factor(nugpr_ctx* c, hipStream_t s) {
   const Layout& L = c->L;
   hipLaunchKernelGGL(k_reset_bad, dim3(1), dim3(1), 0, s, c->d_state);
   for (int k = 0; k < L.ntmax; ++k) {
-    hipLaunchKernelGGL(k_potrf_update, dim3(L.ntmax - k, L.nc), dim3(256), 0, s, c->d_cl, c->Kd, c->Lf, c->G, k,
-                       c->d_state);
+    hipLaunchKernelGGL(k_potrf_update, dim3(die_grid(L.ntmax - k, L.nc)), dim3(256), 0, s, c->d_cl, c->Kd, c->Lf, c->G, k,
+                       L.ntmax - k, L.nc, c->d_state);
     if (k + 1 < L.ntmax)
-      hipLaunchKernelGGL(k_potrf_trsm, dim3(L.ntmax - k - 1, L.nc), dim3(256), 0, s, c->d_cl, c->Lf, c->G, k);
+      hipLaunchKernelGGL(k_potrf_trsm, dim3(die_grid(L.ntmax - k - 1, L.nc)), dim3(256), 0, s, c->d_cl, c->Lf, c->G, k,
+                         L.ntmax - k - 1, L.nc);
   }
   for (int half = 1; half < L.ntmax; half *= 2) {
     const int nodes = (L.ntmax + 2 * half - 1) / (2 * half);
-    dim3 grid(half * half, nodes, L.nc);
-    hipLaunchKernelGGL(k_trtri_stage1, grid, dim3(256), 0, s, c->d_cl, c->Lf, c->G, half);
-    hipLaunchKernelGGL(k_trtri_stage2, grid, dim3(256), 0, s, c->d_cl, c->G, half);
+    const int per = half * half * nodes;
+    dim3 grid(die_grid(per, L.nc));
+    hipLaunchKernelGGL(k_trtri_stage1, grid, dim3(256), 0, s, c->d_cl, c->Lf, c->G, half, per, L.nc);
+    hipLaunchKernelGGL(k_trtri_stage2, grid, dim3(256), 0, s, c->d_cl, c->G, half, per, L.nc);
   }
   hipLaunchKernelGGL(k_mirror, dim3((unsigned)L.n_diag_tiles), dim3(256), 0, s, c->d_cl, c->d_tiles, c->G);
   hipLaunchKernelGGL(k_logdet, dim3(L.nc), dim3(256), 0, s, c->d_cl, c->G, c->d_logdet);
