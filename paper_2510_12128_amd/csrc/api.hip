@@ -362,7 +362,7 @@ int nugpr_destroy(nugpr_ctx* c) {
 
 int nugpr_build_blocks(nugpr_ctx* c, const double* theta, void* stream) {
   if (!c) { set_error("ctx is null"); return NUGPR_ERR_INVALID; }
-  return launch_build(c, theta, as_stream(stream));
+  return launch_build(c, theta, as_stream(stream), !kd_lower_suffices(c));
 }
 
 int nugpr_precond_factor(nugpr_ctx* c, double* logdet_M, int32_t* bad_cluster, void* stream) {
@@ -463,7 +463,7 @@ static int set_operator(nugpr_ctx* c, const double* theta, bool allow_reuse, hip
   bool same = allow_reuse && c->built && (int)c->theta_built.size() == L.p &&
               !(c->params.flags & NUGPR_NO_SHORTCUTS);
   for (int k = 0; same && k < nl; ++k) same = (theta[k] == c->theta_built[k]);
-  if (!same) return launch_build(c, theta, s);
+  if (!same) return launch_build(c, theta, s, !kd_lower_suffices(c));
   for (int i = 0; i < L.p; ++i)
     if (!(theta[i] > 0.0) || !std::isfinite(theta[i])) { set_error("theta entries must be finite and > 0"); return NUGPR_ERR_INVALID; }
   const double a0 = c->theta_built[L.p - 2], s0 = c->theta_built[L.p - 1];

@@ -84,6 +84,7 @@ struct PanelArgs {
   double coef[EXP2_TERMS];   // alpha times the coefficients of 2^f
   float diag_val;       // diagonal entries: float(alpha + sigma^2); coupling under compensation: float(alpha - lambda_0)
   int keep_same;        // coupling: keep the entries between representatives of one cluster (compensation)
+  int mirror;           // diagonal blocks: also store the mirror image of the tiles below the diagonal
   int32_t kd;           // coordinates per point in the scaled array (multiple of 4)
 };
 
@@ -262,7 +263,8 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
         }
         st_w[i * ST_LD] = x[i];
       }
-      *reinterpret_cast<float4*>(om + (ti >> 1) * (TILE * BLK_COLS) + (ti & 1) * FRAG + om_lane) = make_float4(x[0], x[1], x[2], x[3]);
+      if (COUPLING || a.mirror || tr == tc)
+        *reinterpret_cast<float4*>(om + (ti >> 1) * (TILE * BLK_COLS) + (ti & 1) * FRAG + om_lane) = make_float4(x[0], x[1], x[2], x[3]);
       // The staging rows are wave-private and the LDS serves one wave's accesses in order: the read below
       // sees this group's writes, and the next group's writes come after it.
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -437,7 +439,7 @@ int launch_setup(nugpr_ctx* c, const float* user_reps, const float* user_W, hipS
   return NUGPR_OK;
 }
 
-int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s) {
+int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s, bool need_upper) {
   const Layout& L = c->L;
   if (!theta) { set_error("theta is null"); return NUGPR_ERR_INVALID; }
   for (int i = 0; i < L.p; ++i)
@@ -455,6 +457,7 @@ int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s) {
   PanelArgs a;
   for (int k = 0; k < EXP2_TERMS; ++k) a.coef[k] = alpha * EXP2_COEF[k];
   a.diag_val = (float)(alpha + sigma2);
+  a.mirror = need_upper ? 1 : 0;
   a.kd = pair_kd(L.d);
   a.keep_same = 0;
   c->diag_residual = (float)((alpha + sigma2) - (double)a.diag_val);
@@ -510,6 +513,7 @@ int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s) {
   c->op_scale = 1.0;
   c->op_shift = (double)c->diag_residual;
   c->built = true;
+  c->kd_upper_valid = need_upper;
   c->build_gen += 1;
   return NUGPR_OK;
 }
@@ -526,6 +530,10 @@ int launch_export(nugpr_ctx* c, int what, int index, float* dst, int64_t ld, hip
     src = (what == 0 ? c->Kd : what == 1 ? c->Lf : c->G) + ci.koff;
     lds = ci.ld; rows = cols = (int)ci.b; lower = what != 0;
     if ((what == 0 && !c->built) || (what != 0 && !c->factored)) { set_error("nothing stored yet"); return NUGPR_ERR_STATE; }
+    if (what == 0) {
+      const int rc = ensure_kd_upper(c, s);
+      if (rc) return rc;
+    }
   } else if (what == 3) {
     if (!c->built) { set_error("nothing stored yet"); return NUGPR_ERR_STATE; }
     src = c->C; lds = L.ldc; rows = cols = L.ncr;

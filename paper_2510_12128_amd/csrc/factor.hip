@@ -376,6 +376,20 @@ __global__ __launch_bounds__(256) void k_mirror(const ClusterInfo* __restrict__ 
   }
 }
 
+bool kd_lower_suffices(const nugpr_ctx* c) {
+  // fp64 mode with 2..17 columns (one column group): the producer / consumer strip kernel pairs the tiles of
+  // the symmetric blocks.  The Pade route also solves single columns, which read whole strips.
+  return c->acc64 && c->L.T >= 2 && c->L.T <= 17 && !(c->params.flags & NUGPR_LOGDET_PADE);
+}
+
+int ensure_kd_upper(nugpr_ctx* c, hipStream_t s) {
+  if (c->kd_upper_valid || !c->built) return NUGPR_OK;
+  hipLaunchKernelGGL(k_mirror, dim3((unsigned)c->L.n_diag_tiles), dim3(256), 0, s, c->d_cl, c->d_tiles, c->Kd);
+  NUGPR_HIP(hipGetLastError());
+  c->kd_upper_valid = true;
+  return NUGPR_OK;
+}
+
 // log det of the preconditioner of one cluster from the stored inverse diagonal
 __global__ __launch_bounds__(256) void k_logdet(const ClusterInfo* __restrict__ cl, const float* __restrict__ G,
                                                 double* __restrict__ out) {

@@ -226,6 +226,9 @@ struct nugpr_ctx {
   // The stored blocks are the very ones the factor was computed from while build_gen == factor_gen:
   // then Y K_diag Y^T = I for the stored K_diag and Y = L^-1 (eq. (linear1)).
   uint64_t build_gen = 0, factor_gen = ~0ull;
+  // The assembly may leave out the strictly upper tiles of the K_ii (the product's usual launch reads the
+  // lower ones only, see k_strip_ring); whoever needs whole strips calls ensure_kd_upper first.
+  bool kd_upper_valid = false;
   bool general_route = false;   // take the streamed-K_diag route even where the identity relation holds
   // SPD compensation (eq. (krep)): host copy of the representatives and lambda_0 of the last assembly.
   // Clo holds what fp32 storage of C - lambda_0 I drops: C_exact - lambda_0 I - C_stored, itself in fp32,
@@ -254,7 +257,12 @@ int plan_layout(const nugpr_problem* pb, uint32_t flags, Layout& L);
 
 // build_blocks.hip ----------------------------------------------------------
 int launch_setup(nugpr_ctx* c, const float* user_reps, const float* user_W, hipStream_t s);
-int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s);
+// need_upper = false: the strictly upper tiles of the K_ii are not written (kd_upper_valid records it)
+int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s, bool need_upper = true);
+// true when every product this context launches on its own vector blocks reads lower tiles only
+bool kd_lower_suffices(const nugpr_ctx* c);
+// fills the strictly upper tiles of the K_ii from the lower ones if the last assembly left them out
+int ensure_kd_upper(nugpr_ctx* c, hipStream_t s);
 int launch_export(nugpr_ctx* c, int what, int index, float* dst, int64_t ld, hipStream_t s);
 
 // strip_gemm.hip ------------------------------------------------------------

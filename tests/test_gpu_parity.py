@@ -99,6 +99,32 @@ def test_matvec_matches_oracle(lib, case):
     ctx.close()
 
 
+def test_upper_tiles_are_filled_in_when_a_product_needs_them(lib):
+    """An assembly for a context whose products read the lower tiles of the K_ii leaves the upper tiles
+    out; products of other widths (whole strips) and the export must still see the full blocks, after
+    every assembly."""
+    w = CASES["ragged-halves"]()
+    print("case", w.name, flush=True)
+    ctx = make_ctx(lib, w)
+    prob = oracle_problem(w)
+    rng = np.random.default_rng(12)
+    for scale in (1.0, 1.3):
+        theta = w.theta.copy()
+        theta[:-2] *= scale
+        ctx.nugpr_build_blocks(theta)
+        op = prob.operator(theta)
+        for ncols in (w.n_probes + 1, 1, 2):              # paired tiles, whole strips, paired tiles again
+            D = rng.standard_normal((w.n, ncols)).astype(np.float32)
+            Q = ctx.nugpr_matvec(D).cpu().numpy().astype(np.float64)
+            assert relmax(Q, op(D.astype(np.float64))) < 1e-5, (scale, ncols)
+        blocks, _ = prob.assemble(theta)
+        for i in range(w.n_clusters):
+            Ki = ctx.nugpr_export(B.EXPORT_K, i).cpu().numpy().astype(np.float64)
+            np.testing.assert_allclose(Ki, blocks[i], rtol=2e-6, atol=1e-7)
+            assert np.array_equal(Ki, Ki.T)
+    ctx.close()
+
+
 @pytest.mark.parametrize("case", ["ragged-t8", "ragged-t32", "tiny", "iso-d1", "C1-wide"])
 def test_precond_factor_and_apply_match_oracle(lib, case):
     w = CASES[case]()
