@@ -205,6 +205,8 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   c->Lf = reinterpret_cast<float*>(w + L.o_Lf);
   c->G = reinterpret_cast<float*>(w + L.o_G);
   c->C = reinterpret_cast<float*>(w + L.o_C);
+  c->Kd2 = reinterpret_cast<float*>(w + L.o_Kd2);
+  c->C2 = reinterpret_cast<float*>(w + L.o_C2);
   c->Clo = L.compensate ? reinterpret_cast<float*>(w + L.o_Clo) : nullptr;
   c->Wd = reinterpret_cast<float*>(w + L.o_Wd);
   c->Wt = reinterpret_cast<float*>(w + L.o_Wt);
@@ -615,14 +617,24 @@ int nugpr_train_step(nugpr_ctx* c, double* log_theta, double* adam_m, double* ad
     c->fd_halvings[i] = halv;
     grad[i] = t0 * g;
   }
+  // The two assemblies of a lengthscale difference are made in one pass (they share the distance
+  // computation); NUGPR_NO_SHORTCUTS and the compensated operator keep one assembly per evaluation.
+  const bool pairs = !(c->params.flags & NUGPR_NO_SHORTCUTS) && !c->L.compensate;
   for (int k = 0; !forward && k < p; ++k) {
     const int i = k < 2 ? p - 2 + k : k - 2;          // alpha, sigma^2, then the lengthscales
     nugpr_mll_result rp, rm;
-    theta[i] = std::exp(log_theta[i] + h);
+    const double tp = std::exp(log_theta[i] + h), tm = std::exp(log_theta[i] - h);
+    const bool pair = pairs && i < p - 2;
+    if (pair) {
+      rc = launch_build_pair(c, theta.data(), i, h, tp, tm, as_stream(stream), !kd_lower_suffices(c));
+      if (rc) return rc;
+    }
+    theta[i] = tp;
     rc = mll_impl(c, theta.data(), &rp, true, stream);
     if (rc < 0 || rc == NUGPR_INDEFINITE) return rc;
     worst = std::max(worst, rc);
-    theta[i] = std::exp(log_theta[i] - h);
+    if (pair && (rc = swap_pair(c))) return rc;
+    theta[i] = tm;
     rc = mll_impl(c, theta.data(), &rm, true, stream);
     if (rc < 0 || rc == NUGPR_INDEFINITE) return rc;
     worst = std::max(worst, rc);

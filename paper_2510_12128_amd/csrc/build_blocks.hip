@@ -85,6 +85,11 @@ struct PanelArgs {
   float diag_val;       // diagonal entries: float(alpha + sigma^2); coupling under compensation: float(alpha - lambda_0)
   int keep_same;        // coupling: keep the entries between representatives of one cluster (compensation)
   int mirror;           // diagonal blocks: also store the mirror image of the tiles below the diagonal
+  // two matrices from one pass (PAIR instantiations): the exponent of side s is e + g[s] * w, where e is the
+  // exponent at the lengthscales the points were scaled with and w is the squared difference of the scaled
+  // coordinate pair_dim, or e itself when pair_dim < 0 (one lengthscale for all coordinates)
+  double g[2];
+  int pair_dim;
   int32_t kd;           // coordinates per point in the scaled array (multiple of 4)
 };
 
@@ -137,10 +142,15 @@ __device__ __forceinline__ void kernel_values(const double (&arg)[W], const doub
 // operands they share stay in L2.  The exponential uses full-rate instructions only, and the masks
 // run on the tiles that need them.
 // NKS = kd / 4 when positive; NKS = 0 handles any kd with a loop over the coordinate groups.
-template <bool COUPLING, int NKS>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(COUPLING ? 6 : 7, 7)))
+//
+// PAIR: the two matrices of a central difference in one lengthscale, ell_k e^{+h} and ell_k e^{-h}, from one
+// pass.  Their exponents differ from the one at ell_k by a multiple of the squared difference in coordinate
+// k alone, so the matrix instructions (40 % of the pass) and the operand traffic are shared; only the
+// exponential and the stores are done twice.  Side 0 goes to out_base, side 1 to out_base2, same layout.
+template <bool COUPLING, int NKS, bool PAIR>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PAIR ? 5 : 6, 7)))
 void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const double* __restrict__ S,
-                  const double* __restrict__ N, float* __restrict__ out_base, int r) {
+                  const double* __restrict__ N, float* __restrict__ out_base, int r, float* __restrict__ out_base2) {
   extern __shared__ __attribute__((aligned(16))) double sA[];      // 4 * kd * 16 doubles: row operands
   __shared__ __attribute__((aligned(32))) double sNr[TILE];
   __shared__ __attribute__((aligned(16))) float sT[4][16 * ST_LD];      // per wave: one 16-row group in transit
@@ -171,6 +181,8 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
     for (int ks = 0; ks < NKS; ++ks) bv[ks] = Sc[ks * 64];
   }
   const double nc = (N + qg)[(uint32_t)m];
+  double vc = 0.0;                                             // coordinate pair_dim of this lane's column point
+  if (PAIR && a.pair_dim >= 0) vc = (S + (uint64_t)(qg >> 4) * gstride)[(uint32_t)(a.pair_dim * 16 + m)];
   {
     constexpr int NCA = NKS > 0 ? NKS : MAX_D / 4;              // row operand elements per thread (4 kd 16 / 256)
     const double* __restrict__ Sg = S + (uint64_t)((prow + p0) >> 4) * gstride;
@@ -234,46 +246,66 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
                            (2 * wave) * FRAG;
   const uint32_t om_lane = (uint32_t)(m * 16 + 4 * kk);
 
+  // second matrix of a pair: same offsets from the other base
+  const int64_t side_off = PAIR ? (int64_t)(out_base2 - out_base) : 0;
   // the sixteen entries of this lane, one 16-row group at a time: masked (EDGE) or not
   auto entries = [&](auto edge_c) {
     constexpr bool EDGE = decltype(edge_c)::value;
 #pragma unroll
     for (int ti = 0; ti < 4; ++ti) {
-      float x[4];
-      double arg[4];
+      double w[4] = {0.0, 0.0, 0.0, 0.0};
+      if (PAIR) {
+        if (a.pair_dim >= 0) {
+          // the row points 4 kk .. 4 kk + 3 of this group, coordinate pair_dim (staged doubled)
+          const double2* __restrict__ ur = reinterpret_cast<const double2*>(&sA[(ti * kd + a.pair_dim) * 16 + 4 * kk]);
+          const double2 u01 = ur[0], u23 = ur[1];
+          const double d0 = fma(0.5, u01.x, -vc), d1 = fma(0.5, u01.y, -vc), d2 = fma(0.5, u23.x, -vc),
+                       d3 = fma(0.5, u23.y, -vc);
+          w[0] = d0 * d0; w[1] = d1 * d1; w[2] = d2 * d2; w[3] = d3 * d3;
+        } else {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) arg[i] = acc[ti][i];
-      kernel_values<4>(arg, a.coef, x);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = 16 * ti + 4 * kk + i;
-        if (EDGE) {
-          const int p = p0 + row;
-          bool keep = p < total && q < total;
-          if (COUPLING) {
-            // only blocks between DIFFERENT clusters enter K' (eq. (odsplit)): same-cluster entries are 0
-            // (all of C, with alpha - lambda_0 on its diagonal, under the compensation of eq. (krep))
-            keep = keep && (a.keep_same || (p / r) != (q / r));
-            x[i] = keep ? x[i] : 0.f;
-            if (a.keep_same && p == q && p < total) x[i] = dv;
-          } else {
-            x[i] = keep ? x[i] : 0.f;
-            if (p == q && p < total) x[i] = dv;
-          }
+          for (int i = 0; i < 4; ++i) w[i] = acc[ti][i];
         }
-        st_w[i * ST_LD] = x[i];
       }
-      if (COUPLING || a.mirror || tr == tc)
-        *reinterpret_cast<float4*>(om + (ti >> 1) * (TILE * BLK_COLS) + (ti & 1) * FRAG + om_lane) = make_float4(x[0], x[1], x[2], x[3]);
-      // The staging rows are wave-private and the LDS serves one wave's accesses in order: the read below
-      // sees this group's writes, and the next group's writes come after it.
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      const float4 rowv = *st_r;
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      *reinterpret_cast<float4*>(od + (2 * ti) * FRAG + od_lane) = rowv;
+#pragma unroll
+      for (int side = 0; side < (PAIR ? 2 : 1); ++side) {
+        float x[4];
+        double arg[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) arg[i] = PAIR ? fma(a.g[side], w[i], acc[ti][i]) : acc[ti][i];
+        kernel_values<4>(arg, a.coef, x);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int row = 16 * ti + 4 * kk + i;
+          if (EDGE) {
+            const int p = p0 + row;
+            bool keep = p < total && q < total;
+            if (COUPLING) {
+              // only blocks between DIFFERENT clusters enter K' (eq. (odsplit)): same-cluster entries are 0
+              // (all of C, with alpha - lambda_0 on its diagonal, under the compensation of eq. (krep))
+              keep = keep && (a.keep_same || (p / r) != (q / r));
+              x[i] = keep ? x[i] : 0.f;
+              if (a.keep_same && p == q && p < total) x[i] = dv;
+            } else {
+              x[i] = keep ? x[i] : 0.f;
+              if (p == q && p < total) x[i] = dv;
+            }
+          }
+          st_w[i * ST_LD] = x[i];
+        }
+        if (COUPLING || a.mirror || tr == tc)
+          *reinterpret_cast<float4*>(om + side * side_off + (ti >> 1) * (TILE * BLK_COLS) + (ti & 1) * FRAG + om_lane) =
+              make_float4(x[0], x[1], x[2], x[3]);
+        // The staging rows are wave-private and the LDS serves one wave's accesses in order: the read below
+        // sees this group's writes, and the next group's writes come after it.
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const float4 rowv = *st_r;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        *reinterpret_cast<float4*>(od + side * side_off + (2 * ti) * FRAG + od_lane) = rowv;
+      }
     }
   };
   // tiles that can hold dropped or replaced entries: on the diagonal, at the ragged end, or (coupling)
@@ -439,7 +471,11 @@ int launch_setup(nugpr_ctx* c, const float* user_reps, const float* user_W, hipS
   return NUGPR_OK;
 }
 
-int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s, bool need_upper) {
+// pair_param < 0: one assembly at theta.  Otherwise theta holds the centre of a central difference in
+// lengthscale pair_param with step h on its logarithm: ell e^{+h} goes to the blocks in force (Kd, C),
+// ell e^{-h} to the spare ones (Kd2, C2); theta_built / theta_spare record which is which.
+static int build_impl(nugpr_ctx* c, const double* theta, hipStream_t s, bool need_upper, int pair_param, double h,
+                      double value_plus, double value_minus) {
   const Layout& L = c->L;
   if (!theta) { set_error("theta is null"); return NUGPR_ERR_INVALID; }
   for (int i = 0; i < L.p; ++i)
@@ -460,6 +496,16 @@ int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s, bool need_upp
   a.mirror = need_upper ? 1 : 0;
   a.kd = pair_kd(L.d);
   a.keep_same = 0;
+  a.g[0] = a.g[1] = 0.0;
+  a.pair_dim = -1;
+  const bool pair = pair_param >= 0;
+  if (pair) {
+    if (L.compensate || pair_param >= L.p - 2) { set_error("pair assembly: not a lengthscale, or compensation is on"); return NUGPR_ERR_INVALID; }
+    // squared scaled distances go with ell^-2: factors e^{-2h} and e^{+2h}
+    const double gp = std::expm1(-2.0 * h), gm = std::expm1(2.0 * h);
+    if (iso) { a.g[0] = gp; a.g[1] = gm; a.pair_dim = -1; }             // exponent e (1 + g)
+    else { a.g[0] = -gp; a.g[1] = -gm; a.pair_dim = pair_param; }       // exponent e - g (u_k - v_k)^2, e = -|u - v|^2
+  }
   c->diag_residual = (float)((alpha + sigma2) - (double)a.diag_val);
   PanelArgs ac = a;                                  // the coupling launch
   if (L.compensate) {
@@ -490,8 +536,13 @@ int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s, bool need_upp
   const size_t lds = (size_t)4 * a.kd * 16 * sizeof(double);      // row operands of one tile
 #define NUGPR_TILES(NKS)                                                                                         \
   do {                                                                                                           \
-    hipLaunchKernelGGL((k_build_tile<true, NKS>), gc, blk, lds, s, ac, c->d_pan_c, c->Rs, c->Rn, c->C, L.r);     \
-    hipLaunchKernelGGL((k_build_tile<false, NKS>), gd, blk, lds, s, a, c->d_pan_diag, c->Xs, c->Xn, c->Kd, 1);   \
+    if (pair) {                                                                                                  \
+      hipLaunchKernelGGL((k_build_tile<true, NKS, true>), gc, blk, lds, s, ac, c->d_pan_c, c->Rs, c->Rn, c->C, L.r, c->C2);      \
+      hipLaunchKernelGGL((k_build_tile<false, NKS, true>), gd, blk, lds, s, a, c->d_pan_diag, c->Xs, c->Xn, c->Kd, 1, c->Kd2);   \
+    } else {                                                                                                     \
+      hipLaunchKernelGGL((k_build_tile<true, NKS, false>), gc, blk, lds, s, ac, c->d_pan_c, c->Rs, c->Rn, c->C, L.r, (float*)nullptr);    \
+      hipLaunchKernelGGL((k_build_tile<false, NKS, false>), gd, blk, lds, s, a, c->d_pan_diag, c->Xs, c->Xn, c->Kd, 1, (float*)nullptr); \
+    }                                                                                                            \
   } while (0)
   switch (a.kd / 4) {        // the dimensions of the usual workloads get their own instantiation
     case 1: NUGPR_TILES(1); break;
@@ -510,10 +561,37 @@ int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s, bool need_upp
     NUGPR_HIP(hipGetLastError());
   }
   c->theta_built.assign(theta, theta + L.p);
+  c->theta_spare.clear();
+  if (pair) {
+    c->theta_spare = c->theta_built;
+    c->theta_built[pair_param] = value_plus;      // the caller's own values of ell e^{+h} and ell e^{-h}
+    c->theta_spare[pair_param] = value_minus;
+  }
+  c->spare_upper_valid = pair && need_upper;
   c->op_scale = 1.0;
   c->op_shift = (double)c->diag_residual;
   c->built = true;
   c->kd_upper_valid = need_upper;
+  c->build_gen += 1;
+  return NUGPR_OK;
+}
+
+int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s, bool need_upper) {
+  return build_impl(c, theta, s, need_upper, -1, 0.0, 0.0, 0.0);
+}
+
+int launch_build_pair(nugpr_ctx* c, const double* theta, int param, double h, double value_plus, double value_minus,
+                      hipStream_t s, bool need_upper) {
+  return build_impl(c, theta, s, need_upper, param, h, value_plus, value_minus);
+}
+
+int swap_pair(nugpr_ctx* c) {
+  if (c->theta_spare.empty()) { set_error("no spare blocks to switch to"); return NUGPR_ERR_STATE; }
+  std::swap(c->Kd, c->Kd2);
+  std::swap(c->C, c->C2);
+  c->theta_built.swap(c->theta_spare);
+  c->theta_spare.clear();               // the blocks left behind are not used again
+  c->kd_upper_valid = c->spare_upper_valid;
   c->build_gen += 1;
   return NUGPR_OK;
 }

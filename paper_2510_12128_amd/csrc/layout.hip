@@ -95,6 +95,8 @@ int plan_layout(const nugpr_problem* pb, uint32_t flags, Layout& L) {
   L.o_Lf = take(cur, L.kd_elems * f);
   L.o_G = take(cur, L.kd_elems * f);
   L.o_C = take(cur, (size_t)L.ldc * L.ldc * f);
+  L.o_Kd2 = take(cur, L.kd_elems * f);
+  L.o_C2 = take(cur, (size_t)L.ldc * L.ldc * f);
   L.o_Wd = take(cur, (size_t)L.n * L.ldw * f);
   L.o_Wt = take(cur, L.wt_elems * f);
   L.o_reps = take(cur, (size_t)L.ncr * L.d * f);

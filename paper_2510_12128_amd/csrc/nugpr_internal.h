@@ -155,6 +155,7 @@ struct Layout {
   uint64_t rows_pad = 0;      // sum of ld over the clusters
   // byte offsets into the workspace
   size_t o_cl = 0, o_Kd = 0, o_Lf = 0, o_G = 0, o_C = 0, o_Wd = 0, o_Wt = 0, o_reps = 0;
+  size_t o_Kd2 = 0, o_C2 = 0;        // spare K_diag and C: second matrix of a pair assembly
   size_t o_B = 0, o_X = 0, o_R = 0, o_Z = 0, o_D = 0, o_Q = 0, o_V = 0, o_U = 0;
   size_t o_Spart = 0, o_Ppart = 0, o_dot = 0, o_state = 0, o_alog = 0, o_blog = 0;
   size_t o_theta = 0, o_logdet = 0, o_tiles = 0, o_items = 0;
@@ -180,6 +181,7 @@ struct nugpr_ctx {
   // device views into the workspace
   nugpr::ClusterInfo* d_cl = nullptr;
   float *Kd = nullptr, *Lf = nullptr, *G = nullptr, *C = nullptr, *Wd = nullptr, *Wt = nullptr, *reps = nullptr;
+  float *Kd2 = nullptr, *C2 = nullptr;     // spare blocks (launch_build_pair / swap_pair)
   // lengthscale-scaled coordinates in fp64, in MFMA operand order, and their squared norms:
   // of the points (padded row numbering) and of the representatives
   double *Xs = nullptr, *Xn = nullptr, *Rs = nullptr, *Rn = nullptr;
@@ -221,6 +223,7 @@ struct nugpr_ctx {
   //   op_scale * K_0 + op_shift * I  (shift on the diagonal blocks only; the coupling is scaled),
   // which is the covariance at any theta with the same lengthscales (eqs. (linear2), (linear3)).
   std::vector<double> theta_built;
+  std::vector<double> theta_spare;     // theta of the spare blocks after a pair assembly (empty: none)
   double op_scale = 1.0, op_shift = 0.0;
   bool built = false, factored = false;
   // The stored blocks are the very ones the factor was computed from while build_gen == factor_gen:
@@ -228,7 +231,7 @@ struct nugpr_ctx {
   uint64_t build_gen = 0, factor_gen = ~0ull;
   // The assembly may leave out the strictly upper tiles of the K_ii (the product's usual launch reads the
   // lower ones only, see k_strip_ring); whoever needs whole strips calls ensure_kd_upper first.
-  bool kd_upper_valid = false;
+  bool kd_upper_valid = false, spare_upper_valid = false;
   bool general_route = false;   // take the streamed-K_diag route even where the identity relation holds
   // SPD compensation (eq. (krep)): host copy of the representatives and lambda_0 of the last assembly.
   // Clo holds what fp32 storage of C - lambda_0 I drops: C_exact - lambda_0 I - C_stored, itself in fp32,
@@ -259,6 +262,11 @@ int plan_layout(const nugpr_problem* pb, uint32_t flags, Layout& L);
 int launch_setup(nugpr_ctx* c, const float* user_reps, const float* user_W, hipStream_t s);
 // need_upper = false: the strictly upper tiles of the K_ii are not written (kd_upper_valid records it)
 int launch_build(nugpr_ctx* c, const double* theta, hipStream_t s, bool need_upper = true);
+// The two assemblies of a central difference in lengthscale `param` (step h on its logarithm) in one pass:
+// ell e^{+h} into the blocks in force, ell e^{-h} into the spare ones; swap_pair puts the spare ones in force.
+int launch_build_pair(nugpr_ctx* c, const double* theta, int param, double h, double value_plus, double value_minus,
+                      hipStream_t s, bool need_upper);
+int swap_pair(nugpr_ctx* c);
 // true when every product this context launches on its own vector blocks reads lower tiles only
 bool kd_lower_suffices(const nugpr_ctx* c);
 // fills the strictly upper tiles of the K_ii from the lower ones if the last assembly left them out
