@@ -74,14 +74,51 @@ void arrange_for_dies(std::vector<StripItem>& v) {
   v.swap(out);
 }
 
+// The same for whole groups of items that must run together (the strips of one cluster; the two sets of
+// strips that share the tiles of a pair of super-blocks of the coupling matrix): the groups go to the dies
+// in turn, in the order given, each die works through its groups in order, and a die whose queue has run
+// dry takes from the fullest one.
+uint64_t group_work(const std::vector<StripItem>& g) {
+  uint64_t w = 0;
+  for (const StripItem& it : g) w += it.c_end > it.c_begin ? it.c_end - it.c_begin : 0;
+  return w;
+}
+void heaviest_first(std::vector<std::vector<StripItem>>& groups, size_t from) {
+  std::stable_sort(groups.begin() + from, groups.end(),
+                   [](const std::vector<StripItem>& a, const std::vector<StripItem>& b) { return group_work(a) > group_work(b); });
+}
+std::vector<StripItem> deal_groups(std::vector<std::vector<StripItem>>& groups) {
+  std::vector<std::vector<StripItem>> q(NUM_XCD);
+  size_t total = 0;
+  for (size_t g = 0; g < groups.size(); ++g) {
+    q[g % NUM_XCD].insert(q[g % NUM_XCD].end(), groups[g].begin(), groups[g].end());
+    total += groups[g].size();
+  }
+  std::vector<size_t> pos(NUM_XCD, 0);
+  std::vector<StripItem> out;
+  out.reserve(total);
+  while (out.size() < total) {
+    int src = (int)(out.size() % NUM_XCD);
+    if (pos[src] >= q[src].size()) {
+      size_t best = 0;
+      for (int k = 0; k < NUM_XCD; ++k)
+        if (q[k].size() - pos[k] > best) { best = q[k].size() - pos[k]; src = k; }
+    }
+    out.push_back(q[src][pos[src]++]);
+  }
+  return out;
+}
+
 struct Tables {
   std::vector<StripItem> WtD, KC, Conly, WP, lowG, upG, lowL;
 };
 
 void build_tables(const Layout& L, Tables& t) {
   const uint32_t r = (uint32_t)L.r;
+  std::vector<std::vector<StripItem>> kc_groups;      // work of the K_diag + C launch, by group (deal_groups)
   for (int i = 0; i < L.nc; ++i) {
     const ClusterInfo& c = L.cl[i];
+    kc_groups.emplace_back();
     // S_i = W_i^T D_i: strips over the r rows of W_i^T, columns split into nsS slabs
     const uint32_t chunks = c.nt, cpp = (chunks + L.nsS - 1) / L.nsS;
     for (uint32_t rs = 0; rs * TILE < r; ++rs) {
@@ -97,8 +134,8 @@ void build_tables(const Layout& L, Tables& t) {
       const uint32_t nrows = std::min<uint32_t>(TILE, c.b - s * TILE);
       const uint64_t a_off = c.koff + (uint64_t)s * TILE * c.ld;
       const uint32_t row = c.row0 + s * TILE;
-      t.KC.push_back(make_item(a_off, c.ld, nrows, 0, c.b, c.row0, row, s * TILE, 0, 0, 0, 1.f));
-      t.KC.back().blocked = c.nt >= 2 ? 3 : 1;      // K_ii is symmetric: its strips pair up tile by tile
+      kc_groups.back().push_back(make_item(a_off, c.ld, nrows, 0, c.b, c.row0, row, s * TILE, 0, 0, 0, 1.f));
+      kc_groups.back().back().blocked = c.nt >= 2 ? 3 : 1;      // K_ii is symmetric: its strips pair up tile by tile
       t.WP.push_back(make_item((uint64_t)row * L.ldw, (uint32_t)L.ldw, nrows, 0, r, (uint32_t)i * r, row, 0, 0, 0, 0, 0.f));
       t.lowG.push_back(make_item(a_off, c.ld, nrows, 0, s * TILE + nrows, c.row0, row, s * TILE, 0, 0, 1, 0.f));
       t.upG.push_back(make_item(a_off, c.ld, nrows, s * TILE, c.b, c.row0, row, s * TILE, 0, 0, 2, 0.f));
@@ -106,26 +143,52 @@ void build_tables(const Layout& L, Tables& t) {
       t.lowG.back().blocked = t.upG.back().blocked = t.lowL.back().blocked = 1;     // L and L^-1 are stored blocked too
     }
   }
-  // P = C S: strips over the n_c r rows of C, columns split into nsP slabs
+  // the clusters first, heaviest first (the assembly writes cluster 0 last, so with equal clusters the product
+  // starts on blocks that are still in the memory-side cache), then the groups of the coupling matrix
+  heaviest_first(kc_groups, 0);
+  const size_t first_c_group = kc_groups.size();
+  // P = C S: strips over the n_c r rows of C, columns split into nsP slabs of cpp tiles.  C is symmetric:
+  // with the strips grouped like the slabs, the strips of row group I on slab k and the strips of row group
+  // k on slab I share their tiles (one set reads them transposed) and form one group of work; see
+  // k_strip_ring for the order in which they visit them.
   {
     const uint32_t ncr = (uint32_t)L.ncr, chunks = (uint32_t)L.ldc / TILE, cpp = (chunks + L.nsP - 1) / L.nsP;
-    for (uint32_t rs = 0; rs * TILE < ncr; ++rs) {
+    const uint32_t ngroups = (chunks + cpp - 1) / cpp;              // non-empty slabs = row groups
+    const bool pairing = chunks >= 2 && cpp <= 1023;
+    auto c_item = [&](uint32_t rs, int k) {
       const uint32_t nrows = std::min<uint32_t>(TILE, ncr - rs * TILE);
-      for (int k = 0; k < L.nsP; ++k) {
-        const uint32_t cb = std::min<uint32_t>(k * cpp, chunks) * TILE;
-        const uint32_t ce = std::min<uint32_t>(std::min<uint32_t>((k + 1) * cpp, chunks) * TILE, ncr);
-        t.KC.push_back(make_item((uint64_t)rs * TILE * L.ldc, (uint32_t)L.ldc, nrows, cb, std::max(cb, ce), 0,
-                                 rs * TILE, 0, k, 1, 0, 0.f));
-        t.KC.back().blocked = 1;
+      const uint32_t cb = std::min<uint32_t>(k * cpp, chunks) * TILE;
+      const uint32_t ce = std::min<uint32_t>(std::min<uint32_t>((k + 1) * cpp, chunks) * TILE, ncr);
+      StripItem it = make_item((uint64_t)rs * TILE * L.ldc, (uint32_t)L.ldc, nrows, cb, std::max(cb, ce), 0, rs * TILE,
+                               rs * TILE, k, 1, 0, 0.f);
+      it.blocked = 1;
+      if (pairing && (uint32_t)k < ngroups) {
+        const uint32_t I = rs / cpp, na = std::min<uint32_t>(cpp, chunks - I * cpp), jr = rs - I * cpp;
+        const uint32_t kind = I == (uint32_t)k ? 0u : (I > (uint32_t)k ? 1u : 2u);
+        it.blocked = 3u | (kind << 2) | (na << 4) | (jr << 15);
       }
-    }
+      return it;
+    };
+    for (uint32_t I = 0; I < ngroups; ++I)
+      for (uint32_t k = I; k < ngroups; ++k) {
+        kc_groups.emplace_back();
+        for (uint32_t rs = I * cpp; rs < std::min<uint32_t>((I + 1) * cpp, chunks) && rs * TILE < ncr; ++rs)
+          kc_groups.back().push_back(c_item(rs, (int)k));
+        if (k != I)
+          for (uint32_t rs = k * cpp; rs < std::min<uint32_t>((k + 1) * cpp, chunks) && rs * TILE < ncr; ++rs)
+            kc_groups.back().push_back(c_item(rs, (int)I));
+      }
+    // slabs past the last tile are empty; their items only clear their slab of the partial sums
+    kc_groups.emplace_back();
+    for (int k = (int)ngroups; k < L.nsP; ++k)
+      for (uint32_t rs = 0; rs * TILE < ncr; ++rs) kc_groups.back().push_back(c_item(rs, k));
   }
+  heaviest_first(kc_groups, first_c_group);
+  t.KC = deal_groups(kc_groups);
   sort_longest_first(t.WtD);
-  sort_longest_first(t.KC);
   sort_longest_first(t.lowG);
   sort_longest_first(t.upG);
   sort_longest_first(t.lowL);
-  arrange_for_dies(t.KC);
   for (const StripItem& it : t.KC)
     if (it.port == 1) t.Conly.push_back(it);       // the coupling product on its own (eq. (linear1) route)
   arrange_for_dies(t.lowG);
@@ -260,6 +323,8 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   StripItem* cur = reinterpret_cast<StripItem*>(w + L.o_items);
   if ((rc = upload_table(t.WtD, cur, c->tab_WtD, s))) return fail(rc);
   if ((rc = upload_table(t.KC, cur, c->tab_KC, s))) return fail(rc);
+  c->c_paired = false;
+  for (const StripItem& it : t.KC) c->c_paired = c->c_paired || (it.port == 1 && (it.blocked & 2u) != 0);
   if ((rc = upload_table(t.Conly, cur, c->tab_C, s))) return fail(rc);
   if ((rc = upload_table(t.WP, cur, c->tab_WP, s))) return fail(rc);
   if ((rc = upload_table(t.lowG, cur, c->tab_lowG, s))) return fail(rc);

@@ -84,7 +84,7 @@ struct PanelArgs {
   double coef[EXP2_TERMS];   // alpha times the coefficients of 2^f
   float diag_val;       // diagonal entries: float(alpha + sigma^2); coupling under compensation: float(alpha - lambda_0)
   int keep_same;        // coupling: keep the entries between representatives of one cluster (compensation)
-  int mirror;           // diagonal blocks: also store the mirror image of the tiles below the diagonal
+  int mirror;           // also store the mirror image of the tiles below the diagonal
   // two matrices from one pass (PAIR instantiations): the exponent of side s is e + g[s] * w, where e is the
   // exponent at the lengthscales the points were scaled with and w is the squared difference of the scaled
   // coordinate pair_dim, or e itself when pair_dim < 0 (one lengthscale for all coordinates)
@@ -293,7 +293,7 @@ void k_build_tile(const PanelArgs a, const BuildItem* __restrict__ items, const 
           }
           st_w[i * ST_LD] = x[i];
         }
-        if (COUPLING || a.mirror || tr == tc)
+        if (a.mirror || tr == tc)
           *reinterpret_cast<float4*>(om + side * side_off + (ti >> 1) * (TILE * BLK_COLS) + (ti & 1) * FRAG + om_lane) =
               make_float4(x[0], x[1], x[2], x[3]);
         // The staging rows are wave-private and the LDS serves one wave's accesses in order: the read below
@@ -508,6 +508,9 @@ static int build_impl(nugpr_ctx* c, const double* theta, hipStream_t s, bool nee
   }
   c->diag_residual = (float)((alpha + sigma2) - (double)a.diag_val);
   PanelArgs ac = a;                                  // the coupling launch
+  // the upper tiles of C can be left out only if its strips pair up in the product (and nothing else reads them)
+  const bool need_c_upper = need_upper || L.compensate || !c->c_paired;
+  ac.mirror = need_c_upper ? 1 : 0;
   if (L.compensate) {
     // lambda_0 = smallest eigenvalue of the representatives' kernel matrix (eq. (krep)), fp64 on the host
     const int N = L.ncr;
@@ -568,6 +571,8 @@ static int build_impl(nugpr_ctx* c, const double* theta, hipStream_t s, bool nee
     c->theta_spare[pair_param] = value_minus;
   }
   c->spare_upper_valid = pair && need_upper;
+  c->c_upper_valid = need_c_upper;
+  c->spare_c_upper_valid = pair && need_c_upper;
   c->op_scale = 1.0;
   c->op_shift = (double)c->diag_residual;
   c->built = true;
@@ -592,6 +597,7 @@ int swap_pair(nugpr_ctx* c) {
   c->theta_built.swap(c->theta_spare);
   c->theta_spare.clear();               // the blocks left behind are not used again
   c->kd_upper_valid = c->spare_upper_valid;
+  c->c_upper_valid = c->spare_c_upper_valid;
   c->build_gen += 1;
   return NUGPR_OK;
 }
@@ -614,6 +620,10 @@ int launch_export(nugpr_ctx* c, int what, int index, float* dst, int64_t ld, hip
     }
   } else if (what == 3) {
     if (!c->built) { set_error("nothing stored yet"); return NUGPR_ERR_STATE; }
+    {
+      const int rc = ensure_c_upper(c, s);
+      if (rc) return rc;
+    }
     src = c->C; lds = L.ldc; rows = cols = L.ncr;
   } else if (what == 4) {
     if (index < 0 || index >= L.nc) { set_error("cluster index out of range"); return NUGPR_ERR_INVALID; }

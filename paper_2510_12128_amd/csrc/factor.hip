@@ -376,6 +376,32 @@ __global__ __launch_bounds__(256) void k_mirror(const ClusterInfo* __restrict__ 
   }
 }
 
+// upper tiles of one square blocked matrix of nt x nt tiles <- transposes of the lower ones (1-D grid of nt * nt)
+__global__ __launch_bounds__(256) void k_mirror_square(float* __restrict__ M, uint32_t ld, int nt) {
+  __shared__ float sT[TILE][TILE + 1];
+  const int tr = (int)(blockIdx.x / (unsigned)nt), tc = (int)(blockIdx.x % (unsigned)nt);
+  if (tc >= tr) return;
+  const int tid = threadIdx.x;
+  for (int idx = tid; idx < TILE * TILE; idx += 256) {
+    const int r = idx >> 6, q = idx & 63;
+    sT[r][q] = M[blocked_index(ld, tr * TILE + r, tc * TILE + q)];
+  }
+  __syncthreads();
+  for (int idx = tid; idx < TILE * TILE; idx += 256) {
+    const int r = idx >> 6, q = idx & 63;
+    M[blocked_index(ld, tc * TILE + r, tr * TILE + q)] = sT[q][r];
+  }
+}
+
+int ensure_c_upper(nugpr_ctx* c, hipStream_t s) {
+  if (c->c_upper_valid || !c->built) return NUGPR_OK;
+  const int nt = c->L.ldc / TILE;
+  hipLaunchKernelGGL(k_mirror_square, dim3((unsigned)nt * (unsigned)nt), dim3(256), 0, s, c->C, (uint32_t)c->L.ldc, nt);
+  NUGPR_HIP(hipGetLastError());
+  c->c_upper_valid = true;
+  return NUGPR_OK;
+}
+
 bool kd_lower_suffices(const nugpr_ctx* c) {
   // fp64 mode with 2..17 columns (one column group): the producer / consumer strip kernel pairs the tiles of
   // the symmetric blocks.  The Pade route also solves single columns, which read whole strips.

@@ -232,6 +232,8 @@ struct nugpr_ctx {
   // The assembly may leave out the strictly upper tiles of the K_ii (the product's usual launch reads the
   // lower ones only, see k_strip_ring); whoever needs whole strips calls ensure_kd_upper first.
   bool kd_upper_valid = false, spare_upper_valid = false;
+  // the same for the coupling matrix, whose strips pair up when c_paired (set with the work tables)
+  bool c_upper_valid = false, spare_c_upper_valid = false, c_paired = false;
   bool general_route = false;   // take the streamed-K_diag route even where the identity relation holds
   // SPD compensation (eq. (krep)): host copy of the representatives and lambda_0 of the last assembly.
   // Clo holds what fp32 storage of C - lambda_0 I drops: C_exact - lambda_0 I - C_stored, itself in fp32,
@@ -271,6 +273,7 @@ int swap_pair(nugpr_ctx* c);
 bool kd_lower_suffices(const nugpr_ctx* c);
 // fills the strictly upper tiles of the K_ii from the lower ones if the last assembly left them out
 int ensure_kd_upper(nugpr_ctx* c, hipStream_t s);
+int ensure_c_upper(nugpr_ctx* c, hipStream_t s);
 int launch_export(nugpr_ctx* c, int what, int index, float* dst, int64_t ld, hipStream_t s);
 
 // strip_gemm.hip ------------------------------------------------------------

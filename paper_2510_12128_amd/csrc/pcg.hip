@@ -353,8 +353,8 @@ int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s, doubl
   // first direction of every solve on the context's own right-hand sides, is kept with the factor
   const bool s_known = D == c->Z0v && T == L.T && c->z0_ready;
   if (!s_known && (rc = run_project(c, D, T, s))) return rc;
-  // only the launch with one column group in fp64 mode reads the lower tiles of the K_ii alone
-  if (!(c->acc64 && T >= 2 && T <= 17) && (rc = ensure_kd_upper(c, s))) return rc;
+  // only the launch with one column group in fp64 mode reads the lower tiles of the K_ii and of C alone
+  if (!(c->acc64 && T >= 2 && T <= 17) && ((rc = ensure_kd_upper(c, s)) || (rc = ensure_c_upper(c, s)))) return rc;
   // Q_i = K_ii D_i   and   P = C_offdiag S (column slabs), one launch
   StripPort k0{}, k1{};
   k0.A = c->Kd; k0.in = D; k0.out = Q; k0.nin = 1; k0.scale = c->op_scale; k0.diag_add = c->op_shift;
@@ -522,6 +522,7 @@ static int run_lowrank_accumulate(nugpr_ctx* c, const void* D, void* Q, int T, h
   const Layout& L = c->L;
   int rc;
   const uint64_t ppart = (uint64_t)L.ncr * T;
+  if (!(c->acc64 && T >= 2 && T <= 17) && (rc = ensure_c_upper(c, s))) return rc;
   if ((rc = run_project(c, D, T, s))) return rc;
   StripPort k1{};
   k1.A = c->C; k1.in = c->Spart; k1.nin = 1; k1.out = c->Ppart; k1.out_part_stride = ppart; k1.scale = c->op_scale;

@@ -347,22 +347,36 @@ __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(2))) void k
   const int m = lane & 15, kg = lane >> 4;
   const int nrows = (int)it.nrows;
   const int c_begin = (int)it.c_begin, c_end = (int)it.c_end;
-  // Strips of a symmetric square block (flag bit 1, c_begin = 0): strip j of nt visits the 64-column tiles
-  // in the order p = (t - j) mod nt, t = 0 .. nt - 1, and takes tile (j, p) from its own rows when p <= j
-  // but as the transpose of tile (p, j), from strip p's rows, when p > j.  Strip p visits tile (p, j) at
-  // the same step t, so the two workgroups (dealt to the same die, started together) ask for the same
-  // 16 KiB at about the same time and the die's L2 fetches it from HBM once: the lower triangles are
-  // streamed, the upper ones never leave memory.
-  const bool sym = SYM && (it.blocked & 2u) != 0;
-  const int jt = (int)(it.row_in_block >> 6), ntile = (c_end + TILE - 1) >> 6;
-  const int nchunks = sym ? 2 * ntile : (c_end > c_begin ? (c_end - c_begin + RCH - 1) / RCH : 0);
-  // chunk ch: first column c of the product it covers; p > jt marks a transposed tile
-  auto locate = [&](const int ch, int& c, int& p) {
-    if (!sym) { c = c_begin + ch * RCH; p = 0; return false; }
-    p = (ch >> 1) - jt;
-    p += p < 0 ? ntile : 0;
-    c = TILE * p + RCH * (ch & 1);
-    return p > jt;
+  // Strips of a symmetric matrix (StripItem::blocked bit 1).  The item's columns are the tiles tb .. tb + nb - 1
+  // of a square super-block whose rows are a group of `na` strips; the item is strip number jr of that group.
+  // It visits its tiles in the rotating order p = (t - jr) mod max(na, nb), t = 0, 1, ..  A super-block on the
+  // diagonal of the matrix (kind 0: a cluster's K_ii, or a diagonal block of C) takes tile p from the strip's
+  // own rows when p <= jr and as the TRANSPOSE of the stored tile (tb + p, strip) when p > jr; one below the
+  // diagonal (kind 1) always reads its own rows, one above it (kind 2) always the transposed tiles of its
+  // mirror image.  The partner strip visits the same stored tile at the same step t, the two workgroups are
+  // dealt to the same die and start together, so the two requests for the same 16 KiB meet in that die's L2
+  // and HBM serves one: the lower triangle is streamed, the upper one never leaves memory.  Steps whose
+  // tile lies past the item's last one (groups of unequal size) load a valid tile and drop it whole.
+  const uint32_t fl = it.blocked;
+  const bool sym = SYM && (fl & 2u) != 0;
+  const int kind = (int)((fl >> 2) & 3u);
+  const int j_abs = (int)(it.row_in_block >> 6);                      // the strip's index inside the matrix
+  const int tb = c_begin >> 6, nb = (c_end - c_begin + TILE - 1) >> 6;
+  const int na = (int)((fl >> 4) & 0x7ffu);                           // 0: the group is the item's own tile range
+  const int jr = na ? (int)((fl >> 15) & 0x7ffu) : j_abs - tb;
+  const int mrot = na > nb ? na : nb;
+  const int nchunks = sym ? 2 * mrot : (c_end > c_begin ? (c_end - c_begin + RCH - 1) / RCH : 0);
+  // chunk ch: c = first column of the product it covers (c_end: none, the chunk is dropped), c_addr = first
+  // column of the tile that is loaded, p = that tile's number in the item; returns whether it is transposed
+  auto locate = [&](const int ch, int& c, int& c_addr, int& p) {
+    if (!sym) { c = c_addr = c_begin + ch * RCH; p = 0; return false; }
+    p = (ch >> 1) - jr;
+    p += p < 0 ? mrot : 0;
+    const bool valid = p < nb;
+    p = valid ? p : nb - 1;
+    c_addr = c_begin + TILE * p + RCH * (ch & 1);
+    c = valid ? c_addr : c_end;
+    return kind == 2 || (kind == 0 && p > jr);
   };
 
   if (wave == 4) {
@@ -383,18 +397,18 @@ __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(2))) void k
       rowoff[w] = blocked ? (uint64_t)((rw >> 4) * 2) * FRAG + (uint64_t)(rw & 15) * 16 : (uint64_t)rw * (uint64_t)it.lda;
     }
     const unsigned char* __restrict__ vbytes = reinterpret_cast<const unsigned char*>(vin);
-    // transposed tiles: the operand of (w, s) is fragment (2 half + s, w % 2) of column block 2 jt + w / 2
-    // of strip p, whole (every fragment of the padded block exists); lane l fetches the piece (row
+    // transposed tiles: the operand of (w, s) is fragment (2 half + s, w % 2) of column block 2 j_abs + w / 2
+    // of strip tb + p, whole (every fragment of the padded block exists); lane l fetches the piece (row
     // 4 ((l / 4) % 4) + l / 16, columns 4 (l % 4) .. + 3), which puts element (4 kg + i, m) of the fragment
     // at float 64 i + 16 kg + m: the consumers read their four values with unit stride across the wave
-    const float* __restrict__ At = pt.A + it.a_off + (uint64_t)(2 * jt) * (TILE * BLK_COLS) +
+    const float* __restrict__ At = pt.A + it.a_off + (uint64_t)(2 * j_abs) * (TILE * BLK_COLS) +
                                    (((lane >> 2) & 3) * 4 + (lane >> 4)) * 16 + (lane & 3) * 4;
     auto issue = [&](const int ch) {
-      int c, p;
-      const bool tr = locate(ch, c, p);
+      int c, c_addr, p;
+      const bool tr = locate(ch, c, c_addr, p);
       unsigned char* st = ring + (ch % STAGES) * Cfg::STAGE_BYTES;
       if (SYM && tr) {
-        const float* __restrict__ Ap = At + (uint64_t)(p - jt) * TILE * (uint64_t)it.lda + (ch & 1) * (4 * FRAG);
+        const float* __restrict__ Ap = At + (uint64_t)(tb + p - j_abs) * TILE * (uint64_t)it.lda + (ch & 1) * (4 * FRAG);
 #pragma unroll
         for (int w = 0; w < 4; ++w)
 #pragma unroll
@@ -406,7 +420,7 @@ __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(2))) void k
         for (int w = 0; w < 4; ++w)
 #pragma unroll
           for (int s = 0; s < NSTEP; ++s)
-            __builtin_amdgcn_global_load_lds(Ab + rowoff[w] + (uint64_t)c * cmul + s * smul, st + (w * NSTEP + s) * 1024, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(Ab + rowoff[w] + (uint64_t)c_addr * cmul + s * smul, st + (w * NSTEP + s) * 1024, 16, 0, 0);
       }
       // vector slab: rows in_row0 + c .., T columns, contiguous; 16-byte pieces past its last valid byte
       // re-read the last valid piece (the consumers drop those rows).  A chunk that lies wholly past the
@@ -451,8 +465,8 @@ __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(2))) void k
   double daccy = 0.0;
 
   for (int ch = 0; ch < nchunks; ++ch) {
-    int c, p_tile;
-    const bool tr = locate(ch, c, p_tile);
+    int c, c_addr, p_tile;
+    const bool tr = locate(ch, c, c_addr, p_tile);
     __builtin_amdgcn_s_barrier();                             // chunk ch is in its stage
     const unsigned char* st = ring + (ch % STAGES) * Cfg::STAGE_BYTES;
     const float4* __restrict__ sAw = reinterpret_cast<const float4*>(st) + wave * (64 * NSTEP) + lane;

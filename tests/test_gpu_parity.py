@@ -38,6 +38,11 @@ CASES = {
     # cluster sizes whose last 64-column tile is more than half full, exactly half full, and one column wide:
     # the strips of a diagonal block walk their tiles in a rotating order and read the upper ones transposed
     "ragged-halves": lambda: small_ragged(seed=6, t=16, sizes=[104, 242, 160, 321], spacing=6.0),
+    # 17 x 128 representatives: the coupling matrix has 34 tile rows in 12 groups (eleven of 3, one of 1), so
+    # its strips pair up over super-blocks of unequal size, rotate through several tiles, and four column
+    # slabs stay empty
+    "many-reps": lambda: I.make_small(n_clusters=17, sizes=[130 + (7 * i) % 23 for i in range(17)], d=3, rank=128,
+                                      t=16, seed=9, ell=1.5, spacing=7.0, sigma_blob=0.5, tol=1e-6, max_iter=100),
     "tiny": lambda: I.make_small(n_clusters=3, sizes=[8, 12, 5], d=2, rank=2, t=4, seed=7, ell=1.5,
                                  spacing=3.5, sigma_blob=0.3, tol=1e-6, max_iter=50),
     "iso-d1": lambda: I.make_small(n_clusters=2, sizes=[90, 40], d=1, rank=3, t=3, seed=8, ell=0.8,
@@ -55,7 +60,7 @@ def relmax(a, b):
     return float(np.max(np.abs(a - b)) / max(np.max(np.abs(b)), 1e-300))
 
 
-@pytest.mark.parametrize("case", ["ragged-t8", "tiny", "iso-d1", "C1-wide"])
+@pytest.mark.parametrize("case", ["ragged-t8", "many-reps", "tiny", "iso-d1", "C1-wide"])
 def test_build_blocks_matches_oracle(lib, case):
     w = CASES[case]()
     print("case", w.name, flush=True)
@@ -82,7 +87,8 @@ def test_build_blocks_matches_oracle(lib, case):
     ctx.close()
 
 
-@pytest.mark.parametrize("case", ["ragged-t8", "ragged-t16", "ragged-t32", "ragged-halves", "tiny", "iso-d1", "C1-wide"])
+@pytest.mark.parametrize("case", ["ragged-t8", "ragged-t16", "ragged-t32", "ragged-halves", "many-reps", "tiny", "iso-d1",
+                                  "C1-wide"])
 def test_matvec_matches_oracle(lib, case):
     w = CASES[case]()
     print("case", w.name, flush=True)
@@ -99,11 +105,12 @@ def test_matvec_matches_oracle(lib, case):
     ctx.close()
 
 
-def test_upper_tiles_are_filled_in_when_a_product_needs_them(lib):
-    """An assembly for a context whose products read the lower tiles of the K_ii leaves the upper tiles
-    out; products of other widths (whole strips) and the export must still see the full blocks, after
+@pytest.mark.parametrize("case", ["ragged-halves", "many-reps"])
+def test_upper_tiles_are_filled_in_when_a_product_needs_them(lib, case):
+    """An assembly for a context whose products read the lower tiles of the K_ii (and of the coupling matrix,
+    when its strips pair up) leaves the upper tiles out; products of other widths (whole strips) and the export must still see the full blocks, after
     every assembly."""
-    w = CASES["ragged-halves"]()
+    w = CASES[case]()
     print("case", w.name, flush=True)
     ctx = make_ctx(lib, w)
     prob = oracle_problem(w)
@@ -117,11 +124,13 @@ def test_upper_tiles_are_filled_in_when_a_product_needs_them(lib):
             D = rng.standard_normal((w.n, ncols)).astype(np.float32)
             Q = ctx.nugpr_matvec(D).cpu().numpy().astype(np.float64)
             assert relmax(Q, op(D.astype(np.float64))) < 1e-5, (scale, ncols)
-        blocks, _ = prob.assemble(theta)
+        blocks, Cm = prob.assemble(theta)
         for i in range(w.n_clusters):
             Ki = ctx.nugpr_export(B.EXPORT_K, i).cpu().numpy().astype(np.float64)
             np.testing.assert_allclose(Ki, blocks[i], rtol=2e-6, atol=1e-7)
             assert np.array_equal(Ki, Ki.T)
+        Cg = ctx.nugpr_export(B.EXPORT_C).cpu().numpy().astype(np.float64)
+        assert np.array_equal(Cg, Cg.T)
     ctx.close()
 
 
@@ -153,7 +162,8 @@ def test_precond_factor_and_apply_match_oracle(lib, case):
     ctx.close()
 
 
-@pytest.mark.parametrize("case", ["ragged-t8", "ragged-t16", "ragged-t32", "ragged-halves", "tiny", "iso-d1", "C1", "C1-wide"])
+@pytest.mark.parametrize("case", ["ragged-t8", "ragged-t16", "ragged-t32", "ragged-halves", "many-reps", "tiny", "iso-d1",
+                                  "C1", "C1-wide"])
 def test_pcg_solve_and_mll_match_oracle(lib, case):
     w = CASES[case]()
     print("case", w.name, flush=True)
