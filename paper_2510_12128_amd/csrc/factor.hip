@@ -157,8 +157,7 @@ __device__ __forceinline__ void for_each_acc(v4f (&acc)[2][2], int tid, F f) {
 // fall past the last cluster return at once).
 constexpr int NUM_DIES = 8;
 static inline unsigned die_grid(int per, int nc) { return (unsigned)per * NUM_DIES * ((nc + NUM_DIES - 1) / NUM_DIES); }
-__device__ __forceinline__ bool die_local_item(int per, int nc, int& cluster, int& item) {
-  const int id = (int)blockIdx.x;
+__device__ __forceinline__ bool die_local_item(int per, int nc, int& cluster, int& item, int id = (int)blockIdx.x) {
   const int die = id % NUM_DIES, slot = id / NUM_DIES;
   cluster = die + NUM_DIES * (slot / per);
   item = slot % per;
@@ -168,17 +167,29 @@ __device__ __forceinline__ bool die_local_item(int per, int nc, int& cluster, in
 // ---------------------------------------------------------------------------
 // Cholesky, step k
 // ---------------------------------------------------------------------------
+// Left-looking, with the bulk of every tile's update done one step ahead.  The launch of step k has two
+// kinds of workgroups:
+//   finish  tile (m, k), m >= k: subtract the contribution of column k - 1, the only one that was not final
+//           when the bulk was computed; the workgroup of the diagonal tile then factors and inverts it in LDS
+//   bulk    tile (m, k + 1), m >= k + 1: L <- A - sum over the columns < k, all final by now
+// The factorisation of the diagonal tile is serial and keeps one workgroup per cluster busy for tens of
+// microseconds; with the long products of the NEXT column in the same launch the rest of the chip has work
+// meanwhile, where a launch that only finished column k would idle behind its diagonal tiles.
+// Grid: the finish workgroups of all clusters first (n_finish per cluster), then the bulk ones.
 __global__ __launch_bounds__(256) void k_potrf_update(const ClusterInfo* __restrict__ cl, const float* __restrict__ Kd,
                                                       float* __restrict__ Lf, float* __restrict__ G, int k,
-                                                      int per, int nc, PcgState* __restrict__ st) {
-  __shared__ float sA[TILE][SP];
-  __shared__ float sB[TILE][SP];
+                                                      int n_finish, int n_bulk, int grid_finish, int nc,
+                                                      PcgState* __restrict__ st) {
+  __shared__ __attribute__((aligned(16))) float sA[TILE][SP];
+  __shared__ __attribute__((aligned(16))) float sB[TILE][SP];
   __shared__ float sT[TILE][TILE + 1];
   __shared__ float sI[TILE][TILE + 1];
+  const bool bulk = (int)blockIdx.x >= grid_finish;
   int ci, item;
-  if (!die_local_item(per, nc, ci, item)) return;
+  if (!die_local_item(bulk ? n_bulk : n_finish, nc, ci, item, bulk ? (int)blockIdx.x - grid_finish : (int)blockIdx.x)) return;
   const ClusterInfo c = cl[ci];
-  const int mt = k + item;
+  const int col = bulk ? k + 1 : k;            // tile column this workgroup works on
+  const int mt = col + item;
   if (mt >= (int)c.nt) return;
   const int tid = threadIdx.x;
   const int b = (int)c.b;
@@ -187,19 +198,22 @@ __global__ __launch_bounds__(256) void k_potrf_update(const ClusterInfo* __restr
   v4f acc[2][2];
   zero_acc(acc);
   Operand oa{L, c.ld, mt * TILE, b, 0};
-  Operand ob{L, c.ld, k * TILE, b, 0};
-  tile_gemm<false, false>(acc, oa, ob, 0, k * TILE, sA, sB, tid);
-  if (mt != k) {
+  Operand ob{L, c.ld, col * TILE, b, 0};
+  if (bulk) tile_gemm<false, false>(acc, oa, ob, 0, k * TILE, sA, sB, tid);
+  else if (k > 0) tile_gemm<false, false>(acc, oa, ob, (k - 1) * TILE, k * TILE, sA, sB, tid);
+  // what the products are subtracted from: the assembled block, or the bulk result of the step before
+  const float* base = (bulk || k == 0) ? A : L;
+  if (bulk || mt != k) {
     for_each_acc(acc, tid, [&](int r, int q, float v) {
-      const uint64_t at = blocked_index(c.ld, mt * TILE + r, k * TILE + q);
-      L[at] = A[at] - v;
+      const uint64_t at = blocked_index(c.ld, mt * TILE + r, col * TILE + q);
+      L[at] = base[at] - v;
     });
     return;
   }
   // ---- diagonal tile: factor in LDS; rows/cols past the cluster end behave as identity ----
   const int valid = min(TILE, b - k * TILE);
   for_each_acc(acc, tid, [&](int r, int q, float v) {
-    float x = A[blocked_index(c.ld, k * TILE + r, k * TILE + q)] - v;
+    float x = base[blocked_index(c.ld, k * TILE + r, k * TILE + q)] - v;
     if (r >= valid || q >= valid) x = (r == q) ? 1.f : 0.f;
     sT[r][q] = x;
   });
@@ -280,8 +294,8 @@ __global__ __launch_bounds__(256) void k_potrf_update(const ClusterInfo* __restr
 // tiles below the diagonal: L[m,k] <- L[m,k] * inv(L[k,k])^T
 __global__ __launch_bounds__(256) void k_potrf_trsm(const ClusterInfo* __restrict__ cl, float* __restrict__ Lf,
                                                     const float* __restrict__ G, int k, int per, int nc) {
-  __shared__ float sA[TILE][SP];
-  __shared__ float sB[TILE][SP];
+  __shared__ __attribute__((aligned(16))) float sA[TILE][SP];
+  __shared__ __attribute__((aligned(16))) float sB[TILE][SP];
   int ci, item;
   if (!die_local_item(per, nc, ci, item)) return;
   const ClusterInfo c = cl[ci];
@@ -305,8 +319,8 @@ __global__ __launch_bounds__(256) void k_potrf_trsm(const ClusterInfo* __restric
 // stage 1: T = L21 * Y11, stored transposed in the mirror block (upper triangle of G)
 __global__ __launch_bounds__(256) void k_trtri_stage1(const ClusterInfo* __restrict__ cl, const float* __restrict__ Lf,
                                                       float* __restrict__ G, int half, int per, int nc) {
-  __shared__ float sA[TILE][SP];
-  __shared__ float sB[TILE][SP];
+  __shared__ __attribute__((aligned(16))) float sA[TILE][SP];
+  __shared__ __attribute__((aligned(16))) float sB[TILE][SP];
   __shared__ float sT[TILE][TILE + 1];
   int ci, item;
   if (!die_local_item(per, nc, ci, item)) return;
@@ -336,8 +350,8 @@ __global__ __launch_bounds__(256) void k_trtri_stage1(const ClusterInfo* __restr
 // stage 2: Y21 = -Y22 * T
 __global__ __launch_bounds__(256) void k_trtri_stage2(const ClusterInfo* __restrict__ cl, float* __restrict__ G,
                                                       int half, int per, int nc) {
-  __shared__ float sA[TILE][SP];
-  __shared__ float sB[TILE][SP];
+  __shared__ __attribute__((aligned(16))) float sA[TILE][SP];
+  __shared__ __attribute__((aligned(16))) float sB[TILE][SP];
   int ci, item;
   if (!die_local_item(per, nc, ci, item)) return;
   const ClusterInfo c = cl[ci];
@@ -458,8 +472,10 @@ int launch_factor(nugpr_ctx* c, hipStream_t s) {
   const Layout& L = c->L;
   hipLaunchKernelGGL(k_reset_bad, dim3(1), dim3(1), 0, s, c->d_state);
   for (int k = 0; k < L.ntmax; ++k) {
-    hipLaunchKernelGGL(k_potrf_update, dim3(die_grid(L.ntmax - k, L.nc)), dim3(256), 0, s, c->d_cl, c->Kd, c->Lf, c->G, k,
-                       L.ntmax - k, L.nc, c->d_state);
+    const int n_finish = L.ntmax - k, n_bulk = L.ntmax - k - 1;
+    const unsigned grid_finish = die_grid(n_finish, L.nc), grid_bulk = n_bulk > 0 ? die_grid(n_bulk, L.nc) : 0u;
+    hipLaunchKernelGGL(k_potrf_update, dim3(grid_finish + grid_bulk), dim3(256), 0, s, c->d_cl, c->Kd, c->Lf, c->G, k,
+                       n_finish, n_bulk, (int)grid_finish, L.nc, c->d_state);
     if (k + 1 < L.ntmax)
       hipLaunchKernelGGL(k_potrf_trsm, dim3(die_grid(L.ntmax - k - 1, L.nc)), dim3(256), 0, s, c->d_cl, c->Lf, c->G, k,
                          L.ntmax - k - 1, L.nc);
