@@ -152,12 +152,22 @@ __device__ __forceinline__ void for_each_acc(v4f (&acc)[2][2], int tid, F f) {
 // Workgroup -> (cluster, item) for a launch of `per` items for each of `nc` clusters: a 1-D grid of
 // die_grid(per, nc) workgroups.  Workgroups go round-robin to the 8 dies, each with an L2 of its own: with
 // the cluster as the slow index of a plain grid the tiles of one cluster, which all read the same panel,
-// would be spread over every die and the panel fetched eight times.  Here die d takes the clusters d,
-// d + 8, .. one after the other (the grid is rounded up to whole groups of 8 clusters; workgroups that
-// fall past the last cluster return at once).
+// would be spread over every die and the panel fetched eight times.  With nc > 0 die d takes the clusters
+// d, d + 8, .. one after the other (the grid is rounded up to whole groups of 8 clusters; workgroups that
+// fall past the last cluster return at once).  That ties a cluster's work to one die: with clusters of
+// very different sizes the dies would finish far apart, and the host then passes -nc for the plain order
+// (cluster = slow index), which spreads every cluster over all dies (configuration 5: 302 against 353 ms).
 constexpr int NUM_DIES = 8;
-static inline unsigned die_grid(int per, int nc) { return (unsigned)per * NUM_DIES * ((nc + NUM_DIES - 1) / NUM_DIES); }
+static inline unsigned die_grid(int per, int nc) {
+  const int n = nc < 0 ? -nc : nc;
+  return (unsigned)per * NUM_DIES * ((n + NUM_DIES - 1) / NUM_DIES);
+}
 __device__ __forceinline__ bool die_local_item(int per, int nc, int& cluster, int& item, int id = (int)blockIdx.x) {
+  if (nc < 0) {
+    cluster = id / per;
+    item = id % per;
+    return cluster < -nc;
+  }
   const int die = id % NUM_DIES, slot = id / NUM_DIES;
   cluster = die + NUM_DIES * (slot / per);
   item = slot % per;
@@ -470,22 +480,27 @@ __global__ void k_set_col0(VT* __restrict__ B, const float* __restrict__ y, int6
 
 int launch_factor(nugpr_ctx* c, hipStream_t s) {
   const Layout& L = c->L;
+  // clusters of similar size: one die per cluster; otherwise every cluster over all dies (see die_local_item)
+  uint64_t tiles_sum = 0;
+  for (const ClusterInfo& ci : L.cl) tiles_sum += ci.nt;
+  const bool even = (uint64_t)L.ntmax * (uint64_t)L.nc * 4 <= tiles_sum * 5;
+  const int ncm = even ? L.nc : -L.nc;
   hipLaunchKernelGGL(k_reset_bad, dim3(1), dim3(1), 0, s, c->d_state);
   for (int k = 0; k < L.ntmax; ++k) {
     const int n_finish = L.ntmax - k, n_bulk = L.ntmax - k - 1;
-    const unsigned grid_finish = die_grid(n_finish, L.nc), grid_bulk = n_bulk > 0 ? die_grid(n_bulk, L.nc) : 0u;
+    const unsigned grid_finish = die_grid(n_finish, ncm), grid_bulk = n_bulk > 0 ? die_grid(n_bulk, ncm) : 0u;
     hipLaunchKernelGGL(k_potrf_update, dim3(grid_finish + grid_bulk), dim3(256), 0, s, c->d_cl, c->Kd, c->Lf, c->G, k,
-                       n_finish, n_bulk, (int)grid_finish, L.nc, c->d_state);
+                       n_finish, n_bulk, (int)grid_finish, ncm, c->d_state);
     if (k + 1 < L.ntmax)
-      hipLaunchKernelGGL(k_potrf_trsm, dim3(die_grid(L.ntmax - k - 1, L.nc)), dim3(256), 0, s, c->d_cl, c->Lf, c->G, k,
-                         L.ntmax - k - 1, L.nc);
+      hipLaunchKernelGGL(k_potrf_trsm, dim3(die_grid(L.ntmax - k - 1, ncm)), dim3(256), 0, s, c->d_cl, c->Lf, c->G, k,
+                         L.ntmax - k - 1, ncm);
   }
   for (int half = 1; half < L.ntmax; half *= 2) {
     const int nodes = (L.ntmax + 2 * half - 1) / (2 * half);
     const int per = half * half * nodes;
-    dim3 grid(die_grid(per, L.nc));
-    hipLaunchKernelGGL(k_trtri_stage1, grid, dim3(256), 0, s, c->d_cl, c->Lf, c->G, half, per, L.nc);
-    hipLaunchKernelGGL(k_trtri_stage2, grid, dim3(256), 0, s, c->d_cl, c->G, half, per, L.nc);
+    dim3 grid(die_grid(per, ncm));
+    hipLaunchKernelGGL(k_trtri_stage1, grid, dim3(256), 0, s, c->d_cl, c->Lf, c->G, half, per, ncm);
+    hipLaunchKernelGGL(k_trtri_stage2, grid, dim3(256), 0, s, c->d_cl, c->G, half, per, ncm);
   }
   hipLaunchKernelGGL(k_mirror, dim3((unsigned)L.n_diag_tiles), dim3(256), 0, s, c->d_cl, c->d_tiles, c->G);
   hipLaunchKernelGGL(k_logdet, dim3(L.nc), dim3(256), 0, s, c->d_cl, c->G, c->d_logdet);
