@@ -190,10 +190,14 @@ __global__ __launch_bounds__(256) void k_potrf_update(const ClusterInfo* __restr
                                                       float* __restrict__ Lf, float* __restrict__ G, int k,
                                                       int n_finish, int n_bulk, int grid_finish, int nc,
                                                       PcgState* __restrict__ st) {
-  __shared__ __attribute__((aligned(16))) float sA[TILE][SP];
-  __shared__ __attribute__((aligned(16))) float sB[TILE][SP];
-  __shared__ float sT[TILE][TILE + 1];
+  // the operand stages and, once the products are done, the tile being factored share one piece of LDS
+  // (34 KB per workgroup with the inverse: four workgroups per compute unit instead of three)
+  static_assert(2 * TILE * SP >= TILE * (TILE + 1), "the factored tile must fit in the operand stages");
+  __shared__ __attribute__((aligned(16))) float stage[2 * TILE * SP];
   __shared__ float sI[TILE][TILE + 1];
+  float (*sA)[SP] = reinterpret_cast<float (*)[SP]>(stage);
+  float (*sB)[SP] = reinterpret_cast<float (*)[SP]>(stage + TILE * SP);
+  float (*sT)[TILE + 1] = reinterpret_cast<float (*)[TILE + 1]>(stage);
   const bool bulk = (int)blockIdx.x >= grid_finish;
   int ci, item;
   if (!die_local_item(bulk ? n_bulk : n_finish, nc, ci, item, bulk ? (int)blockIdx.x - grid_finish : (int)blockIdx.x)) return;
@@ -221,6 +225,7 @@ __global__ __launch_bounds__(256) void k_potrf_update(const ClusterInfo* __restr
     return;
   }
   // ---- diagonal tile: factor in LDS; rows/cols past the cluster end behave as identity ----
+  __syncthreads();                              // every wave is done reading the operand stages
   const int valid = min(TILE, b - k * TILE);
   for_each_acc(acc, tid, [&](int r, int q, float v) {
     float x = base[blocked_index(c.ld, k * TILE + r, k * TILE + q)] - v;
@@ -329,9 +334,10 @@ __global__ __launch_bounds__(256) void k_potrf_trsm(const ClusterInfo* __restric
 // stage 1: T = L21 * Y11, stored transposed in the mirror block (upper triangle of G)
 __global__ __launch_bounds__(256) void k_trtri_stage1(const ClusterInfo* __restrict__ cl, const float* __restrict__ Lf,
                                                       float* __restrict__ G, int half, int per, int nc) {
-  __shared__ __attribute__((aligned(16))) float sA[TILE][SP];
-  __shared__ __attribute__((aligned(16))) float sB[TILE][SP];
-  __shared__ float sT[TILE][TILE + 1];
+  __shared__ __attribute__((aligned(16))) float stage[2 * TILE * SP];   // operand stages, then the tile on its way to the mirror block
+  float (*sA)[SP] = reinterpret_cast<float (*)[SP]>(stage);
+  float (*sB)[SP] = reinterpret_cast<float (*)[SP]>(stage + TILE * SP);
+  float (*sT)[TILE + 1] = reinterpret_cast<float (*)[TILE + 1]>(stage);
   int ci, item;
   if (!die_local_item(per, nc, ci, item)) return;
   const ClusterInfo c = cl[ci];
@@ -347,6 +353,7 @@ __global__ __launch_bounds__(256) void k_trtri_stage1(const ClusterInfo* __restr
   Operand oa{L, c.ld, tm * TILE, (int)c.b, 0};          // L21[m][k]
   Operand ob{Y, c.ld, tn * TILE, (int)c.ld, 2};         // OpB[n][k] = Y11[k][n], nonzero for k >= n
   tile_gemm<false, true>(acc, oa, ob, tn * TILE, mid * TILE, sA, sB, tid);
+  __syncthreads();                              // every wave is done reading the operand stages
   for_each_acc(acc, tid, [&](int r, int q, float v) { sT[r][q] = v; });
   __syncthreads();
   // mirror block: rows = columns of T (tile tn), columns = rows of T (tile tm)
