@@ -269,6 +269,7 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   c->G = reinterpret_cast<float*>(w + L.o_G);
   c->C = reinterpret_cast<float*>(w + L.o_C);
   c->Kd2 = reinterpret_cast<float*>(w + L.o_Kd2);
+  c->Q0v = w + L.o_Q0;
   c->C2 = reinterpret_cast<float*>(w + L.o_C2);
   c->Clo = L.compensate ? reinterpret_cast<float*>(w + L.o_Clo) : nullptr;
   c->Wd = reinterpret_cast<float*>(w + L.o_Wd);

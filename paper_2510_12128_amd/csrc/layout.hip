@@ -124,6 +124,7 @@ int plan_layout(const nugpr_problem* pb, uint32_t flags, Layout& L) {
   L.o_x0 = take(cur, (size_t)L.n * sizeof(double));
   L.o_Z0 = take(cur, vec);
   L.o_P = take(cur, vec);
+  L.o_Q0 = take(cur, vec);
   L.o_S0 = take(cur, (size_t)L.ncr * L.T * sizeof(double));
   L.o_Spart = take(cur, (size_t)L.nsS * L.ncr * L.T * sizeof(double));
   L.o_Ppart = take(cur, (size_t)L.nsP * L.ncr * L.T * sizeof(double));

@@ -155,6 +155,7 @@ struct Layout {
   uint64_t rows_pad = 0;      // sum of ld over the clusters
   // byte offsets into the workspace
   size_t o_cl = 0, o_Kd = 0, o_Lf = 0, o_G = 0, o_C = 0, o_Wd = 0, o_Wt = 0, o_reps = 0;
+  size_t o_Q0 = 0;                   // K' z_0 kept from the base loss
   size_t o_Kd2 = 0, o_C2 = 0;        // spare K_diag and C: second matrix of a pair assembly
   size_t o_B = 0, o_X = 0, o_R = 0, o_Z = 0, o_D = 0, o_Q = 0, o_V = 0, o_U = 0;
   size_t o_Spart = 0, o_Ppart = 0, o_dot = 0, o_state = 0, o_alog = 0, o_blog = 0;
@@ -234,6 +235,11 @@ struct nugpr_ctx {
   bool kd_upper_valid = false, spare_upper_valid = false;
   // the same for the coupling matrix, whose strips pair up when c_paired (set with the work tables)
   bool c_upper_valid = false, spare_c_upper_valid = false, c_paired = false;
+  // K' z_0 of the factored blocks, kept from the base loss: the output-scale and noise evaluations apply
+  // s K_0 + shift I to the same first direction z_0 and get their first product as a combination of Q0v and z_0
+  void* Q0v = nullptr;
+  uint64_t q0_gen = ~0ull;
+  double q0_scale = 1.0, q0_shift = 0.0;
   bool general_route = false;   // take the streamed-K_diag route even where the identity relation holds
   // SPD compensation (eq. (krep)): host copy of the representatives and lambda_0 of the last assembly.
   // Clo holds what fp32 storage of C - lambda_0 I drops: C_exact - lambda_0 I - C_stored, itself in fp32,

@@ -343,6 +343,39 @@ int from_internal(nugpr_ctx* c, const void* src, float* dst, int64_t count, hipS
 // operator applications on internal vector blocks
 // ---------------------------------------------------------------------------
 static int run_project(nugpr_ctx* c, const void* D, int T, hipStream_t s);
+// Q = a Q0 + b D with the reduction that follows a product in the solver (partial as in
+// k_onehot_expand_dot; may be null)
+template <typename VT>
+__global__ __launch_bounds__(256) void k_lincomb_dot(VT* __restrict__ Q, const VT* __restrict__ Q0,
+                                                     const VT* __restrict__ D, double a, double b, int64_t n, int T,
+                                                     double* __restrict__ partial) {
+  __shared__ double red[256];
+  const int rpp = 256 / T;
+  const int tid = threadIdx.x;
+  const int myrow = tid / T, col = tid - myrow * T;
+  const bool live = myrow < rpp;
+  const int64_t rows_per_block = (n + gridDim.x - 1) / gridDim.x;
+  const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
+  const int64_t r1 = r0 + rows_per_block < n ? r0 + rows_per_block : n;
+  double s0 = 0.0;
+  if (live) {
+    for (int64_t p = r0 + myrow; p < r1; p += rpp) {
+      const int64_t idx = p * T + col;
+      const double d = (double)D[idx];
+      const VT qn = (VT)fma(a, (double)Q0[idx], b * d);
+      Q[idx] = qn;
+      s0 = fma(d, (double)qn, s0);
+    }
+  }
+  red[tid] = s0;
+  __syncthreads();
+  if (partial && tid < T) {
+    double sacc = 0.0;
+    for (int k = 0; k < rpp; ++k) sacc += red[k * T + tid];
+    partial[(int64_t)blockIdx.x * MAX_COLS + tid] = sacc;
+  }
+}
+
 static int run_expand(nugpr_ctx* c, void* Q, int T, hipStream_t s, const void* D = nullptr, double* dq_partial = nullptr);
 
 int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s, double* dq_partial, bool* dq_done) {
@@ -352,6 +385,18 @@ int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s, doubl
   // S_j = W_j^T D_j (dense W: in column slabs of W_j^T that are then added up); the projection of z_0, the
   // first direction of every solve on the context's own right-hand sides, is kept with the factor
   const bool s_known = D == c->Z0v && T == L.T && c->z0_ready;
+  // The first direction again, on the blocks whose product with it is kept (base loss of a train step): the
+  // operator is s K_0 + shift I for some other (s, shift), and the product a combination of what is kept.
+  const bool shortcuts = !(c->params.flags & NUGPR_NO_SHORTCUTS);
+  if (s_known && shortcuts && c->q0_gen == c->build_gen && Q != c->Q0v) {
+    const double a = c->op_scale / c->q0_scale, b = c->op_shift - a * c->q0_shift;
+    const int nb = L.n_dot_blocks;
+    if (c->acc64) hipLaunchKernelGGL((k_lincomb_dot<double>), dim3(nb), dim3(256), 0, s, (double*)Q, (const double*)c->Q0v, (const double*)D, a, b, (int64_t)L.n, T, dq_partial);
+    else hipLaunchKernelGGL((k_lincomb_dot<float>), dim3(nb), dim3(256), 0, s, (float*)Q, (const float*)c->Q0v, (const float*)D, a, b, (int64_t)L.n, T, dq_partial);
+    NUGPR_HIP(hipGetLastError());
+    if (dq_done) *dq_done = dq_partial != nullptr;
+    return NUGPR_OK;
+  }
   if (!s_known && (rc = run_project(c, D, T, s))) return rc;
   // only the launch with one column group in fp64 mode reads the lower tiles of the K_ii and of C alone
   if (!(c->acc64 && T >= 2 && T <= 17) && ((rc = ensure_kd_upper(c, s)) || (rc = ensure_c_upper(c, s)))) return rc;
@@ -375,7 +420,15 @@ int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s, doubl
   // Q_i += W_i P_i (and, on request, the partial sums of <d, q> in the same pass)
   const bool fuse = dq_partial && c->onehot;
   if (dq_done) *dq_done = fuse;
-  return run_expand(c, Q, T, s, fuse ? D : nullptr, fuse ? dq_partial : nullptr);
+  if ((rc = run_expand(c, Q, T, s, fuse ? D : nullptr, fuse ? dq_partial : nullptr))) return rc;
+  if (s_known && shortcuts && c->build_gen == c->factor_gen && c->q0_gen != c->build_gen) {
+    const size_t bytes = (size_t)L.n * T * (c->acc64 ? sizeof(double) : sizeof(float));
+    NUGPR_HIP(hipMemcpyAsync(c->Q0v, Q, bytes, hipMemcpyDeviceToDevice, s));
+    c->q0_gen = c->build_gen;
+    c->q0_scale = c->op_scale;
+    c->q0_shift = c->op_shift;
+  }
+  return NUGPR_OK;
 }
 
 // out = a * x  (elementwise over a vector block)
