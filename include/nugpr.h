@@ -74,7 +74,10 @@ enum {
                                   Default: evaluations that differ from the assembled blocks only in the
                                   output scale or the noise reuse them through the linear relations of
                                   Section 3.3 (eqs. (linear2), (linear3)): the operator becomes
-                                  s K_0 + shift I with s = alpha / alpha_0. */
+                                  s K_0 + shift I with s = alpha / alpha_0 (and their first product is taken
+                                  from the base loss's, K' z_0 being linear in s and shift); the two
+                                  assemblies of a central difference in a lengthscale are made in one pass
+                                  into two sets of blocks. */
   ,
   NUGPR_LOGDET_PADE = 8u       /* log-determinant by the paper's own route (Section 3.1, eqs. (PQ), (logdet)):
                                   Q(A) s_i = z_i by batched CG on A = R^-T K' R^-1 (two applications of A per
@@ -164,7 +167,9 @@ const char* nugpr_last_error_string(void);
  * Section 3.3 generalised to r representatives per cluster):
  *   K_ii[p,q] = alpha exp(-1/2 sum_k ((x_pk - x_qk)/ell_k)^2) + sigma^2 [p = q]
  *   C[(i,a),(j,c)] = alpha exp(-1/2 sum_k ((R_iak - R_jck)/ell_k)^2), i != j (no noise).
- * Overwrites the stored K_diag and C; never touches the preconditioner. */
+ * Overwrites the stored K_diag and C; never touches the preconditioner.  Both are symmetric
+ * and the tiles above their diagonals may be left unwritten until an operation needs them
+ * (nugpr_export and the products on widths that read whole rows fill them in first). */
 int nugpr_build_blocks(nugpr_ctx* ctx, const double* theta /*HOST*/, void* stream);
 
 /* Block-Jacobi preconditioner, eq. (cholesky factorization): per cluster
