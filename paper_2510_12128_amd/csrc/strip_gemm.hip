@@ -330,7 +330,11 @@ struct RingCfg {
   static constexpr int LDS_BYTES = STAGES * STAGE_BYTES + 512;             // + slack for reads of unused columns
 };
 
-template <int NG, int RCH, int STAGES_, bool SYM>
+// TC: the number of columns T when it is known at compile time (the usual widths: 16 or 32 probes + y), else
+// 0.  With T a constant the LDS addresses of the vector rows a lane reads in a chunk differ from one base by
+// constants that fit the instructions' offset fields; with T at run time they cost some thirty vector
+// instructions per chunk, on a pipe that the matrix instructions already keep busy half of the time.
+template <int NG, int RCH, int STAGES_, bool SYM, int TC>
 __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(2))) void k_strip_ring(const StripArgs a) {
 #if __HIP_DEVICE_COMPILE__
   typedef RingCfg<NG, RCH, STAGES_> Cfg;
@@ -341,7 +345,7 @@ __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(2))) void k
   const StripItem it = a.items[blockIdx.x];
   const StripPort& pt = a.port[it.port];
   const double* __restrict__ vin = static_cast<const double*>(pt.in);
-  const int T = a.T;
+  const int T = TC > 0 ? TC : a.T;
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int m = lane & 15, kg = lane >> 4;
@@ -478,9 +482,16 @@ __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(2))) void k
 #pragma unroll
     for (int s = 0; s < NSTEP; ++s) {
       // the operand: float4 number `lane` of the (wave, s) fragment, or, for a transposed tile, four floats 64 apart
+      // (the 16-byte read goes through a volatile pointer into LDS: otherwise the compiler merges the two
+      // branches into four 4-byte reads at selected addresses, for both kinds of tile)
       float4 av;
-      if (SYM && tr) av = make_float4(sAt[s * 256], sAt[s * 256 + 64], sAt[s * 256 + 128], sAt[s * 256 + 192]);
-      else av = sAw[s * 64];
+      if (SYM && tr) {
+        av = make_float4(sAt[s * 256], sAt[s * 256 + 64], sAt[s * 256 + 128], sAt[s * 256 + 192]);
+      } else {
+        typedef __attribute__((address_space(3))) const volatile v4f* lds_v4f;
+        const v4f q = *(lds_v4f)(sAw + s * 64);
+        av = make_float4(q[0], q[1], q[2], q[3]);
+      }
       const int k0 = 16 * s + 4 * kg;                         // chunk-local column of av.x
       const double* __restrict__ vr = sV + k0 * T;
       double y[4], b[NG][4];
@@ -602,26 +613,37 @@ int launch_strip(const StripTable& tab, const StripPort& p0, const StripPort& p1
   const int ng = (T - 1 + 15) / 16;
   // the ring kernels use more than the default 64 KiB of dynamic LDS: raise their limit once
   static const hipError_t ring_attr = []() {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_strip_ring<1, RING1_CH, RING1_ST, false>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, Ring1::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_strip_ring<1, RING1_CH, RING1_ST, true>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, Ring1::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_strip_ring<2, RING2_CH, RING2_ST, false>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, Ring2::LDS_BYTES);
+    const void* k1[] = {reinterpret_cast<const void*>(&k_strip_ring<1, RING1_CH, RING1_ST, false, 0>),
+                        reinterpret_cast<const void*>(&k_strip_ring<1, RING1_CH, RING1_ST, true, 0>),
+                        reinterpret_cast<const void*>(&k_strip_ring<1, RING1_CH, RING1_ST, false, 17>),
+                        reinterpret_cast<const void*>(&k_strip_ring<1, RING1_CH, RING1_ST, true, 17>)};
+    const void* k2[] = {reinterpret_cast<const void*>(&k_strip_ring<2, RING2_CH, RING2_ST, false, 0>),
+                        reinterpret_cast<const void*>(&k_strip_ring<2, RING2_CH, RING2_ST, false, 33>)};
+    for (const void* f : k1) {
+      const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, Ring1::LDS_BYTES);
+      if (e != hipSuccess) return e;
+    }
+    for (const void* f : k2) {
+      const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, Ring2::LDS_BYTES);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
   }();
   NUGPR_HIP(ring_attr);
   // Tables with strips of symmetric blocks take the instantiation that pairs their tiles, the others the
   // plain loop.  With two column groups (T > 17) the launch is bound by the matrix cores, the pairing
-  // saves nothing and its operand read costs 6 %: those launches read every strip whole.
+  // saves nothing and its operand read costs 6 %: those launches read every strip whole.  The widths of
+  // 16 and 32 probes have instantiations with T as a constant.
   const dim3 grid(tab.count), block(320);
-  if (acc64 && ng == 1 && tab.sym)
-    hipLaunchKernelGGL((k_strip_ring<1, RING1_CH, RING1_ST, true>), grid, block, Ring1::LDS_BYTES, s, a);
-  else if (acc64 && ng == 1)
-    hipLaunchKernelGGL((k_strip_ring<1, RING1_CH, RING1_ST, false>), grid, block, Ring1::LDS_BYTES, s, a);
-  else if (acc64 && ng == 2)
-    hipLaunchKernelGGL((k_strip_ring<2, RING2_CH, RING2_ST, false>), grid, block, Ring2::LDS_BYTES, s, a);
+  if (acc64 && ng == 1) {
+    if (tab.sym && T == 17) hipLaunchKernelGGL((k_strip_ring<1, RING1_CH, RING1_ST, true, 17>), grid, block, Ring1::LDS_BYTES, s, a);
+    else if (tab.sym) hipLaunchKernelGGL((k_strip_ring<1, RING1_CH, RING1_ST, true, 0>), grid, block, Ring1::LDS_BYTES, s, a);
+    else if (T == 17) hipLaunchKernelGGL((k_strip_ring<1, RING1_CH, RING1_ST, false, 17>), grid, block, Ring1::LDS_BYTES, s, a);
+    else hipLaunchKernelGGL((k_strip_ring<1, RING1_CH, RING1_ST, false, 0>), grid, block, Ring1::LDS_BYTES, s, a);
+  } else if (acc64 && ng == 2) {
+    if (T == 33) hipLaunchKernelGGL((k_strip_ring<2, RING2_CH, RING2_ST, false, 33>), grid, block, Ring2::LDS_BYTES, s, a);
+    else hipLaunchKernelGGL((k_strip_ring<2, RING2_CH, RING2_ST, false, 0>), grid, block, Ring2::LDS_BYTES, s, a);
+  }
   else if (acc64) launch_typed<true>(ng, dim3(tab.count), s, a);
   else launch_typed<false>(ng, dim3(tab.count), s, a);
   NUGPR_HIP(hipGetLastError());
