@@ -287,6 +287,28 @@ int nugpr_profile_enable(nugpr_ctx* ctx, int32_t on);
 int nugpr_profile_read(nugpr_ctx* ctx, double* total_ms /*HOST*/, int32_t* launches /*HOST*/, void* stream);
 double nugpr_profile_bytes(const nugpr_ctx* ctx, int32_t ncols);
 
+/* Name of the kernel instantiation behind that launch for vector blocks of `ncols` columns, as profilers print it
+ * without the namespace (e.g. "k_strip_ring<1, 32, 4, true, 17>"), copied into buf (HOST, at most len bytes
+ * including the terminating zero).  Pure host logic; lets a caller match stored counter readings to the code
+ * that is actually running. */
+int nugpr_profile_kernel_name(const nugpr_ctx* ctx, int32_t ncols, char* buf /*HOST*/, int32_t len);
+
+/* Work counters of a context since nugpr_create or the last reset (host bookkeeping, no GPU work):
+ * what the calls so far did in units of the path's steps (Algorithm 1 / ComputeLoss). */
+typedef struct {
+  int64_t loss_evals;        /* loss evaluations (nugpr_mll, and those inside nugpr_train_step)          */
+  int64_t pcg_solves;        /* batched PCG solves                                                        */
+  int64_t pcg_iterations;    /* iterations summed over the solves (a solve counts its slowest column)     */
+  int64_t pcg_iterations_max;/* most iterations any solve took                                            */
+  int64_t products;          /* applications of K' that streamed K_diag and C                             */
+  int64_t products_reused;   /* applications of K' taken from a kept product through eqs. (linear2), (linear3) */
+  int64_t precond_applies;   /* applications of the block-Jacobi preconditioner                           */
+  int64_t matrices_assembled;/* sets of blocks (K_diag, C) written by the assembly                        */
+  int64_t assembly_passes;   /* assembly passes (a pass over a lengthscale pair writes two sets)          */
+  int64_t factorisations;    /* block-Jacobi factorisations                                               */
+} nugpr_stats;
+int nugpr_stats_read(nugpr_ctx* ctx, nugpr_stats* out /*HOST*/, int32_t reset);
+
 /* A plain device-to-device copy kernel of `bytes` bytes (16-byte loads/stores, both
  * DEVICE pointers 16-byte aligned, bytes a multiple of 16): the known-size dispatch
  * against which hardware HBM byte counters are scaled.  Does not synchronise. */

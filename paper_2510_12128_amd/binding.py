@@ -51,6 +51,12 @@ class MllResult(C.Structure):
                 ("logdet_precond", C.c_double), ("max_iters_used", C.c_int32), ("status", C.c_int32)]
 
 
+class Stats(C.Structure):
+    _fields_ = [(k, C.c_int64) for k in ("loss_evals", "pcg_solves", "pcg_iterations", "pcg_iterations_max",
+                                          "products", "products_reused", "precond_applies",
+                                          "matrices_assembled", "assembly_passes", "factorisations")]
+
+
 _LIB = None
 
 
@@ -115,6 +121,10 @@ def load_library():
     lib.nugpr_profile_read.argtypes = [vp, dp, ip, vp]
     lib.nugpr_profile_bytes.restype = C.c_double
     lib.nugpr_profile_bytes.argtypes = [vp, C.c_int32]
+    lib.nugpr_profile_kernel_name.restype = C.c_int
+    lib.nugpr_profile_kernel_name.argtypes = [vp, C.c_int32, C.c_char_p, C.c_int32]
+    lib.nugpr_stats_read.restype = C.c_int
+    lib.nugpr_stats_read.argtypes = [vp, C.POINTER(Stats), C.c_int32]
     lib.nugpr_copy_probe.restype = C.c_int
     lib.nugpr_copy_probe.argtypes = [vp, vp, C.c_size_t, vp]
     _LIB = lib
@@ -352,6 +362,16 @@ class Context:
 
     def nugpr_profile_bytes(self, ncols):
         return float(self.lib.nugpr_profile_bytes(self.handle, int(ncols)))
+
+    def nugpr_profile_kernel_name(self, ncols):
+        buf = C.create_string_buffer(128)
+        _check(self.lib.nugpr_profile_kernel_name(self.handle, int(ncols), buf, 128))
+        return buf.value.decode()
+
+    def nugpr_stats_read(self, reset=False):
+        st = Stats()
+        _check(self.lib.nugpr_stats_read(self.handle, C.byref(st), 1 if reset else 0))
+        return {k: int(getattr(st, k)) for k, _ in Stats._fields_}
 
     def nugpr_export(self, what, index=0):
         if what in (EXPORT_K, EXPORT_L, EXPORT_LINV):

@@ -419,6 +419,21 @@ double nugpr_profile_bytes(const nugpr_ctx* c, int32_t ncols) {
   return 4.0 * entries + vec;
 }
 
+int nugpr_profile_kernel_name(const nugpr_ctx* c, int32_t ncols, char* buf, int32_t len) {
+  if (!c || !buf || len < 1 || ncols < 1 || ncols > MAX_COLS) { set_error("bad argument"); return NUGPR_ERR_INVALID; }
+  const char* name = strip_kernel_name(c->tab_KC, ncols, c->acc64);
+  std::strncpy(buf, name, (size_t)len - 1);
+  buf[len - 1] = 0;
+  return NUGPR_OK;
+}
+
+int nugpr_stats_read(nugpr_ctx* c, nugpr_stats* out, int32_t reset) {
+  if (!c || !out) { set_error("null argument"); return NUGPR_ERR_INVALID; }
+  *out = c->stats;
+  if (reset) c->stats = nugpr_stats{};
+  return NUGPR_OK;
+}
+
 int nugpr_destroy(nugpr_ctx* c) {
   if (!c) return NUGPR_OK;
   for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
@@ -467,6 +482,9 @@ int nugpr_matvec(nugpr_ctx* c, const float* D, float* Q, int32_t ncols, void* st
   if (!c->built) { set_error("matvec needs build_blocks first"); return NUGPR_ERR_STATE; }
   hipStream_t s = as_stream(stream);
   if (!c->acc64) return run_matvec(c, D, Q, ncols, s);
+  // default basis: the projection widens D into the solver's fp64 block while it gathers it, and the expansion
+  // writes the fp32 result: three launches (four when the coupling product is summed over column slabs)
+  if (c->onehot) return run_matvec(c, c->Dv, c->Qv, ncols, s, nullptr, nullptr, D, Q);
   const int64_t cnt = c->L.n * ncols;
   if ((rc = to_internal(c, D, c->Dv, cnt, s))) return rc;
   if ((rc = run_matvec(c, c->Dv, c->Qv, ncols, s))) return rc;
@@ -592,6 +610,7 @@ static int mll_impl(nugpr_ctx* c, const double* theta, nugpr_mll_result* res, bo
   if (!theta) { set_error("theta is null"); return NUGPR_ERR_INVALID; }
   int rc = set_operator(c, theta, allow_reuse, s);
   if (rc) return rc;
+  c->stats.loss_evals += 1;
   if (c->params.flags & NUGPR_LOGDET_PADE) return mll_pade(c, res, s);
   const int T = L.T, max_iter = c->params.max_iter;
   std::vector<int32_t> iters(T);

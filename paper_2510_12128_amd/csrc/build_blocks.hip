@@ -578,6 +578,8 @@ static int build_impl(nugpr_ctx* c, const double* theta, hipStream_t s, bool nee
   c->built = true;
   c->kd_upper_valid = need_upper;
   c->build_gen += 1;
+  c->stats.assembly_passes += 1;
+  c->stats.matrices_assembled += pair ? 2 : 1;
   return NUGPR_OK;
 }
 

@@ -533,6 +533,7 @@ int launch_factor(nugpr_ctx* c, hipStream_t s) {
   if ((rc = store_known_starts(c, s))) return rc;
   c->z0_ready = true;
   c->factor_gen = c->build_gen;
+  c->stats.factorisations += 1;
   return NUGPR_OK;
 }
 

@@ -247,6 +247,7 @@ struct nugpr_ctx {
   std::vector<double> h_reps;
   double lambda0 = 0.0;
   float* Clo = nullptr;
+  nugpr_stats stats{};                   // work counters (nugpr_stats_read)
   std::vector<int32_t> fd_halvings;      // halvings per hyperparameter in the last forward-difference step
   double logdetM = 0.0;
 };
@@ -286,6 +287,9 @@ int launch_export(nugpr_ctx* c, int what, int index, float* dst, int64_t ld, hip
 int launch_strip(const StripTable& tab, const StripPort& p0, const StripPort& p1, int T, bool acc64,
                  hipStream_t s);
 
+// name of the kernel instantiation launch_strip picks for such a table and width (profilers' spelling, no namespace)
+const char* strip_kernel_name(const StripTable& tab, int T, bool acc64);
+
 int launch_sum_parts(const void* in, void* out, int64_t count, int parts, uint64_t stride, bool acc64,
                      hipStream_t s);
 
@@ -296,8 +300,11 @@ int launch_factor(nugpr_ctx* c, hipStream_t s);
 // (vector blocks are the context's internal type: fp64 when acc64, else fp32)
 // (dq_partial: if not null and the basis is one-hot, the per-workgroup sums of <d, q> per column are left
 // there by the product's last kernel, in the layout of the solver's dot products; returns 1 in *dq_done then)
+// (D32 / Q32, one-hot basis in fp64 mode only: the block is read from the fp32 array D32, its widened copy
+// being left in D by the product's first kernel, and the result is written to the fp32 array Q32 by its last
+// one, Q holding the block-diagonal part only: a caller's fp32 blocks then cost no conversion passes)
 int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s, double* dq_partial = nullptr,
-               bool* dq_done = nullptr);
+               bool* dq_done = nullptr, const float* D32 = nullptr, float* Q32 = nullptr);
 int run_precond(nugpr_ctx* c, const void* R, void* Z, int T, hipStream_t s);
 // What a loss evaluation needs besides the solution, fetched with the solve's last synchronisation:
 // <b_c, x_c> per column and rho_0 = <r_0, M^-1 r_0>.

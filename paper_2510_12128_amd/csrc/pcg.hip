@@ -342,7 +342,7 @@ int from_internal(nugpr_ctx* c, const void* src, float* dst, int64_t count, hipS
 // ---------------------------------------------------------------------------
 // operator applications on internal vector blocks
 // ---------------------------------------------------------------------------
-static int run_project(nugpr_ctx* c, const void* D, int T, hipStream_t s);
+static int run_project(nugpr_ctx* c, const void* D, int T, hipStream_t s, const float* D32 = nullptr);
 // Q = a Q0 + b D with the reduction that follows a product in the solver (partial as in
 // k_onehot_expand_dot; may be null)
 template <typename VT>
@@ -376,15 +376,17 @@ __global__ __launch_bounds__(256) void k_lincomb_dot(VT* __restrict__ Q, const V
   }
 }
 
-static int run_expand(nugpr_ctx* c, void* Q, int T, hipStream_t s, const void* D = nullptr, double* dq_partial = nullptr);
+static int run_expand(nugpr_ctx* c, void* Q, int T, hipStream_t s, const void* D = nullptr, double* dq_partial = nullptr,
+                      float* Q32 = nullptr);
 
-int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s, double* dq_partial, bool* dq_done) {
+int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s, double* dq_partial, bool* dq_done,
+               const float* D32, float* Q32) {
   const Layout& L = c->L;
   int rc;
   const uint64_t ppart = (uint64_t)L.ncr * T;
   // S_j = W_j^T D_j (dense W: in column slabs of W_j^T that are then added up); the projection of z_0, the
   // first direction of every solve on the context's own right-hand sides, is kept with the factor
-  const bool s_known = D == c->Z0v && T == L.T && c->z0_ready;
+  const bool s_known = D == c->Z0v && T == L.T && c->z0_ready && !D32;
   // The first direction again, on the blocks whose product with it is kept (base loss of a train step): the
   // operator is s K_0 + shift I for some other (s, shift), and the product a combination of what is kept.
   const bool shortcuts = !(c->params.flags & NUGPR_NO_SHORTCUTS);
@@ -395,9 +397,11 @@ int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s, doubl
     else hipLaunchKernelGGL((k_lincomb_dot<float>), dim3(nb), dim3(256), 0, s, (float*)Q, (const float*)c->Q0v, (const float*)D, a, b, (int64_t)L.n, T, dq_partial);
     NUGPR_HIP(hipGetLastError());
     if (dq_done) *dq_done = dq_partial != nullptr;
+    c->stats.products_reused += 1;
     return NUGPR_OK;
   }
-  if (!s_known && (rc = run_project(c, D, T, s))) return rc;
+  c->stats.products += 1;
+  if (!s_known && (rc = run_project(c, D, T, s, D32))) return rc;
   // only the launch with one column group in fp64 mode reads the lower tiles of the K_ii and of C alone
   if (!(c->acc64 && T >= 2 && T <= 17) && ((rc = ensure_kd_upper(c, s)) || (rc = ensure_c_upper(c, s)))) return rc;
   // Q_i = K_ii D_i   and   P = C_offdiag S (column slabs), one launch
@@ -420,7 +424,7 @@ int run_matvec(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s, doubl
   // Q_i += W_i P_i (and, on request, the partial sums of <d, q> in the same pass)
   const bool fuse = dq_partial && c->onehot;
   if (dq_done) *dq_done = fuse;
-  if ((rc = run_expand(c, Q, T, s, fuse ? D : nullptr, fuse ? dq_partial : nullptr))) return rc;
+  if ((rc = run_expand(c, Q, T, s, fuse ? D : nullptr, fuse ? dq_partial : nullptr, Q32))) return rc;
   if (s_known && shortcuts && c->build_gen == c->factor_gen && c->q0_gen != c->build_gen) {
     const size_t bytes = (size_t)L.n * T * (c->acc64 ? sizeof(double) : sizeof(float));
     NUGPR_HIP(hipMemcpyAsync(c->Q0v, Q, bytes, hipMemcpyDeviceToDevice, s));
@@ -455,8 +459,12 @@ static int scaled_copy(void* out, const void* x, double a, int64_t count, hipStr
 // One-hot basis (every point belongs to exactly one representative): S = W^T D is the sum of the rows of
 // D over each representative's points, taken in ascending point order; Q += W P adds row assign[p] of P to
 // row p.  Neither streams the dense W.
-template <typename VT>
-__global__ __launch_bounds__(256) void k_onehot_project(const VT* __restrict__ D, const int32_t* __restrict__ rep_ptr,
+// ST: type of the block that is read.  Dwide (may be null): every point belongs to exactly one representative,
+// so the gather visits every row of D once and can leave a copy of it in the solver's own type on the way
+// (the widening of a caller's fp32 block, which the strip kernels then read, costs no pass of its own).
+template <typename VT, typename ST>
+__global__ __launch_bounds__(256) void k_onehot_project(const ST* __restrict__ D, VT* __restrict__ Dwide,
+                                                        const int32_t* __restrict__ rep_ptr,
                                                         const int32_t* __restrict__ rep_pts, VT* __restrict__ S,
                                                         int ncr, int T) {
   const int rpp = 256 / T;
@@ -474,6 +482,11 @@ __global__ __launch_bounds__(256) void k_onehot_project(const VT* __restrict__ D
       for (int j = 0; j < 8; ++j) idx[j] = rep_pts[q + j < q1 ? q + j : q1 - 1];
 #pragma unroll
       for (int j = 0; j < 8; ++j) v[j] = (double)D[(int64_t)idx[j] * T + col];
+      if (Dwide) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (q + j < q1) Dwide[(int64_t)idx[j] * T + col] = (VT)v[j];
+      }
 #pragma unroll
       for (int j = 0; j < 8; ++j) s += q + j < q1 ? v[j] : 0.0;
     }
@@ -481,16 +494,18 @@ __global__ __launch_bounds__(256) void k_onehot_project(const VT* __restrict__ D
   }
 }
 
-template <typename VT>
-__global__ __launch_bounds__(256) void k_onehot_expand(VT* __restrict__ Q, const VT* __restrict__ P,
-                                                       const int32_t* __restrict__ assign, int64_t n, int T) {
+// out = Q + W P: out is Q itself, or the caller's fp32 block (the narrowing then costs no pass of its own)
+template <typename VT, typename OT>
+__global__ __launch_bounds__(256) void k_onehot_expand(const VT* Q, const VT* __restrict__ P,
+                                                       const int32_t* __restrict__ assign, int64_t n, int T,
+                                                       OT* out) {
   const int rpp = 256 / T;
   const int tid = threadIdx.x;
   const int myrow = tid / T, col = tid - myrow * T;
   if (myrow >= rpp) return;
   for (int64_t p = (int64_t)blockIdx.x * rpp + myrow; p < n; p += (int64_t)gridDim.x * rpp) {
     const int64_t idx = p * T + col;
-    Q[idx] = (VT)((double)Q[idx] + (double)P[(int64_t)assign[p] * T + col]);
+    out[idx] = (OT)((double)Q[idx] + (double)P[(int64_t)assign[p] * T + col]);
   }
 }
 
@@ -529,13 +544,16 @@ __global__ __launch_bounds__(256) void k_onehot_expand_dot(VT* __restrict__ Q, c
 
 static int elementwise_grid(int64_t n, int T);
 
-// S = W^T D into the first slab of Spart (summed over the column slabs when W is dense)
-static int run_project(nugpr_ctx* c, const void* D, int T, hipStream_t s) {
+// S = W^T D into the first slab of Spart (summed over the column slabs when W is dense).  D32 (one-hot basis,
+// fp64 mode only): the block is read from this fp32 array and its widened copy is written to D on the way.
+static int run_project(nugpr_ctx* c, const void* D, int T, hipStream_t s, const float* D32) {
   const Layout& L = c->L;
+  if (D32 && !(c->onehot && c->acc64)) { set_error("internal: fused widening needs the one-hot basis in fp64 mode"); return NUGPR_ERR_INVALID; }
   if (c->onehot) {
     const int grid = elementwise_grid(L.ncr, T);
-    if (c->acc64) hipLaunchKernelGGL((k_onehot_project<double>), dim3(grid), dim3(256), 0, s, (const double*)D, c->rep_ptr, c->rep_pts, (double*)c->Spart, L.ncr, T);
-    else hipLaunchKernelGGL((k_onehot_project<float>), dim3(grid), dim3(256), 0, s, (const float*)D, c->rep_ptr, c->rep_pts, (float*)c->Spart, L.ncr, T);
+    if (D32) hipLaunchKernelGGL((k_onehot_project<double, float>), dim3(grid), dim3(256), 0, s, D32, (double*)const_cast<void*>(D), c->rep_ptr, c->rep_pts, (double*)c->Spart, L.ncr, T);
+    else if (c->acc64) hipLaunchKernelGGL((k_onehot_project<double, double>), dim3(grid), dim3(256), 0, s, (const double*)D, (double*)nullptr, c->rep_ptr, c->rep_pts, (double*)c->Spart, L.ncr, T);
+    else hipLaunchKernelGGL((k_onehot_project<float, float>), dim3(grid), dim3(256), 0, s, (const float*)D, (float*)nullptr, c->rep_ptr, c->rep_pts, (float*)c->Spart, L.ncr, T);
     NUGPR_HIP(hipGetLastError());
     return NUGPR_OK;
   }
@@ -548,9 +566,10 @@ static int run_project(nugpr_ctx* c, const void* D, int T, hipStream_t s) {
   return NUGPR_OK;
 }
 
-// Q += W P with P the first slab of Ppart
-static int run_expand(nugpr_ctx* c, void* Q, int T, hipStream_t s, const void* D, double* dq_partial) {
+// Q += W P with P the first slab of Ppart; with Q32 (one-hot basis, fp64 mode) the sum goes to that fp32 array instead
+static int run_expand(nugpr_ctx* c, void* Q, int T, hipStream_t s, const void* D, double* dq_partial, float* Q32) {
   const Layout& L = c->L;
+  if (Q32 && !(c->onehot && c->acc64 && !dq_partial)) { set_error("internal: fused narrowing needs the one-hot basis in fp64 mode"); return NUGPR_ERR_INVALID; }
   if (c->onehot && dq_partial) {
     const int nb = L.n_dot_blocks;
     if (c->acc64) hipLaunchKernelGGL((k_onehot_expand_dot<double>), dim3(nb), dim3(256), 0, s, (double*)Q, (const double*)c->Ppart, c->assign, (const double*)D, (int64_t)L.n, T, dq_partial);
@@ -560,8 +579,9 @@ static int run_expand(nugpr_ctx* c, void* Q, int T, hipStream_t s, const void* D
   }
   if (c->onehot) {
     const int grid = elementwise_grid(L.n, T);
-    if (c->acc64) hipLaunchKernelGGL((k_onehot_expand<double>), dim3(grid), dim3(256), 0, s, (double*)Q, (const double*)c->Ppart, c->assign, (int64_t)L.n, T);
-    else hipLaunchKernelGGL((k_onehot_expand<float>), dim3(grid), dim3(256), 0, s, (float*)Q, (const float*)c->Ppart, c->assign, (int64_t)L.n, T);
+    if (Q32) hipLaunchKernelGGL((k_onehot_expand<double, float>), dim3(grid), dim3(256), 0, s, (const double*)Q, (const double*)c->Ppart, c->assign, (int64_t)L.n, T, Q32);
+    else if (c->acc64) hipLaunchKernelGGL((k_onehot_expand<double, double>), dim3(grid), dim3(256), 0, s, (const double*)Q, (const double*)c->Ppart, c->assign, (int64_t)L.n, T, (double*)Q);
+    else hipLaunchKernelGGL((k_onehot_expand<float, float>), dim3(grid), dim3(256), 0, s, (const float*)Q, (const float*)c->Ppart, c->assign, (int64_t)L.n, T, (float*)Q);
     NUGPR_HIP(hipGetLastError());
     return NUGPR_OK;
   }
@@ -631,6 +651,7 @@ static int run_pade_q(nugpr_ctx* c, const void* D, void* Q, int T, hipStream_t s
 
 int run_precond(nugpr_ctx* c, const void* R, void* Z, int T, hipStream_t s) {
   int rc;
+  c->stats.precond_applies += 1;
   StripPort a{};
   a.A = c->G; a.in = R; a.out = c->Vv; a.nin = 1;
   if ((rc = launch_strip(c->tab_lowG, a, a, T, c->acc64, s))) return rc;
@@ -764,6 +785,9 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
     Dcur = D;
   }
   c->expect_iters[plain ? 1 : 0] = it > 0 ? it : 1;
+  c->stats.pcg_solves += 1;
+  c->stats.pcg_iterations += it;
+  c->stats.pcg_iterations_max = std::max<int64_t>(c->stats.pcg_iterations_max, it);
   if (!tail_current && (rc = issue_tail(it, false))) return rc;
   if ((rc = wait_seq(&c->h_flags->tail_seq, c->tail_seq, s))) return rc;
   bool all_conv = true;

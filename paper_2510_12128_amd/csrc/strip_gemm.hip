@@ -592,6 +592,20 @@ constexpr int RING1_CH = 32, RING1_ST = 4, RING2_CH = 32, RING2_ST = 3;     // c
 typedef RingCfg<1, RING1_CH, RING1_ST> Ring1;
 typedef RingCfg<2, RING2_CH, RING2_ST> Ring2;
 
+const char* strip_kernel_name(const StripTable& tab, int T, bool acc64) {
+  const int ng = (T - 1 + 15) / 16;
+  if (acc64 && ng == 1) {
+    if (tab.sym && T == 17) return "k_strip_ring<1, 32, 4, true, 17>";
+    if (tab.sym) return "k_strip_ring<1, 32, 4, true, 0>";
+    if (T == 17) return "k_strip_ring<1, 32, 4, false, 17>";
+    return "k_strip_ring<1, 32, 4, false, 0>";
+  }
+  if (acc64 && ng == 2) return T == 33 ? "k_strip_ring<2, 32, 3, false, 33>" : "k_strip_ring<2, 32, 3, false, 0>";
+  if (acc64) return ng == 0 ? "k_strip<0, true>" : (ng == 1 ? "k_strip<1, true>" : "k_strip<2, true>");
+  return ng == 0 ? "k_strip<0, false>" : (ng == 1 ? "k_strip<1, false>" : "k_strip<2, false>");
+}
+static_assert(RING1_CH == 32 && RING1_ST == 4 && RING2_CH == 32 && RING2_ST == 3, "strip_kernel_name spells these out");
+
 template <bool ACC64>
 static void launch_typed(int ng, dim3 grid, hipStream_t s, const StripArgs& a) {
   dim3 block(256);
