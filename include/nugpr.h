@@ -60,7 +60,12 @@ enum {
   /* numerical status */
   NUGPR_NOT_PD = 1,            /* a diagonal block failed Cholesky (Section 3.3: not SPD) */
   NUGPR_INDEFINITE = 2,        /* PCG met <d, K'd> <= 0: the approximated K' is not SPD */
-  NUGPR_NOT_CONVERGED = 3      /* max_iter reached before every column met the tolerance */
+  NUGPR_NOT_CONVERGED = 3,     /* max_iter reached before every column met the tolerance */
+  NUGPR_NOT_FINITE = 4         /* NaN or Inf in the inputs: among the coordinates (X, representatives), found
+                                  when the blocks are assembled and reported by precond_factor and by every
+                                  solve on those blocks; or in a right-hand side (e.g. y), found in the first
+                                  dot products of the solve, <b, b> and <b, M^-1 b>.  The outputs of the
+                                  affected columns are not meaningful and a loss is returned as NaN */
 };
 
 enum {
@@ -95,9 +100,14 @@ enum {
   NUGPR_COMPENSATE = 32u       /* the operator is the compensated K'' = K_diag + W (C - lambda_0 I) W^T of
                                   Section 3.3 (eqs. (krep), (kypp)), positive definite by construction:
                                   C is the full kernel matrix of the representatives (its diagonal blocks
-                                  included) and lambda_0 its smallest eigenvalue, computed on the host in
-                                  fp64 at every assembly (dense symmetric eigen-solve).  Supported for
-                                  n_clusters * rank <= 512, the paper's regime (n_c <= 20, rank 1).
+                                  included) and lambda_0 its smallest eigenvalue, computed in fp64 at every
+                                  assembly: by a dense symmetric eigen-solve on the host for
+                                  n_clusters * rank <= 512 (the paper's regime: n_c <= 20, rank 1), beyond that
+                                  by a matrix-free, block-preconditioned eigenvalue iteration on the device
+                                  over the assembled matrix, to 2e-11 alpha (default arithmetic mode only).  If
+                                  its cap of 150 steps is reached, an estimate below 1e-5 alpha is used as it
+                                  stands (lambda_min then lies between 0 and the estimate: a kernel matrix is
+                                  positive semi-definite); otherwise the assembly returns NUGPR_ERR_INVALID.
                                   Default: the uncompensated K' of eq. (odsplit). */
 };
 
@@ -201,8 +211,8 @@ int nugpr_split_apply(nugpr_ctx* ctx, const float* D, float* out, int32_t ncols,
  * from X = 0, preconditioned by the stored factor, until every column meets the
  * tolerance or max_iter.  B, Xout: DEVICE n x ncols.  iters: HOST ncols (iterations
  * each column ran).  alpha, beta: HOST max_iter*ncols row-major CG coefficients
- * (zero past a column's count), or NULL.  Returns NUGPR_OK, NUGPR_INDEFINITE or
- * NUGPR_NOT_CONVERGED (Xout is written in every case). */
+ * (zero past a column's count), or NULL.  Returns NUGPR_OK, NUGPR_INDEFINITE,
+ * NUGPR_NOT_CONVERGED or NUGPR_NOT_FINITE (Xout is written in every case). */
 int nugpr_pcg_solve(nugpr_ctx* ctx, const float* B, float* Xout, int32_t ncols,
                     int32_t* iters, double* alpha, double* beta, void* stream);
 
@@ -251,6 +261,9 @@ int nugpr_confidence_band(const double* mean, const double* var, int64_t m, doub
 
 /* lambda_0 of eq. (krep) at the last assembly of a NUGPR_COMPENSATE context (HOST double out). */
 int nugpr_compensation_lambda(const nugpr_ctx* ctx, double* out /*HOST*/);
+
+/* Steps the device iteration for that lambda_0 took (0: it came from the dense host eigen-solve). */
+int nugpr_compensation_steps(const nugpr_ctx* ctx, int32_t* out /*HOST*/);
 
 /* Smallest eigenvalue of a dense symmetric n x n matrix A (HOST, row-major fp64, not modified; only
  * its lower triangle and diagonal are meaningful as a symmetric matrix): the host routine behind

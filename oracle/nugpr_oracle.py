@@ -19,7 +19,9 @@ What each function follows:
   coupling            K_rep of Section 3.3 generalised to r points per cluster
   dense_K/apply_K     the approximated covariance, eq. (odblock)/(odsplit); with a
                       compensation lambda_0 the SPD form of eqs. (krep), (kypp)
-  compensation_lambda lambda_0 of eq. (krep)
+  compensation_lambda lambda_0 of eq. (krep); compensation_lambda_iterative: the same number by a
+                      block-preconditioned Davidson iteration, for matrices beyond a dense eigen-solve
+                      (pinned against the former)
   precond_factor      eq. (cholesky factorization); R_i = L_i^T
   pcg                 batched preconditioned CG, Sections 3.1-3.2
   slq_logdet          eq. (log to trace), (trace estimation), (logdet) with the
@@ -160,6 +162,69 @@ def coupling(reps, theta):
 def compensation_lambda(C):
     """lambda_0 of eq. (krep): the smallest eigenvalue of the representatives' kernel matrix."""
     return float(np.linalg.eigvalsh(C)[0])
+
+
+def compensation_lambda_iterative(C, rel_tol=2e-11, block=128, max_basis=24, keep=3, max_steps=150, psd_tol=1e-5):
+    """lambda_0 of eq. (krep) without a dense eigen-solve (the route open to a matrix too large for one):
+    generalised Davidson iteration for the smallest eigenvalue.  The low end of the spectrum of a kernel
+    matrix of clustered representatives is a dense cluster of small eigenvalues that a plain Krylov process
+    resolves only after thousands of steps; those eigenvalues come from within the diagonal blocks, so the
+    inverse of a block-diagonal part, T = blockdiag(C_kk + mu I)^-1 with blocks of `block` consecutive indices,
+    is the preconditioner.  Steps: Rayleigh-Ritz on an orthonormal basis V (thick restart to `keep` vectors at
+    `max_basis`), residual res = C x - theta x, new direction T res orthogonalised against V.  Stop when
+    min(|res|, 4 |res|^2 / gap) <= rel_tol * C[0, 0] (gap to the second Ritz value when clearly separate), or
+    |theta| <= that tolerance (a kernel matrix is positive semi-definite: lambda_min lies in [0, theta]).
+    If max_steps is reached, a theta below psd_tol * C[0, 0] is returned as it stands (same argument: the
+    error is at most theta); a larger one raises.  Returns (theta, steps).  Pinned against eigvalsh."""
+    n = C.shape[0]
+    alpha = abs(C[0, 0])
+    tol = rel_tol * alpha
+    facs = []
+    for k0 in range(0, n, block):
+        B = C[k0:k0 + block, k0:k0 + block]
+        facs.append(cholesky(B + 1e-10 * alpha * np.eye(B.shape[0]), lower=True))
+    idx = np.arange(n, dtype=np.uint64)
+    h = (idx * np.uint64(2654435761)) & np.uint64(0xFFFFFFFF)
+    h ^= h >> np.uint64(15)
+    h = (h * np.uint64(2246822519)) & np.uint64(0xFFFFFFFF)
+    h ^= h >> np.uint64(13)
+    v = np.where(h & np.uint64(1), 1.0, -1.0) / np.sqrt(n)
+    V, AV = [v], [C @ v]
+    for step in range(max_steps):
+        Vm, AVm = np.array(V).T, np.array(AV).T
+        H = Vm.T @ AVm
+        ev, Y = np.linalg.eigh(0.5 * (H + H.T))
+        if len(V) == max_basis:
+            V = [Vm @ Y[:, q] for q in range(keep)]
+            AV = [AVm @ Y[:, q] for q in range(keep)]
+            Vm, AVm = np.array(V).T, np.array(AV).T
+            ev, Y = ev[:keep], np.eye(keep)
+        theta, y = ev[0], Y[:, 0]
+        res = AVm @ y - theta * (Vm @ y)
+        rn = float(np.linalg.norm(res))
+        est = rn
+        if len(V) > 1 and ev[1] - ev[0] > 10.0 * rn:
+            est = min(est, 4.0 * rn * rn / (ev[1] - ev[0]))
+        if est <= tol or abs(theta) <= tol:
+            return float(theta), step + 1
+        t = np.empty(n)
+        for k, L in enumerate(facs):
+            sl = slice(k * block, min((k + 1) * block, n))
+            t[sl] = solve_triangular(L, solve_triangular(L, res[sl], lower=True), lower=True, trans="T")
+        for _ in range(2):
+            for u in V:
+                t -= (u @ t) * u
+        nt = float(np.linalg.norm(t))
+        if nt <= 1e-300:
+            if est <= 1e3 * tol:
+                return float(theta), step + 1
+            break
+        t /= nt
+        V.append(t)
+        AV.append(C @ t)
+    if abs(theta) <= psd_tol * alpha:
+        return float(theta), max_steps
+    raise ValueError("lambda_0 iteration not converged")
 
 
 def dense_K(blocks, Ws, C, offsets, r, lam0=None):

@@ -17,6 +17,7 @@ NUGPR_ERR_STATE = -4
 NUGPR_NOT_PD = 1
 NUGPR_INDEFINITE = 2
 NUGPR_NOT_CONVERGED = 3
+NUGPR_NOT_FINITE = 4
 NUGPR_ISOTROPIC = 1
 NUGPR_ACC_FP32 = 2
 NUGPR_NO_SHORTCUTS = 4
@@ -107,6 +108,8 @@ def load_library():
     lib.nugpr_confidence_band.argtypes = [dp, dp, C.c_int64, dp, dp]
     lib.nugpr_compensation_lambda.restype = C.c_int
     lib.nugpr_compensation_lambda.argtypes = [vp, dp]
+    lib.nugpr_compensation_steps.restype = C.c_int
+    lib.nugpr_compensation_steps.argtypes = [vp, ip]
     lib.nugpr_host_smallest_eigenvalue.restype = C.c_int
     lib.nugpr_host_smallest_eigenvalue.argtypes = [dp, C.c_int32, dp]
     lib.nugpr_fd_halvings.restype = C.c_int
@@ -337,6 +340,11 @@ class Context:
     def nugpr_compensation_lambda(self):
         out = C.c_double()
         _check(self.lib.nugpr_compensation_lambda(self.handle, C.byref(out)))
+        return out.value
+
+    def nugpr_compensation_steps(self):
+        out = C.c_int32()
+        _check(self.lib.nugpr_compensation_steps(self.handle, C.byref(out)))
         return out.value
 
     def nugpr_fd_halvings(self):

@@ -162,6 +162,9 @@ void build_tables(const Layout& L, Tables& t) {
       StripItem it = make_item((uint64_t)rs * TILE * L.ldc, (uint32_t)L.ldc, nrows, cb, std::max(cb, ce), 0, rs * TILE,
                                rs * TILE, k, 1, 0, 0.f);
       it.blocked = 1;
+      // the item whose columns hold the strip's own rows adds the port's scalar diagonal (used when the diagonal
+      // of the matrix is carried as an exact scalar: the eigenvalue iteration for lambda_0)
+      it.diag_add = (rs / cpp == (uint32_t)k) ? 1.f : 0.f;
       if (pairing && (uint32_t)k < ngroups) {
         const uint32_t I = rs / cpp, na = std::min<uint32_t>(cpp, chunks - I * cpp), jr = rs - I * cpp;
         const uint32_t kind = I == (uint32_t)k ? 0u : (I > (uint32_t)k ? 1u : 2u);
@@ -235,8 +238,8 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   Layout L;
   int rc = plan_layout(pb, prm->flags, L);
   if (rc) return rc;
-  if (L.compensate && L.ncr > 512) {
-    set_error("NUGPR_COMPENSATE supports n_clusters * rank <= 512 (lambda_0 is a dense host eigen-solve)");
+  if (L.compensate && L.ncr > COMPENSATE_HOST_MAX && (prm->flags & NUGPR_ACC_FP32)) {
+    set_error("NUGPR_COMPENSATE with n_clusters * rank > 512 needs the default (fp64) arithmetic mode");
     return NUGPR_ERR_INVALID;
   }
   if (!pb->X || !pb->y || (pb->n_probes > 0 && !pb->probes)) { set_error("X, y or probes is null"); return NUGPR_ERR_INVALID; }
@@ -271,7 +274,8 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   c->Kd2 = reinterpret_cast<float*>(w + L.o_Kd2);
   c->Q0v = w + L.o_Q0;
   c->C2 = reinterpret_cast<float*>(w + L.o_C2);
-  c->Clo = L.compensate ? reinterpret_cast<float*>(w + L.o_Clo) : nullptr;
+  c->Clo = !L.compensate ? nullptr : (L.ncr <= COMPENSATE_HOST_MAX ? reinterpret_cast<float*>(w + L.o_Clo) : c->C2);
+  c->dav = L.ncr > COMPENSATE_HOST_MAX ? reinterpret_cast<double*>(w + L.o_dav) : nullptr;
   c->Wd = reinterpret_cast<float*>(w + L.o_Wd);
   c->Wt = reinterpret_cast<float*>(w + L.o_Wt);
   c->reps = reinterpret_cast<float*>(w + L.o_reps);
@@ -353,7 +357,7 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
     if (e != hipSuccess) return fail(hip_fail(e, "upload the basis lists"));
     c->onehot = true;
   }
-  if (L.compensate) {
+  if (L.compensate && L.ncr <= COMPENSATE_HOST_MAX) {
     // lambda_0 is computed on the host from the representatives themselves, in fp64
     std::vector<float> hr((size_t)L.ncr * L.d);
     e = hipMemcpy(hr.data(), c->reps, hr.size() * sizeof(float), hipMemcpyDeviceToHost);
@@ -465,7 +469,9 @@ int nugpr_precond_factor(nugpr_ctx* c, double* logdet_M, int32_t* bad_cluster, v
   if (logdet_M) *logdet_M = acc;
   const bool bad = hs->bad_cluster != std::numeric_limits<int>::max();
   if (bad_cluster) *bad_cluster = bad ? hs->bad_cluster : -1;
-  c->factored = !bad;
+  const bool nonfinite = c->assembly_mark != 0 && hs->nonfinite_mark == c->assembly_mark;
+  c->factored = !bad && !nonfinite;
+  if (nonfinite) return NUGPR_NOT_FINITE;        // NaN / Inf among the coordinates the blocks were assembled from
   return bad ? NUGPR_NOT_PD : NUGPR_OK;
 }
 
@@ -537,6 +543,9 @@ int nugpr_pcg_solve(nugpr_ctx* c, const float* B, float* Xout, int32_t ncols, in
   return status;
 }
 
+// statuses after which a loss has no value: negative errors, an indefinite operator, non-finite inputs
+static inline bool no_value(int rc) { return rc < 0 || rc == NUGPR_INDEFINITE || rc == NUGPR_NOT_FINITE; }
+
 // The operator of a loss evaluation at theta.  If the stored blocks were assembled with the same
 // lengthscales, nothing is assembled: with s = alpha / alpha_0,
 //   K_ii(theta) = s K_ii(theta_0) + (sigma^2 - s sigma_0^2) I,   C(theta) = s C(theta_0)
@@ -573,7 +582,7 @@ static int mll_pade(nugpr_ctx* c, nugpr_mll_result* res, hipStream_t s) {
   if (rc < 0) return rc;
   res->max_iters_used = mx;
   res->status = rc;
-  if (rc == NUGPR_INDEFINITE) return rc;
+  if (no_value(rc)) return rc;
   res->quad = ex.bx[0];
   int worst = rc;
   double est = 0.0;
@@ -581,7 +590,7 @@ static int mll_pade(nugpr_ctx* c, nugpr_mll_result* res, hipStream_t s) {
     rc = run_pcg(c, c->Pv, c->Xv, T, nullptr, nullptr, nullptr, &mx2, s, nullptr, PCG_PADE_Q);
     if (rc < 0) return rc;
     res->max_iters_used = std::max(mx, mx2);
-    if (rc == NUGPR_INDEFINITE) { res->status = rc; return rc; }
+    if (no_value(rc)) { res->status = rc; return rc; }
     worst = std::max(worst, rc);
     int rc2;
     if ((rc2 = run_split_op(c, c->Xv, c->Zv, T, s))) return rc2;           // A s
@@ -621,7 +630,7 @@ static int mll_impl(nugpr_ctx* c, const double* theta, nugpr_mll_result* res, bo
   if (rc < 0) return rc;
   res->max_iters_used = mx;
   res->status = rc;
-  if (rc == NUGPR_INDEFINITE) return rc;
+  if (no_value(rc)) return rc;
   res->quad = ex.bx[0];                          // <y, K'^-1 y>: column 0 of B is y
   double est = 0.0;
   for (int col = 1; col < T; ++col) {
@@ -662,7 +671,7 @@ int nugpr_train_step(nugpr_ctx* c, double* log_theta, double* adam_m, double* ad
   // overwrite the stored blocks.
   nugpr_mll_result r0;
   rc = mll_impl(c, theta.data(), &r0, true, stream);
-  if (rc < 0 || rc == NUGPR_INDEFINITE) return rc;
+  if (no_value(rc)) return rc;
   worst = std::max(worst, rc);
   *nll0 = r0.nll;
   const bool forward = (c->params.flags & NUGPR_FD_FORWARD) != 0;
@@ -676,7 +685,7 @@ int nugpr_train_step(nugpr_ctx* c, double* log_theta, double* adam_m, double* ad
     c->general_route = true;
     rc = mll_impl(c, theta.data(), &r0_general, true, stream);
     c->general_route = false;
-    if (rc < 0 || rc == NUGPR_INDEFINITE) return rc;
+    if (no_value(rc)) return rc;
     worst = std::max(worst, rc);
   }
   for (int k = 0; forward && k < p; ++k) {
@@ -692,7 +701,7 @@ int nugpr_train_step(nugpr_ctx* c, double* log_theta, double* adam_m, double* ad
       theta[i] = t0 + delta;
       rc = mll_impl(c, theta.data(), &r1, true, stream);
       theta[i] = t0;
-      if (rc < 0 || rc == NUGPR_INDEFINITE) return rc;
+      if (no_value(rc)) return rc;
       worst = std::max(worst, rc);
       g = (r1.nll - (k < 2 ? r0.nll : r0_general.nll)) / delta;
       halv = e;
@@ -716,12 +725,12 @@ int nugpr_train_step(nugpr_ctx* c, double* log_theta, double* adam_m, double* ad
     }
     theta[i] = tp;
     rc = mll_impl(c, theta.data(), &rp, true, stream);
-    if (rc < 0 || rc == NUGPR_INDEFINITE) return rc;
+    if (no_value(rc)) return rc;
     worst = std::max(worst, rc);
     if (pair && (rc = swap_pair(c))) return rc;
     theta[i] = tm;
     rc = mll_impl(c, theta.data(), &rm, true, stream);
-    if (rc < 0 || rc == NUGPR_INDEFINITE) return rc;
+    if (no_value(rc)) return rc;
     worst = std::max(worst, rc);
     theta[i] = std::exp(log_theta[i]);
     grad[i] = (rp.nll - rm.nll) / (2.0 * h);
@@ -769,6 +778,13 @@ int nugpr_confidence_band(const double* mean, const double* var, int64_t m, doub
     lo[j] = mean[j] - 2.0 * sd;
     hi[j] = mean[j] + 2.0 * sd;
   }
+  return NUGPR_OK;
+}
+
+int nugpr_compensation_steps(const nugpr_ctx* c, int32_t* out) {
+  if (!c || !out) { set_error("null argument"); return NUGPR_ERR_INVALID; }
+  if (!c->L.compensate || !c->built) { set_error("no compensated assembly yet"); return NUGPR_ERR_STATE; }
+  *out = c->lambda0_steps;
   return NUGPR_OK;
 }
 

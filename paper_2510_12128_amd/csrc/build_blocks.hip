@@ -50,7 +50,8 @@ __host__ __device__ inline int pair_kd(int d) { return (d + 3) & ~3; }
 // written as zeros.  grid.y = cluster (or 0 for the representatives), 64 points per block.
 __global__ __launch_bounds__(256) void k_scale_points(const ScaleArgs a, const ClusterInfo* __restrict__ cl,
                                                       const float* __restrict__ P, double* __restrict__ S,
-                                                      double* __restrict__ N, int single_total, int single_ld) {
+                                                      double* __restrict__ N, int single_total, int single_ld,
+                                                      PcgState* __restrict__ st, int mark) {
   uint32_t first, total, ld, prow;
   if (cl) {
     const ClusterInfo c = cl[blockIdx.y];
@@ -71,7 +72,10 @@ __global__ __launch_bounds__(256) void k_scale_points(const ScaleArgs a, const C
   }
   nrm += __shfl_xor(nrm, 1);
   nrm += __shfl_xor(nrm, 2);
-  if (sub == 0) N[pr] = nrm;
+  if (sub == 0) {
+    N[pr] = nrm;
+    if (!(nrm < INFINITY)) st->nonfinite_mark = mark;       // NaN or Inf among this point's coordinates
+  }
 }
 
 // 2^f on [-1/2, 1/2]: degree-6 interpolant at the Chebyshev nodes (near-minimax), relative error
@@ -511,7 +515,14 @@ static int build_impl(nugpr_ctx* c, const double* theta, hipStream_t s, bool nee
   // the upper tiles of C can be left out only if its strips pair up in the product (and nothing else reads them)
   const bool need_c_upper = need_upper || L.compensate || !c->c_paired;
   ac.mirror = need_c_upper ? 1 : 0;
-  if (L.compensate) {
+  const bool host_lambda = L.compensate && L.ncr <= COMPENSATE_HOST_MAX;
+  if (L.compensate && !host_lambda) {
+    // large coupling: the matrix is assembled with a zero diagonal first, lambda_0 comes from an eigenvalue
+    // iteration on the assembled matrix (below), and the diagonal alpha - lambda_0 is written last
+    ac.keep_same = 1;
+    ac.diag_val = 0.f;
+  }
+  if (host_lambda) {
     // lambda_0 = smallest eigenvalue of the representatives' kernel matrix (eq. (krep)), fp64 on the host
     const int N = L.ncr;
     std::vector<double> Cm((size_t)N * N);
@@ -528,13 +539,15 @@ static int build_impl(nugpr_ctx* c, const double* theta, hipStream_t s, bool nee
     double lam0 = 0.0;
     if (sym_smallest_eigenvalue(Cm, N, &lam0)) { set_error("lambda_0: eigen-solve did not converge"); return NUGPR_ERR_INVALID; }
     c->lambda0 = lam0;
+    c->lambda0_steps = 0;
     ac.keep_same = 1;
     ac.diag_val = (float)(alpha - lam0);
   }
+  c->assembly_mark = c->assembly_mark >= 0x7ffffff0 ? 1 : c->assembly_mark + 1;
   hipLaunchKernelGGL(k_scale_points, dim3((unsigned)L.ntmax, (unsigned)L.nc), dim3(256), 0, s, sa, c->d_cl, c->X, c->Xs,
-                     c->Xn, 0, 0);
+                     c->Xn, 0, 0, c->d_state, c->assembly_mark);
   hipLaunchKernelGGL(k_scale_points, dim3((unsigned)(L.ldc / TILE), 1u), dim3(256), 0, s, sa,
-                     (const ClusterInfo*)nullptr, c->reps, c->Rs, c->Rn, L.ncr, L.ldc);
+                     (const ClusterInfo*)nullptr, c->reps, c->Rs, c->Rn, L.ncr, L.ldc, c->d_state, c->assembly_mark);
   const dim3 gd((unsigned)c->n_pan_diag), gc((unsigned)c->n_pan_c), blk(256);
   const size_t lds = (size_t)4 * a.kd * 16 * sizeof(double);      // row operands of one tile
 #define NUGPR_TILES(NKS)                                                                                         \
@@ -558,10 +571,20 @@ static int build_impl(nugpr_ctx* c, const double* theta, hipStream_t s, bool nee
   if (L.compensate) {
     CouplingArgs ca;
     for (int k = 0; k < MAX_D; ++k) ca.inv_ell[k] = k < L.d ? 1.0 / (iso ? theta[0] : theta[k]) : 0.0;
-    ca.alpha = alpha; ca.lambda0 = c->lambda0; ca.n = L.ncr; ca.d = L.d; ca.ld = (uint32_t)L.ldc;
+    // (large coupling: the diagonal is zero for now, in both terms)
+    ca.alpha = alpha; ca.lambda0 = host_lambda ? c->lambda0 : alpha; ca.n = L.ncr; ca.d = L.d; ca.ld = (uint32_t)L.ldc;
     const unsigned blocks = (unsigned)(((uint64_t)L.ldc * L.ldc + 255) / 256);
     hipLaunchKernelGGL(k_coupling_residual, dim3(blocks), dim3(256), 0, s, ca, c->reps, c->C, c->Clo);
     NUGPR_HIP(hipGetLastError());
+    if (!host_lambda) {
+      double lam0 = 0.0;
+      int steps = 0;
+      int rc = coupling_lambda_min(c, theta, s, &lam0, &steps);
+      if (rc) return rc;
+      c->lambda0 = lam0;
+      c->lambda0_steps = steps;
+      if ((rc = coupling_set_diag(c, alpha - lam0, s))) return rc;
+    }
   }
   c->theta_built.assign(theta, theta + L.p);
   c->theta_spare.clear();

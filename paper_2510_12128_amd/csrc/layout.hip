@@ -109,7 +109,10 @@ int plan_layout(const nugpr_problem* pb, uint32_t flags, Layout& L) {
   }
   // residual matrix of the compensated coupling; reserved whenever the problem is small enough for the
   // compensation, so that the workspace size does not depend on the flags
-  if (L.ncr <= 512) L.o_Clo = take(cur, (size_t)L.ldc * L.ldc * sizeof(float));
+  // (larger couplings keep it in the spare coupling matrix, which only the pair assembly uses and the
+  // compensation does without)
+  if (L.ncr <= COMPENSATE_HOST_MAX) L.o_Clo = take(cur, (size_t)L.ldc * L.ldc * sizeof(float));
+  if (L.ncr > COMPENSATE_HOST_MAX) L.o_dav = take(cur, eigmin_workspace_doubles((size_t)L.ldc, (size_t)L.ncr) * sizeof(double));
   L.o_assign = take(cur, (size_t)L.n * sizeof(int32_t));
   L.o_rep_ptr = take(cur, ((size_t)L.ncr + 1) * sizeof(int32_t));
   L.o_rep_pts = take(cur, (size_t)L.n * sizeof(int32_t));

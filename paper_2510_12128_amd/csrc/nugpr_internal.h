@@ -15,6 +15,12 @@ constexpr int TILE = 64;        // rows per strip / edge of the square tiles
 constexpr int MAX_COLS = 33;    // widest vector block (1 + 32 probes)
 constexpr int MAX_D = 64;
 constexpr int MAX_ITER_CAP = 4096;
+constexpr int COMPENSATE_HOST_MAX = 512;     // lambda_0 of eq. (krep): dense host eigen-solve up to this n_c r, iteration on the device beyond
+constexpr double EIGMIN_REL_TOL = 2e-11;     // stopping tolerance of that iteration on lambda_0, relative to alpha
+constexpr double EIGMIN_PSD_TOL = 1e-5;      // at its step cap a Ritz value below this (times alpha) is accepted: lambda_min lies in [0, theta]
+// doubles of workspace the device iteration needs for a coupling matrix of leading dimension ldc with n rows:
+// 24 + 24 basis vectors and their images, residual, new direction, a few scalars, the factors of the 128 x 128 blocks
+inline size_t eigmin_workspace_doubles(size_t ldc, size_t n) { return 50 * ldc + 64 + ((n + 127) / 128) * 128 * 128; }
 
 // ---------------------------------------------------------------------------
 // per-cluster geometry (device copy lives in the workspace)
@@ -123,7 +129,7 @@ struct PcgState {
   int32_t bad_cluster;    // Cholesky: lowest failing cluster index, or INT_MAX
   int32_t tail_count;     // workgroups of the end-of-solve report that are done (returns to 0)
   int32_t check_count;    // workgroups of the stop test that are done (returns to 0)
-  int32_t pad_;
+  int32_t nonfinite_mark; // mark of the last assembly that met NaN / Inf coordinates (nugpr_ctx::assembly_mark)
   // <b, b> and <b, z_0> of the two right-hand-side blocks the context owns ([y | L Z] with z_0 = M^-1 b,
   // and the probe block [0 | Z] with z_0 = b): they depend on the factor only and are taken with it
   double known_bb[2][MAX_COLS];
@@ -161,7 +167,7 @@ struct Layout {
   size_t o_Spart = 0, o_Ppart = 0, o_dot = 0, o_state = 0, o_alog = 0, o_blog = 0;
   size_t o_theta = 0, o_logdet = 0, o_tiles = 0, o_items = 0;
   size_t o_Xs = 0, o_Xn = 0, o_Rs = 0, o_Rn = 0;
-  size_t o_x0 = 0, o_Z0 = 0, o_P = 0, o_Clo = 0, o_S0 = 0;
+  size_t o_x0 = 0, o_Z0 = 0, o_P = 0, o_Clo = 0, o_S0 = 0, o_dav = 0;
   size_t o_assign = 0, o_rep_ptr = 0, o_rep_pts = 0;
   size_t items_bytes = 0;
   int n_dot_blocks = 0;
@@ -230,6 +236,10 @@ struct nugpr_ctx {
   // The stored blocks are the very ones the factor was computed from while build_gen == factor_gen:
   // then Y K_diag Y^T = I for the stored K_diag and Y = L^-1 (eq. (linear1)).
   uint64_t build_gen = 0, factor_gen = ~0ull;
+  // every assembly pass hands its kernels a fresh non-zero mark; the coordinate-scaling kernel stores it in the
+  // device state when it meets a NaN or Inf among the points or representatives (the kernel values of such a
+  // point would otherwise quietly come out as zero)
+  int32_t assembly_mark = 0;
   // The assembly may leave out the strictly upper tiles of the K_ii (the product's usual launch reads the
   // lower ones only, see k_strip_ring); whoever needs whole strips calls ensure_kd_upper first.
   bool kd_upper_valid = false, spare_upper_valid = false;
@@ -246,7 +256,9 @@ struct nugpr_ctx {
   // applied as a second small product so that the compensation term is carried to ~2^-48.
   std::vector<double> h_reps;
   double lambda0 = 0.0;
+  int lambda0_steps = 0;                 // steps the device iteration for the last lambda_0 took (0: dense host eigen-solve)
   float* Clo = nullptr;
+  double* dav = nullptr;                 // workspace of that iteration (eigmin_workspace_doubles)
   nugpr_stats stats{};                   // work counters (nugpr_stats_read)
   std::vector<int32_t> fd_halvings;      // halvings per hyperparameter in the last forward-difference step
   double logdetM = 0.0;
@@ -282,6 +294,13 @@ bool kd_lower_suffices(const nugpr_ctx* c);
 int ensure_kd_upper(nugpr_ctx* c, hipStream_t s);
 int ensure_c_upper(nugpr_ctx* c, hipStream_t s);
 int launch_export(nugpr_ctx* c, int what, int index, float* dst, int64_t ld, hipStream_t s);
+
+// eigmin.hip -----------------------------------------------------------------
+// smallest eigenvalue of the kernel matrix of the representatives at theta: off-diagonal part from (c->C + c->Clo),
+// the scalar alpha on the diagonal, diagonal blocks for the preconditioner recomputed from the representatives
+int coupling_lambda_min(nugpr_ctx* c, const double* theta, hipStream_t s, double* lambda_out, int* steps_out);
+// Chi_ii = float(value), Clo_ii = what that drops
+int coupling_set_diag(nugpr_ctx* c, double value, hipStream_t s);
 
 // strip_gemm.hip ------------------------------------------------------------
 int launch_strip(const StripTable& tab, const StripPort& p0, const StripPort& p1, int T, bool acc64,
@@ -334,6 +353,9 @@ int run_predict(nugpr_ctx* c, const double* theta, const float* Xt, int64_t m, d
 // slq.cpp ---------------------------------------------------------------------
 // e_1^T log(T) e_1 for the k x k Lanczos matrix built from CG coefficients.
 int slq_e1_log_e1(const double* alpha, const double* beta, int stride, int k, double* out);
+// Eigenvalues (left in d) of the symmetric tridiagonal matrix with diagonal d (k) and sub-diagonal e (k - 1) by the
+// implicit-shift QL iteration, with the first components of the eigenvectors in z; 0 on success.
+int tridiag_eigen_first_row(std::vector<double>& d, std::vector<double>& e, std::vector<double>& z);
 // Smallest eigenvalue of a dense symmetric n x n matrix (row-major, overwritten); 0 on success.
 int sym_smallest_eigenvalue(std::vector<double>& A, int n, double* out);
 

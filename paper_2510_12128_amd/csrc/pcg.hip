@@ -814,6 +814,11 @@ static int pcg_t(nugpr_ctx* c, const VT* B, VT* X, int T, int32_t* iters, double
         if (beta) beta[(size_t)j * T + col] = j < it - 1 ? ha[cnt + (size_t)j * MAX_COLS + col] : 0.0;
       }
   }
+  // NaN / Inf among the coordinates of the last assembly (found by its scaling kernel), or in a right-hand
+  // side: the latter shows in the first dot products of its column, <b, b> and <b, M^-1 b>
+  if (c->assembly_mark != 0 && hs->nonfinite_mark == c->assembly_mark) return NUGPR_NOT_FINITE;
+  for (int col = 0; col < T; ++col)
+    if (!std::isfinite(hs->bnorm2[col]) || !std::isfinite(hs->rho0[col])) return NUGPR_NOT_FINITE;
   if (indefinite) return NUGPR_INDEFINITE;
   return all_conv ? NUGPR_OK : NUGPR_NOT_CONVERGED;
 }

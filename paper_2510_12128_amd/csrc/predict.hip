@@ -94,7 +94,7 @@ static int predict_t(nugpr_ctx* c, const double* theta, const float* Xt, int64_t
   if (rc) return rc;
   int mx = 0;
   rc = run_pcg(c, U, S, 1, nullptr, nullptr, nullptr, &mx, s);
-  if (rc < 0 || rc == NUGPR_INDEFINITE) return rc;
+  if (rc < 0 || rc == NUGPR_INDEFINITE || rc == NUGPR_NOT_FINITE) return rc;
   worst = std::max(worst, rc);
   mx_all = std::max(mx_all, mx);
   NUGPR_HIP(hipMemcpyAsync(u, S, (size_t)n * sizeof(VT), hipMemcpyDeviceToDevice, s));
@@ -114,7 +114,7 @@ static int predict_t(nugpr_ctx* c, const double* theta, const float* Xt, int64_t
     NUGPR_HIP(hipGetLastError());
     if (var) {
       rc = run_pcg(c, U, S, T, nullptr, nullptr, nullptr, &mx, s);
-      if (rc < 0 || rc == NUGPR_INDEFINITE) return rc;
+      if (rc < 0 || rc == NUGPR_INDEFINITE || rc == NUGPR_NOT_FINITE) return rc;
       worst = std::max(worst, rc);
       mx_all = std::max(mx_all, mx);
     }

@@ -13,7 +13,7 @@ namespace nugpr {
 // Symmetric tridiagonal eigenproblem by the implicit-shift QL iteration, carrying only
 // the first row of the eigenvector matrix (all the quadrature needs).
 // d: diagonal (k), e: sub-diagonal (k-1, padded to k), z: out first components.
-static int tridiag_ql_first_row(std::vector<double>& d, std::vector<double>& e, std::vector<double>& z) {
+int tridiag_eigen_first_row(std::vector<double>& d, std::vector<double>& e, std::vector<double>& z) {
   const int k = (int)d.size();
   z.assign(k, 0.0);
   z[0] = 1.0;
@@ -76,7 +76,7 @@ int slq_e1_log_e1(const double* alpha, const double* beta, int stride, int k, do
   }
   for (int j = 0; j < k; ++j)
     if (!std::isfinite(d[j])) return 1;
-  if (tridiag_ql_first_row(d, e, z)) return 1;
+  if (tridiag_eigen_first_row(d, e, z)) return 1;
   double acc = 0.0;
   for (int j = 0; j < k; ++j) {
     if (!(d[j] > 0.0)) return 1;
@@ -120,7 +120,7 @@ int sym_smallest_eigenvalue(std::vector<double>& A, int n, double* out) {
   if (n >= 2) e[n - 2] = a(n - 1, n - 2);
   for (int i = 0; i < n; ++i)
     if (!std::isfinite(d[i])) return 1;
-  if (tridiag_ql_first_row(d, e, z)) return 1;
+  if (tridiag_eigen_first_row(d, e, z)) return 1;
   double mn = d[0];
   for (int i = 1; i < n; ++i) mn = d[i] < mn ? d[i] : mn;
   *out = mn;

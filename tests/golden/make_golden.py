@@ -8,10 +8,13 @@ Quantities follow eq. (loss function), eq. (logdet) and eq. (numerical gradient)
 paper in the central-difference form on log(theta) (h = 1e-3), all evaluations sharing
 the preconditioner factored at theta_0 and the same probes.
 
-    python tests/golden/make_golden.py [C3 C4 C3-adam20 ...] [--workers N]
+    python tests/golden/make_golden.py [C3 C4 C3-adam20 C3c-adam20 ...] [--workers N] [--steps K]
 
   C3, C4       base loss + central-difference gradient components (several lengthscales, the output
                scale, the noise) at the configured hyperparameters
+  C3c-adam20   the same 20 steps with the compensated operator K'' of eqs. (krep), (kypp), which stays
+               positive definite when the lengthscales grow (the uncompensated K' of C3-adam20 does not:
+               that record ends with the step at which the oracle finds it indefinite)
   C3-adam20    configuration 3's own workload: 20 passes of Algorithm 1's loop body (factor at theta_0,
                base loss, central differences with that factor and the same probes, Adam with
                gamma = 0.05 on log theta); per step the base loss, the whole gradient and the
@@ -87,14 +90,14 @@ def run_point(name, workers):
                 logdet_precond=base["logdet_precond"], max_iters=int(base["iters"].max()), grad=grad)
 
 
-def run_adam(name, steps, workers, save):
+def run_adam(name, steps, workers, save, compensate=False):
     w = I.make_config(name)
-    prob = O.Problem(w.X, w.y, w.offsets, w.probes, w.rank)
+    prob = O.Problem(w.X, w.y, w.offsets, w.probes, w.rank, compensate=compensate)
     phi = np.log(w.theta)
     p = phi.shape[0]
     m, v, step = np.zeros(p), np.zeros(p), 0
     rec = dict(config=name, n=w.n, theta0=list(map(float, w.theta)), tol=w.tol, max_iter=w.max_iter,
-               fd_step=w.fd_step, lr=w.lr, steps=[])
+               fd_step=w.fd_step, lr=w.lr, compensate=bool(compensate), steps_requested=steps, steps=[])
     t0 = time.time()
     for it in range(steps):
         fac = O.Factor(prob, np.exp(phi))
@@ -122,10 +125,14 @@ def run_adam(name, steps, workers, save):
 
 if __name__ == "__main__":
     args = sys.argv[1:]
-    workers = 1
+    workers, nsteps = 1, 20
     if "--workers" in args:
         k = args.index("--workers")
         workers = int(args[k + 1])
+        del args[k:k + 2]
+    if "--steps" in args:                  # fewer than the 20 steps of the workload (recorded as steps_requested)
+        k = args.index("--steps")
+        nsteps = int(args[k + 1])
         del args[k:k + 2]
     names = args or ["C3", "C4"]
     data = json.load(open(OUT)) if os.path.exists(OUT) else {}
@@ -140,7 +147,9 @@ if __name__ == "__main__":
             def save(rec, key=nm):
                 data[key] = rec
                 write()
-            run_adam(nm[:-len("-adam20")], 20, workers, save)
+            base = nm[:-len("-adam20")]
+            comp = base.endswith("c")               # "C3c-adam20": the compensated operator of eqs. (krep), (kypp)
+            run_adam(base[:-1] if comp else base, nsteps, workers, save, compensate=comp)
         else:
             data[nm] = run_point(nm, workers)
             write()

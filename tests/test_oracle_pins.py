@@ -467,7 +467,54 @@ def test_train_step_reduces_loss_on_small_problem():
     assert step == 5
 
 
-# ---------------------------------------------------------------- inputs
+def test_train_step_is_adam_on_the_central_differences_of_one_factor():
+    """Algorithm 1's loop body as the GPU train step is compared with it: ONE factor at theta_0, base loss and
+    every perturbed loss with that factor and the same probes, central differences with step h, then Adam."""
+    w = I.make_small(n_clusters=3, sizes=[9, 14, 11], d=2, rank=2, t=5, seed=61, ell=1.4, spacing=3.0, sigma_blob=0.4)
+    prob = O.Problem(w.X, w.y, w.offsets, w.probes, 2)
+    phi0 = np.log(w.theta)
+    p = phi0.shape[0]
+    h, tol, mi, lr = 0.05, 1e-12, 300, 0.05
+    m0, v0 = 0.01 * np.arange(1, p + 1), 0.002 * np.arange(1, p + 1)
+    phi, m, v, step, nll0, g = O.train_step(prob, phi0, m0, v0, 3, h, tol, mi, lr=lr)
+    # (i) exactly the composition of the pinned pieces (random probes: a factor rebuilt at a perturbed theta, or
+    # another probe set, would change the Lanczos estimates and fail this to the bit)
+    fac = O.Factor(prob, np.exp(phi0))
+    assert nll0 == O.mll(prob, fac, np.exp(phi0), tol, mi)["nll"]
+    g_ref = O.fd_gradient(prob, fac, phi0, h, tol, mi)
+    assert np.array_equal(g, g_ref)
+    ph, mh, vh, sh = O.adam_step(phi0, g_ref, m0, v0, 3, lr=lr)
+    assert np.array_equal(phi, ph) and np.array_equal(m, mh) and np.array_equal(v, vh) and step == sh == 4
+    # (ii) the differences by hand, with this h and no other: (L(phi + h e_i) - L(phi - h e_i)) / (2h)
+    for i in range(p):
+        e = np.zeros(p)
+        e[i] = h
+        lp = O.mll(prob, fac, np.exp(phi0 + e), tol, mi)["nll"]
+        lm = O.mll(prob, fac, np.exp(phi0 - e), tol, mi)["nll"]
+        assert g[i] == (lp - lm) / (2 * h)
+        half = (O.mll(prob, fac, np.exp(phi0 + e / 2), tol, mi)["nll"] -
+                O.mll(prob, fac, np.exp(phi0 - e / 2), tol, mi)["nll"]) / h
+        assert abs(g[i] - half) > 1e-7 * abs(g[i])          # a halved step is a different number at this h
+    # (iii) against the mathematics: with Hadamard probes the estimate is exact for any factor, so loss and
+    # gradient are those of the dense matrix (central differences of the dense loss with the same h)
+    n = 32
+    w2 = I.make_small(n_clusters=4, sizes=[8, 8, 8, 8], d=2, rank=2, t=1, seed=59, ell=1.5, spacing=3.5, sigma_blob=0.3)
+    prob2 = O.Problem(w2.X, w2.y, w2.offsets, I.hadamard_probes(n), 2)
+
+    def dense_loss(ph):
+        K = prob2.dense(np.exp(ph))
+        return 0.5 * (prob2.y @ np.linalg.solve(K, prob2.y) + np.linalg.slogdet(K)[1] + n * math.log(2 * math.pi))
+
+    q0 = np.log(w2.theta)
+    _, _, _, _, nll2, g2 = O.train_step(prob2, q0, np.zeros_like(q0), np.zeros_like(q0), 0, h, 1e-13, 400, lr=lr)
+    assert abs(nll2 - dense_loss(q0)) < 1e-8 * abs(nll2)
+    for i in range(q0.shape[0]):
+        e = np.zeros_like(q0)
+        e[i] = h
+        gd = (dense_loss(q0 + e) - dense_loss(q0 - e)) / (2 * h)
+        assert abs(g2[i] - gd) < 1e-7 * max(abs(gd), 1.0)
+
+
 # ---------------------------------------------------------------- prediction
 def _textbook_posterior(K, Ks, alpha, y):
     """Posterior mean and variance of a zero-mean GP by dense solves (Section 2.1)."""
@@ -547,6 +594,58 @@ def test_compensation_lambda_by_the_cholesky_criterion():
     np.linalg.cholesky(C - (lam0 - 1e-9) * np.eye(7))
     with pytest.raises(np.linalg.LinAlgError):
         np.linalg.cholesky(C - (lam0 + 1e-9) * np.eye(7))
+
+
+@pytest.mark.parametrize("name,scale,variant,shrink", [("C5", 24 / 256, "default", 1.0), ("C5", 24 / 256, "wide", 1.5),
+                                                        ("C2", 10 / 32, "wide", 1.5), ("C4", 8 / 128, "wide", 1.0),
+                                                        ("C3", 16 / 64, "wide", 1.75), ("C2", 1.0, "default", 1.0)])
+def test_iterative_lambda_reproduces_the_dense_eigenvalue_on_coupling_matrices_of_600_to_2000(name, scale, variant, shrink):
+    # eq. (krep): lambda_0 = lambda_min(K_rep).  The matrix-free route must deliver the number the dense
+    # eigen-solve gives, on kernel matrices of the representatives of the benchmark shapes, the wide-lengthscale
+    # ones (a dense cluster of small eigenvalues at the bottom of the spectrum) included
+    w = I.make_config(name, variant, scale=scale, centre_shrink=shrink)
+    reps = O.default_reps(w.X.astype(np.float64), w.offsets, w.rank)
+    C = O.coupling(reps, w.theta)
+    assert 600 <= C.shape[0] <= 2100
+    ref = O.compensation_lambda(C)
+    got, steps = O.compensation_lambda_iterative(C)
+    alpha = w.theta[-2]
+    assert got >= ref - 1e-12 * alpha            # Ritz values approach from above
+    assert abs(got - ref) <= 1e-10 * alpha, (got, ref, steps)
+    assert steps <= 100
+    # the compensated coupling is positive semi-definite up to that error
+    assert np.linalg.eigvalsh(C - got * np.eye(C.shape[0]))[0] >= -1e-10 * alpha
+
+
+def test_iterative_lambda_on_singular_tiny_and_degenerate_matrices():
+    # 128 representatives packed into one small blob: the kernel matrix is singular to rounding; the iteration
+    # must say "zero to the tolerance" (a kernel matrix is positive semi-definite), not run for ever
+    w = I.make_small(n_clusters=17, sizes=[130 + (7 * i) % 23 for i in range(17)], d=3, rank=128, t=2, seed=9, ell=1.5,
+                     spacing=2.0, sigma_blob=0.5)
+    C = O.coupling(O.default_reps(w.X.astype(np.float64), w.offsets, w.rank), w.theta)
+    ref = O.compensation_lambda(C)
+    got, steps = O.compensation_lambda_iterative(C)
+    assert abs(ref) < 1e-11 and abs(got - ref) <= 1e-10 * w.theta[-2] and steps <= 20
+    # strongly overlapping clusters, wide lengthscale: the small eigenvalues (2e-6 alpha here) belong to modes that
+    # span many blocks and the iteration crawls; at its step cap it returns an estimate that is within
+    # [lambda_min, lambda_min + theta] by positive semi-definiteness, here far closer
+    w2 = I.make_small(n_clusters=10, sizes=[150 + (11 * i) % 37 for i in range(10)], d=4, rank=64, t=2, seed=21, ell=1.5,
+                      spacing=3.0, sigma_blob=0.8)
+    C2 = O.coupling(O.default_reps(w2.X.astype(np.float64), w2.offsets, w2.rank), w2.theta)
+    ref2 = O.compensation_lambda(C2)
+    got2, steps2 = O.compensation_lambda_iterative(C2)
+    assert steps2 == 150 and ref2 <= got2 <= 1e-5 * w2.theta[-2] and got2 - ref2 < 2e-7
+    assert O.compensation_lambda_iterative(np.array([[2.5]]))[0] == 2.5
+    lam, steps = O.compensation_lambda_iterative(3.0 * np.eye(7))
+    assert abs(lam - 3.0) < 1e-14 and steps <= 2
+    # a matrix with a known spectrum, no block structure at all
+    rng = np.random.default_rng(5)
+    Q, _ = np.linalg.qr(rng.standard_normal((40, 40)))
+    ev = np.concatenate([[0.013], np.linspace(0.5, 3.0, 39)])
+    A = (Q * ev) @ Q.T
+    A = 0.5 * (A + A.T)
+    lam, _ = O.compensation_lambda_iterative(A)
+    assert abs(lam - 0.013) < 1e-10
 
 
 def test_compensated_matrix_has_the_printed_form_at_rank_one_and_is_spd():
