@@ -196,6 +196,19 @@ int nugpr_precond_factor(nugpr_ctx* ctx, double* logdet_M /*HOST*/, int32_t* bad
  * bandwidth metric.  D, Q: DEVICE n x ncols, must not alias. */
 int nugpr_matvec(nugpr_ctx* ctx, const float* D, float* Q, int32_t ncols, void* stream);
 
+/* nugpr_matvec for callers that cannot allocate or hand over scratch memory for the call (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels, but the blocks the
+ * product needs beyond D, Q and the stored matrices (the two vector blocks in the solver's own type, the
+ * slabs of partial sums of W^T D and C S) live in a static device buffer inside the library instead of the
+ * context's workspace.  That buffer holds nugpr_matvec_static_max_bytes() = 16 MiB per GPU and is kept until
+ * the process ends; a product that needs more (about 16 n ncols + 8 (slabs) n_c r ncols bytes in the default
+ * mode) is refused with NUGPR_ERR_WORKSPACE.  No hipMalloc / hipFree or allocating routine is called.
+ * Every call on a GPU shares that GPU's buffer, which keeps the last call's contents (nothing in it needs to
+ * start at zero): calls that overlap on one GPU, on any streams or contexts, race.  The context must have
+ * been created on the device that is current.  Does not synchronise. */
+int nugpr_matvec_static(nugpr_ctx* ctx, const float* D, float* Q, int32_t ncols, void* stream);
+size_t nugpr_matvec_static_max_bytes(void);
+
 /* Z = M^-1 R with M the factored block-Jacobi preconditioner (Section 3.2).
  * R, Z: DEVICE n x ncols, must not alias. */
 int nugpr_precond_apply(nugpr_ctx* ctx, const float* R, float* Z, int32_t ncols, void* stream);

@@ -90,6 +90,10 @@ def load_library():
     lib.nugpr_precond_factor.argtypes = [vp, dp, ip, vp]
     lib.nugpr_matvec.restype = C.c_int
     lib.nugpr_matvec.argtypes = [vp, vp, vp, C.c_int32, vp]
+    lib.nugpr_matvec_static.restype = C.c_int
+    lib.nugpr_matvec_static.argtypes = [vp, vp, vp, C.c_int32, vp]
+    lib.nugpr_matvec_static_max_bytes.restype = C.c_size_t
+    lib.nugpr_matvec_static_max_bytes.argtypes = []
     lib.nugpr_split_apply.restype = C.c_int
     lib.nugpr_split_apply.argtypes = [vp, vp, vp, C.c_int32, vp]
     lib.nugpr_precond_apply.restype = C.c_int
@@ -280,6 +284,12 @@ class Context:
         _check(self.lib.nugpr_matvec(self.handle, D.data_ptr(), Q.data_ptr(), D.shape[1], self._stream()))
         return Q
 
+    def nugpr_matvec_static(self, D):
+        D = self._block(D)
+        Q = self.torch.empty_like(D)
+        _check(self.lib.nugpr_matvec_static(self.handle, D.data_ptr(), Q.data_ptr(), D.shape[1], self._stream()))
+        return Q
+
     def nugpr_split_apply(self, D):
         D = self._block(D)
         out = self.torch.empty_like(D)
@@ -355,6 +365,11 @@ class Context:
     def nugpr_matvec_into(self, D, Q):
         """nugpr_matvec on caller-held device tensors (no allocation; used for timing)."""
         return _check(self.lib.nugpr_matvec(self.handle, D.data_ptr(), Q.data_ptr(), D.shape[1], self._stream()))
+
+    def nugpr_matvec_static_into(self, D, Q):
+        """nugpr_matvec_static on caller-held device tensors: nothing is allocated on either side of the ABI."""
+        return _check(self.lib.nugpr_matvec_static(self.handle, D.data_ptr(), Q.data_ptr(), D.shape[1],
+                                                   self._stream()))
 
     def nugpr_precond_apply_into(self, R, Z):
         return _check(self.lib.nugpr_precond_apply(self.handle, R.data_ptr(), Z.data_ptr(), R.shape[1],

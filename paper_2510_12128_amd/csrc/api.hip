@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstring>
 #include <limits>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -20,6 +21,33 @@ __global__ void k_copy16(const float4* __restrict__ src, float4* __restrict__ ds
 }
 
 hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+// ---- scratch memory of the entry point that allocates nothing (nugpr_matvec_static) ----------------
+// One file-scope device array per GPU the library is loaded on, held until the process ends.  Host code
+// never uses the array's name as an address: its device address is looked up once per device with
+// hipGetSymbolAddress (at nugpr_create, with that device current) and kept in g_scratch_ptr.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+
+// address of `scratch` on the CURRENT device (looked up on first use), or an error code
+int scratch_address(int* device_out, void** ptr_out) {
+  int dev = -1;
+  NUGPR_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) { set_error("device index out of range"); return NUGPR_ERR_INVALID; }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    NUGPR_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) { set_error("hipGetSymbolAddress returned a null address for the static scratch"); return NUGPR_ERR_HIP; }
+    g_scratch_ptr[dev] = ptr;
+  }
+  if (device_out) *device_out = dev;
+  if (ptr_out) *ptr_out = g_scratch_ptr[dev];
+  return NUGPR_OK;
+}
 
 // ---- strip work tables ------------------------------------------------------
 StripItem make_item(uint64_t a_off, uint32_t lda, uint32_t nrows, uint32_t c_begin, uint32_t c_end,
@@ -252,8 +280,11 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
     set_error("X / y misaligned");
     return NUGPR_ERR_INVALID;
   }
+  int device = -1;
+  if ((rc = scratch_address(&device, nullptr))) return rc;      // also records which GPU this context lives on
   nugpr_ctx* c = new (std::nothrow) nugpr_ctx();
   if (!c) { set_error("out of host memory"); return NUGPR_ERR_INVALID; }
+  c->device = device;
   c->L = L;
   c->params = *prm;
   c->acc64 = (prm->flags & NUGPR_ACC_FP32) == 0;
@@ -495,6 +526,39 @@ int nugpr_matvec(nugpr_ctx* c, const float* D, float* Q, int32_t ncols, void* st
   if ((rc = to_internal(c, D, c->Dv, cnt, s))) return rc;
   if ((rc = run_matvec(c, c->Dv, c->Qv, ncols, s))) return rc;
   return from_internal(c, c->Qv, Q, cnt, s);
+}
+
+size_t nugpr_matvec_static_max_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
+int nugpr_matvec_static(nugpr_ctx* c, const float* D, float* Q, int32_t ncols, void* stream) {
+  int rc = check_block_args(c, D, Q, ncols);
+  if (rc) return rc;
+  if (!c->built) { set_error("matvec needs build_blocks first"); return NUGPR_ERR_STATE; }
+  const Layout& L = c->L;
+  // what nugpr_matvec takes from the context's workspace beyond the stored matrices: the two vector blocks in
+  // the solver's own type and the slabs of partial sums of W^T D and C S
+  const size_t vs = c->acc64 ? sizeof(double) : sizeof(float);
+  auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+  const size_t b_vec = c->acc64 ? up((size_t)L.n * ncols * vs) : 0;
+  const size_t b_S = up((size_t)L.nsS * L.ncr * ncols * vs), b_P = up((size_t)L.nsP * L.ncr * ncols * vs);
+  const size_t need = 2 * b_vec + b_S + b_P;
+  if (need > STATIC_SCRATCH_BYTES) {
+    set_error("nugpr_matvec_static: this product needs " + std::to_string(need) + " bytes of scratch, the static "
+              "buffer holds " + std::to_string(STATIC_SCRATCH_BYTES) + "; use nugpr_matvec");
+    return NUGPR_ERR_WORKSPACE;
+  }
+  int dev = -1;
+  NUGPR_HIP(hipGetDevice(&dev));
+  if (dev != c->device) { set_error("the current device is not the one the context was created on"); return NUGPR_ERR_STATE; }
+  char* base = static_cast<char*>(g_scratch_ptr[dev]);        // looked up at nugpr_create on this device
+  if (!base) { set_error("static scratch address unknown on this device"); return NUGPR_ERR_STATE; }
+  // the kernels take their buffers as arguments, as in nugpr_matvec: only the addresses differ.  Nothing in the
+  // scratch needs clearing: every slab and block that is read was written by an earlier kernel of this call.
+  void *sDv = c->Dv, *sQv = c->Qv, *sS = c->Spart, *sP = c->Ppart;
+  c->Dv = base; c->Qv = base + b_vec; c->Spart = base + 2 * b_vec; c->Ppart = base + 2 * b_vec + b_S;
+  rc = nugpr_matvec(c, D, Q, ncols, stream);
+  c->Dv = sDv; c->Qv = sQv; c->Spart = sS; c->Ppart = sP;
+  return rc;
 }
 
 int nugpr_split_apply(nugpr_ctx* c, const float* D, float* out, int32_t ncols, void* stream) {

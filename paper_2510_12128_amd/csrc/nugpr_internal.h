@@ -182,6 +182,7 @@ struct nugpr_ctx {
   nugpr::Layout L;
   nugpr_params params;
   char* ws = nullptr;
+  int device = -1;                       // the GPU that was current at nugpr_create
   const float* X = nullptr;
   const float* y = nullptr;
   const float* probes = nullptr;
