@@ -289,7 +289,9 @@ int nugpr_fd_halvings(const nugpr_ctx* ctx, int32_t* out /*HOST*/);
 
 /* Copies one stored matrix to a dense row-major DEVICE array `dst` with leading
  * dimension `ld` (for verification).  what: 0 = K_ii (b_i x b_i), 1 = L_i lower
- * factor (b_i x b_i, zeros above the diagonal), 2 = L_i^-1 (b_i x b_i), 3 = coupling
+ * factor (b_i x b_i, zeros above the diagonal; it shares its storage with the second matrix of a lengthscale
+ * pair assembly, so it is available from nugpr_precond_factor until the next nugpr_train_step has assembled
+ * such a pair: NUGPR_ERR_STATE afterwards), 2 = L_i^-1 (b_i x b_i), 3 = coupling
  * C with zeroed diagonal blocks, or C - lambda_0 I under NUGPR_COMPENSATE
  * ((n_c r) x (n_c r); index ignored), 4 = W_i (b_i x r),
  * 5 = right-hand sides B (n x (t+1); index ignored), 6 = representatives

@@ -299,7 +299,6 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
   char* w = c->ws;
   c->d_cl = reinterpret_cast<ClusterInfo*>(w + L.o_cl);
   c->Kd = reinterpret_cast<float*>(w + L.o_Kd);
-  c->Lf = reinterpret_cast<float*>(w + L.o_Lf);
   c->G = reinterpret_cast<float*>(w + L.o_G);
   c->C = reinterpret_cast<float*>(w + L.o_C);
   c->Kd2 = reinterpret_cast<float*>(w + L.o_Kd2);

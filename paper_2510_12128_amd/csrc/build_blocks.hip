@@ -593,6 +593,7 @@ static int build_impl(nugpr_ctx* c, const double* theta, hipStream_t s, bool nee
     c->theta_built[pair_param] = value_plus;      // the caller's own values of ell e^{+h} and ell e^{-h}
     c->theta_spare[pair_param] = value_minus;
   }
+  if (pair) c->lf_valid = false;              // the second matrix of the pair has just overwritten the Cholesky factor
   c->spare_upper_valid = pair && need_upper;
   c->c_upper_valid = need_c_upper;
   c->spare_c_upper_valid = pair && need_c_upper;
@@ -639,6 +640,11 @@ int launch_export(nugpr_ctx* c, int what, int index, float* dst, int64_t ld, hip
     src = (what == 0 ? c->Kd : what == 1 ? c->Lf : c->G) + ci.koff;
     lds = ci.ld; rows = cols = (int)ci.b; lower = what != 0;
     if ((what == 0 && !c->built) || (what != 0 && !c->factored)) { set_error("nothing stored yet"); return NUGPR_ERR_STATE; }
+    if (what == 1 && !c->lf_valid) {
+      set_error("the Cholesky factor's storage has since been reused by a lengthscale pair assembly (nugpr_train_step); "
+                "call nugpr_precond_factor again");
+      return NUGPR_ERR_STATE;
+    }
     if (what == 0) {
       const int rc = ensure_kd_upper(c, s);
       if (rc) return rc;

@@ -492,6 +492,8 @@ int launch_factor(nugpr_ctx* c, hipStream_t s) {
   for (const ClusterInfo& ci : L.cl) tiles_sum += ci.nt;
   const bool even = (uint64_t)L.ntmax * (uint64_t)L.nc * 4 <= tiles_sum * 5;
   const int ncm = even ? L.nc : -L.nc;
+  c->Lf = c->Kd2;                 // the factor goes into the spare blocks (see nugpr_ctx::lf_valid)
+  c->lf_valid = true;
   hipLaunchKernelGGL(k_reset_bad, dim3(1), dim3(1), 0, s, c->d_state);
   for (int k = 0; k < L.ntmax; ++k) {
     const int n_finish = L.ntmax - k, n_bulk = L.ntmax - k - 1;

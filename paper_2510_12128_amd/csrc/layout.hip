@@ -92,7 +92,6 @@ int plan_layout(const nugpr_problem* pb, uint32_t flags, Layout& L) {
   const size_t vec = (size_t)L.n * L.T * sizeof(double);      // fp64 vector blocks (fp32 mode uses half)
   L.o_cl = take(cur, sizeof(ClusterInfo) * L.nc);
   L.o_Kd = take(cur, L.kd_elems * f);
-  L.o_Lf = take(cur, L.kd_elems * f);
   L.o_G = take(cur, L.kd_elems * f);
   L.o_C = take(cur, (size_t)L.ldc * L.ldc * f);
   L.o_Kd2 = take(cur, L.kd_elems * f);

@@ -160,7 +160,7 @@ struct Layout {
   uint64_t kd_elems = 0, wt_elems = 0;
   uint64_t rows_pad = 0;      // sum of ld over the clusters
   // byte offsets into the workspace
-  size_t o_cl = 0, o_Kd = 0, o_Lf = 0, o_G = 0, o_C = 0, o_Wd = 0, o_Wt = 0, o_reps = 0;
+  size_t o_cl = 0, o_Kd = 0, o_G = 0, o_C = 0, o_Wd = 0, o_Wt = 0, o_reps = 0;
   size_t o_Q0 = 0;                   // K' z_0 kept from the base loss
   size_t o_Kd2 = 0, o_C2 = 0;        // spare K_diag and C: second matrix of a pair assembly
   size_t o_B = 0, o_X = 0, o_R = 0, o_Z = 0, o_D = 0, o_Q = 0, o_V = 0, o_U = 0;
@@ -190,6 +190,11 @@ struct nugpr_ctx {
   nugpr::ClusterInfo* d_cl = nullptr;
   float *Kd = nullptr, *Lf = nullptr, *G = nullptr, *C = nullptr, *Wd = nullptr, *Wt = nullptr, *reps = nullptr;
   float *Kd2 = nullptr, *C2 = nullptr;     // spare blocks (launch_build_pair / swap_pair)
+  // The Cholesky factor L has no storage of its own: the factorisation writes it into the spare K_diag blocks
+  // (Lf = Kd2 at that time).  After the factorisation only the inverse factor G is applied; L itself is needed
+  // for the right-hand sides B = [y | L Z], formed in the same call, and by nugpr_export.  The next lengthscale
+  // pair assembly overwrites it (lf_valid).
+  bool lf_valid = false;
   // lengthscale-scaled coordinates in fp64, in MFMA operand order, and their squared norms:
   // of the points (padded row numbering) and of the representatives
   double *Xs = nullptr, *Xn = nullptr, *Rs = nullptr, *Rn = nullptr;
