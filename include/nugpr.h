@@ -182,6 +182,16 @@ const char* nugpr_last_error_string(void);
  * (nugpr_export and the products on widths that read whole rows fill them in first). */
 int nugpr_build_blocks(nugpr_ctx* ctx, const double* theta /*HOST*/, void* stream);
 
+/* Replaces the basis W by Nystrom weights at theta (Section 3.3 defines the rank-1 block 1 1^T and leaves higher
+ * ranks open): W_i = k(X_i, R_i) (k(R_i, R_i) + jitter alpha I)^-1, every point expressed through all r
+ * representatives of its cluster by kernel interpolation, in fp64, stored in fp32.  The basis then stays fixed
+ * (it does NOT follow later theta, so the loss remains smooth in theta) until the next call; products use the
+ * dense-W strips.  jitter = 0 selects 1e-4: the weights of nearby representatives are large and of mixed sign,
+ * and whatever they multiply, the fp32 rounding of the stored coupling matrix included, is amplified by their size;
+ * 1e-4 keeps them of order 10 at no visible cost in approximation error.  rank <= 128.  The preconditioner must be factored (again)
+ * afterwards: nugpr_precond_factor before any solve.  Only enqueues. */
+int nugpr_set_nystrom_basis(nugpr_ctx* ctx, const double* theta /*HOST*/, double jitter, void* stream);
+
 /* Block-Jacobi preconditioner, eq. (cholesky factorization): per cluster
  * K_ii = L_i L_i^T (the paper's R_i = L_i^T) from the CURRENT K_diag, the explicit
  * inverses L_i^-1 (the paper applies R^-1 as an explicit inverse, Table 2), and the

@@ -86,6 +86,8 @@ def load_library():
     lib.nugpr_last_error_string.argtypes = []
     lib.nugpr_build_blocks.restype = C.c_int
     lib.nugpr_build_blocks.argtypes = [vp, dp, vp]
+    lib.nugpr_set_nystrom_basis.restype = C.c_int
+    lib.nugpr_set_nystrom_basis.argtypes = [vp, dp, C.c_double, vp]
     lib.nugpr_precond_factor.restype = C.c_int
     lib.nugpr_precond_factor.argtypes = [vp, dp, ip, vp]
     lib.nugpr_matvec.restype = C.c_int
@@ -266,6 +268,10 @@ class Context:
     def nugpr_build_blocks(self, theta):
         th = self._theta(theta)
         return _check(self.lib.nugpr_build_blocks(self.handle, _dptr(th), self._stream()))
+
+    def nugpr_set_nystrom_basis(self, theta, jitter=0.0):
+        th = self._theta(theta)
+        return _check(self.lib.nugpr_set_nystrom_basis(self.handle, _dptr(th), float(jitter), self._stream()))
 
     def nugpr_precond_factor(self):
         ld, bad = C.c_double(), C.c_int32()

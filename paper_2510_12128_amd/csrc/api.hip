@@ -482,6 +482,11 @@ int nugpr_build_blocks(nugpr_ctx* c, const double* theta, void* stream) {
   return launch_build(c, theta, as_stream(stream), !kd_lower_suffices(c));
 }
 
+int nugpr_set_nystrom_basis(nugpr_ctx* c, const double* theta, double jitter, void* stream) {
+  if (!c) { set_error("ctx is null"); return NUGPR_ERR_INVALID; }
+  return launch_nystrom_basis(c, theta, jitter, as_stream(stream));
+}
+
 int nugpr_precond_factor(nugpr_ctx* c, double* logdet_M, int32_t* bad_cluster, void* stream) {
   if (!c) { set_error("ctx is null"); return NUGPR_ERR_INVALID; }
   if (!c->built) { set_error("precond_factor needs build_blocks first"); return NUGPR_ERR_STATE; }

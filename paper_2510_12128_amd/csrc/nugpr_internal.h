@@ -301,6 +301,10 @@ int ensure_kd_upper(nugpr_ctx* c, hipStream_t s);
 int ensure_c_upper(nugpr_ctx* c, hipStream_t s);
 int launch_export(nugpr_ctx* c, int what, int index, float* dst, int64_t ld, hipStream_t s);
 
+// basis.hip ------------------------------------------------------------------
+// W_i = k(X_i, R_i) (k(R_i, R_i) + jitter alpha I)^-1 at theta (jitter_rel = 0 selects 1e-4); rank <= 128
+int launch_nystrom_basis(nugpr_ctx* c, const double* theta, double jitter_rel, hipStream_t s);
+
 // eigmin.hip -----------------------------------------------------------------
 // smallest eigenvalue of the kernel matrix of the representatives at theta: off-diagonal part from (c->C + c->Clo),
 // the scalar alpha on the diagonal, diagonal blocks for the preconditioner recomputed from the representatives

@@ -693,6 +693,64 @@ def test_user_supplied_representatives_and_dense_basis(lib):
     ctx.close()
 
 
+@pytest.mark.parametrize("case", ["ragged-t16", "overlap", "r128"])
+def test_nystrom_basis_matches_oracle(lib, case):
+    # Section 3.3 fixes the basis only at rank one; nugpr_set_nystrom_basis builds W_i = k(X_i, R_i) k(R_i, R_i)^-1
+    # on the device.  The basis is an input of the method (theta independent once built): the oracle is handed
+    # the library's W, after it has been compared with the formula evaluated in numpy
+    w = {"ragged-t16": lambda: small_ragged(seed=4, t=16),
+         # clusters moved together: the one-hot K' is indefinite here, the Nystrom one is not
+         "overlap": lambda: I.make_config("C1", "wide", centre_shrink=2.0),
+         "r128": lambda: I.make_small(n_clusters=5, sizes=[200, 131, 128, 260, 190], d=3, rank=128, t=8, seed=33, ell=1.2,
+                                      spacing=4.0, sigma_blob=0.9, tol=1e-6, max_iter=100)}[case]()
+    print("case", w.name, flush=True)
+    ctx = make_ctx(lib, w)
+    theta_b = w.theta * (1.0 + 0.02 * np.sin(np.arange(w.theta.shape[0])))      # the basis point: not the evaluation point
+    ctx.nugpr_set_nystrom_basis(theta_b)
+    plain = oracle_problem(w)
+    ell, alpha, _ = O.split_theta(theta_b, w.d)
+    Ws = []
+    for i in range(w.n_clusters):
+        Wi = ctx.nugpr_export(B.EXPORT_W, i).cpu().numpy().astype(np.float64)
+        Xi = plain.X[w.offsets[i]:w.offsets[i + 1]]
+        Ri = plain.reps[i * w.rank:(i + 1) * w.rank]
+        Krr = O.rbf(Ri, Ri, ell, alpha) + 1e-4 * alpha * np.eye(w.rank)
+        ref = np.linalg.solve(Krr, O.rbf(Ri, Xi, ell, alpha)).T
+        # the weights themselves are ill-conditioned (kernel matrix of nearby points); what is well defined is
+        # what they are used for: the interpolated kernel rows W_i Krr against k(X_i, R_i)
+        assert relmax(Wi @ Krr, ref @ Krr) < 1e-4, ("W", i, relmax(Wi @ Krr, ref @ Krr))
+        Ws.append(Wi)
+    prob = O.Problem(w.X, w.y, w.offsets, w.probes, w.rank, Ws=Ws)
+    if case == "overlap":
+        assert np.linalg.eigvalsh(plain.dense(w.theta))[0] < 0 < np.linalg.eigvalsh(prob.dense(w.theta))[0]
+    ctx.nugpr_build_blocks(w.theta)
+    op = prob.operator(w.theta)
+    rng = np.random.default_rng(81)
+    for ncols in (1, w.n_probes + 1):
+        D = rng.standard_normal((w.n, ncols)).astype(np.float32)
+        Q = ctx.nugpr_matvec(D).cpu().numpy().astype(np.float64)
+        assert relmax(Q, op(D.astype(np.float64))) < 1e-5
+    with pytest.raises(B.NugprError) as e:            # a new basis needs a new factorisation call
+        ctx.nugpr_mll(w.theta)
+    assert e.value.code == B.NUGPR_ERR_STATE
+    assert ctx.nugpr_precond_factor()[0] == 0
+    fac = O.Factor(prob, w.theta)
+    ref = O.mll(prob, fac, w.theta, w.tol, w.max_iter)
+    out = ctx.nugpr_mll(w.theta)
+    assert out["code"] == 0
+    for key in ("quad", "logdet", "nll"):
+        assert abs(out[key] - ref[key]) <= 1e-4 * abs(ref[key]), (key, out[key], ref[key])
+    phi = np.log(w.theta)
+    step = ctx.nugpr_train_step(phi, np.zeros(ctx.p), np.zeros(ctx.p), 0)
+    assert step["code"] == 0
+    g = O.fd_gradient(prob, fac, phi, w.fd_step, w.tol, w.max_iter)
+    gerr = float(np.linalg.norm(step["grad"] - g) / np.linalg.norm(g))
+    record_metric("nystrom:" + case, nll_err=abs(out["nll"] - ref["nll"]) / abs(ref["nll"]), grad_err=gerr,
+                  iters=int(out["max_iters_used"]))
+    assert gerr < 1e-4, gerr
+    ctx.close()
+
+
 def test_stale_factor_is_reused_across_theta(lib):
     # Section 3.2: the factor of theta_0 preconditions K(theta') too; eq. (logdet) stays exact
     w = small_ragged(seed=11, t=16)
