@@ -1,4 +1,4 @@
-// Strip GEMM: the bandwidth-bound product of a stored fp32 matrix strip (64 rows,
+// Strip GEMM: the product of a stored fp32 matrix strip (64 rows,
 // any number of columns) with a tall-skinny vector block of T <= 33 columns.
 //
 // Every matrix of the hot path is applied through this one kernel:
@@ -8,19 +8,29 @@
 //                                                          applied as explicit inverses (Table 2)
 //   tril(L_i) Z_i                                        -- probe right-hand sides
 //
-// Design (gfx950, wave64): a workgroup of 4 waves owns a strip of 64 matrix rows,
-// each wave 16 of them, and walks along the rows in chunks of 64 columns so every
-// matrix element is read from HBM exactly once, with 16-byte loads, for all T columns.
-// Lane (m, kg) of a wave loads float4 A[row m][c + 16 s + 4 kg ..]; the four components
-// feed four 16x16x4 MFMAs, whose contraction index is the kg of the lane, so the column
-// permutation inside a 16-column group is absorbed by reading the matching rows of
-// the vector block from LDS (stored as 4-vectors over 4 consecutive rows).
-// Columns 1..T-1 (the probes) go through the matrix cores in groups of 16; column 0
-// (y) rides on the vector ALUs from the same registers, so T = 17 costs one MFMA
-// group, not two.  The vector block chunk is double-buffered in LDS.  The matrix
-// chunk lives in ONE register set: slot s is reloaded with the next chunk's data right
-// after it has been consumed, so each load has a full chunk period to land while few
-// registers are live, and occupancy hides the rest of the HBM latency.
+// Two kernels share the tiling and the arithmetic and differ in how the matrix reaches the
+// matrix cores:
+//   k_strip       the fp32 mode and single-column products: every wave loads its own matrix
+//                 rows into registers (described next);
+//   k_strip_ring  the fp64 mode with two or more columns, i.e. every launch of the training
+//                 path: a fifth wave streams matrix tiles and vector slabs into an LDS ring
+//                 with LDS-direct loads while four waves consume them, and the tiles of a
+//                 symmetric block are read once for the two strips they serve (its own
+//                 description stands in front of it, further down).
+//
+// Common design (gfx950, wave64): a workgroup owns a strip of 64 matrix rows, each of four
+// consumer waves 16 of them, and walks along the rows in chunks of 64 columns with 16-byte
+// loads, for all T columns at once.  Lane (m, kg) of a wave holds float4
+// A[row m][c + 16 s + 4 kg ..]; the four components feed four 16x16x4 MFMAs, whose
+// contraction index is the kg of the lane, so the column permutation inside a 16-column
+// group is absorbed by reading the matching rows of the vector block from LDS (stored as
+// 4-vectors over 4 consecutive rows).  Columns 1..T-1 (the probes) go through the matrix
+// cores in groups of 16; column 0 (y) rides on the vector ALUs from the same registers, so
+// T = 17 costs one MFMA group, not two.
+// k_strip: the vector block chunk is double-buffered in LDS; the matrix chunk lives in ONE
+// register set: slot s is reloaded with the next chunk's data right after it has been
+// consumed, so each load has a full chunk period to land while few registers are live, and
+// occupancy hides the rest of the HBM latency.
 //
 // Two arithmetic modes, same data movement:
 //   ACC64 = true   vector blocks are fp64; the fp32 matrix entries are widened in
