@@ -96,6 +96,10 @@ def main():
     ap.add_argument("--cpu-clusters", type=int, default=16, help="clusters in the CPU-oracle sample (0 = skip)")
     ap.add_argument("--kv-reps", type=int, default=20)
     ap.add_argument("--no-trajectory", action="store_true", help="skip the second (Adam fed back) run")
+    ap.add_argument("--compensate", action="store_true",
+                    help="solve with the compensated operator K'' of eqs. (krep), (kypp) (needed where the "
+                         "uncompensated K' is not positive definite: configuration 5)")
+    ap.add_argument("--max-iter", type=int, default=0, help="PCG iteration limit (0 = the configuration's own)")
     ap.add_argument("--copy-probe-gib", type=float, default=0.0,
                     help="also run a plain copy kernel of this many GiB three times (reference dispatch for "
                          "scaling hardware HBM byte counters)")
@@ -123,8 +127,10 @@ def main():
         torch.cuda.synchronize(dev)
         del src, dst
     w = inputs.make_config(args.config)
-    ctx = Context(w.X, w.y, w.offsets, w.probes, w.rank, tol=w.tol, max_iter=w.max_iter, fd_step=w.fd_step,
-                  lr=w.lr, isotropic=w.isotropic, device=dev, acc_fp32=(args.acc == "fp32"))
+    max_iter = args.max_iter if args.max_iter > 0 else w.max_iter
+    ctx = Context(w.X, w.y, w.offsets, w.probes, w.rank, tol=w.tol, max_iter=max_iter, fd_step=w.fd_step,
+                  lr=w.lr, isotropic=w.isotropic, device=dev, acc_fp32=(args.acc == "fp32"),
+                  compensate=args.compensate)
     p, T = ctx.p, ctx.T
     phi0 = np.log(w.theta)
     zeros = np.zeros(p)
@@ -162,7 +168,7 @@ def main():
     ctx.nugpr_profile_enable(False)
     stats = ctx.nugpr_stats_read(reset=True)
     total_s = t1 - t0
-    evals = args.steps * (1 + 2 * p)
+    evals = stats["loss_evals"]             # = steps * (1 + 2 p) when every step ends with status 0
     evals_per_s = evals / total_s
 
     # ---- second figure: the same number of steps with Adam's update fed back (a training run) ----
@@ -186,7 +192,7 @@ def main():
         done = len(tr_ms)
         trajectory = {"what": "the same steps with Adam's update fed back (theta moves; later solves need more "
                               "PCG iterations); context only, not `value`",
-                      "evals_per_s": done * (1 + 2 * p) / (tt1 - tt0), "ms_per_step": (tt1 - tt0) * 1e3 / done,
+                      "evals_per_s": tstats["loss_evals"] / (tt1 - tt0), "ms_per_step": (tt1 - tt0) * 1e3 / done,
                       "step_ms": [round(x, 2) for x in tr_ms], "status_codes": tr_codes,
                       "per_step": per_step(tstats, done)}
 
@@ -288,7 +294,8 @@ def main():
                                "(factor + %d loss evaluations + Adam)" % (args.config, n, ctx.d, nc, r, ctx.t,
                                                                           w.tol, 1 + 2 * p),
                    "protocol": "every timed step starts from theta_0 (Adam's update is computed, not fed back)",
-                   "acc": args.acc, "status_codes": codes, "step_ms": [round(x, 2) for x in step_ms],
+                   "acc": args.acc, "operator": "K'' (compensated, eq. (kypp))" if args.compensate else
+                   "K' (eq. (odsplit))", "max_iter": max_iter, "status_codes": codes, "step_ms": [round(x, 2) for x in step_ms],
                    "per_step": per_step(stats, args.steps)},
         "pcg_iters_per_solve": stats["pcg_iterations"] / max(stats["pcg_solves"], 1),
         "kv_ms": kv_ms,

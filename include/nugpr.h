@@ -334,7 +334,7 @@ int nugpr_profile_kernel_name(const nugpr_ctx* ctx, int32_t ncols, char* buf /*H
 /* Work counters of a context since nugpr_create or the last reset (host bookkeeping, no GPU work):
  * what the calls so far did in units of the path's steps (Algorithm 1 / ComputeLoss). */
 typedef struct {
-  int64_t loss_evals;        /* loss evaluations (nugpr_mll, and those inside nugpr_train_step)          */
+  int64_t loss_evals;        /* loss evaluations that returned a value (nugpr_mll, nugpr_train_step)     */
   int64_t pcg_solves;        /* batched PCG solves                                                        */
   int64_t pcg_iterations;    /* iterations summed over the solves (a solve counts its slowest column)     */
   int64_t pcg_iterations_max;/* most iterations any solve took                                            */

@@ -687,8 +687,11 @@ static int mll_impl(nugpr_ctx* c, const double* theta, nugpr_mll_result* res, bo
   if (!theta) { set_error("theta is null"); return NUGPR_ERR_INVALID; }
   int rc = set_operator(c, theta, allow_reuse, s);
   if (rc) return rc;
-  c->stats.loss_evals += 1;
-  if (c->params.flags & NUGPR_LOGDET_PADE) return mll_pade(c, res, s);
+  if (c->params.flags & NUGPR_LOGDET_PADE) {
+    rc = mll_pade(c, res, s);
+    if (rc >= 0 && !no_value(rc)) c->stats.loss_evals += 1;
+    return rc;
+  }
   const int T = L.T, max_iter = c->params.max_iter;
   std::vector<int32_t> iters(T);
   std::vector<double> alpha((size_t)max_iter * T), beta((size_t)max_iter * T);
@@ -711,6 +714,7 @@ static int mll_impl(nugpr_ctx* c, const double* theta, nugpr_mll_result* res, bo
   }
   res->logdet = c->logdetM + (L.t > 0 ? est / L.t : 0.0);
   res->nll = 0.5 * (res->quad + res->logdet + (double)L.n * std::log(2.0 * M_PI));
+  c->stats.loss_evals += 1;
   return rc;
 }
 

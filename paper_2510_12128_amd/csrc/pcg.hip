@@ -51,18 +51,24 @@ __global__ __launch_bounds__(256) void k_dot(const VT* __restrict__ A0, const VT
   }
 }
 
+// sum over the 64 lanes of a wave by register shuffles, fixed pairing (lane, lane + 32), (lane, lane + 16), ..;
+// lane 0 holds the result
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+  return v;
+}
+
 __device__ __forceinline__ double sum_partials(const double* __restrict__ partial, int nblocks, int col,
                                                double* red, int tid) {
-  // 256 threads cooperate on one column at a time, fixed order
+  // 256 threads cooperate on one column at a time, fixed order: strided partial sums per thread, shuffles
+  // inside each wave, then the four wave totals through LDS
   double s = 0.0;
   for (int b = tid; b < nblocks; b += 256) s += partial[(int64_t)b * MAX_COLS + col];
-  red[tid] = s;
+  s = wave_sum(s);
+  if ((tid & 63) == 0) red[tid >> 6] = s;
   __syncthreads();
-  for (int w = 128; w > 0; w >>= 1) {
-    if (tid < w) red[tid] += red[tid + w];
-    __syncthreads();
-  }
-  const double r = red[0];
+  const double r = (red[0] + red[1]) + (red[2] + red[3]);
   __syncthreads();
   return r;
 }
