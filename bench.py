@@ -93,7 +93,9 @@ def main():
     ap.add_argument("--config", default="C4")
     ap.add_argument("--acc", choices=["fp64", "fp32"], default="fp64",
                     help="arithmetic of the operator applications over the fp32 stored matrices")
-    ap.add_argument("--cpu-clusters", type=int, default=16, help="clusters in the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--cpu-clusters", type=int, default=-1,
+                    help="clusters in the CPU-oracle sample (0 = skip; default: as many leading clusters as "
+                         "hold 2e8 covariance entries, about 10 - 20 s of host time)")
     ap.add_argument("--kv-reps", type=int, default=20)
     ap.add_argument("--no-trajectory", action="store_true", help="skip the second (Adam fed back) run")
     ap.add_argument("--compensate", action="store_true",
@@ -317,8 +319,11 @@ def main():
     }
     if trajectory is not None:
         line["trajectory"] = trajectory
-    if args.cpu_clusters > 0:
-        line["cpu_baseline"] = cpu_baseline(w, args.cpu_clusters)
+    if args.cpu_clusters != 0:
+        k = args.cpu_clusters
+        if k < 0:               # bounded sample: leading clusters holding at most 2e8 entries of K_diag
+            k = max(1, int(np.searchsorted(np.cumsum(sizes ** 2), 2.05e8, side="right")))
+        line["cpu_baseline"] = cpu_baseline(w, k)
     ctx.close()
     print(json.dumps(line))
 
