@@ -6,9 +6,10 @@
 // Everything is tiled in 64 x 64 fp32 tiles whose products run on the matrix cores
 // (v_mfma_f32_16x16x4_f32, four waves per tile, each 32 x 32).
 //   Cholesky: left-looking over tile columns.  Step k: every tile (m, k), m >= k, gets
-//     A[m,k] - sum_{j<k} L[m,j] L[k,j]^T in one batched launch over clusters; the
-//     workgroup that owns the diagonal tile factors it in LDS and also writes its
-//     inverse; a second launch multiplies the tiles below by that inverse.
+//     A[m,k] - sum_{j<k} L[m,j] L[k,j]^T in one batched launch over clusters (most of
+//     the sum one step ahead, see k_potrf_update); the workgroup that owns the diagonal
+//     tile factors and inverts it in registers; a second launch multiplies the tiles
+//     below by that inverse.
 //   Inverse: the binary-tree identity
 //     [L11 0; L21 L22]^-1 = [Y11 0; -Y22 L21 Y11, Y22]
 //     applied bottom-up over tile ranges, two batched products per level
@@ -149,6 +150,18 @@ __device__ __forceinline__ void for_each_acc(v4f (&acc)[2][2], int tid, F f) {
         f(wy * 32 + 16 * i + 4 * (lane >> 4) + v, wx * 32 + 16 * j + (lane & 15), acc[i][j][v]);
 }
 
+// Blocked storage seen tile by tile: element (r, q) of the 64 x 64 tile (tr, tc) of a square block lies at
+// tile_base(ld, tr, tc) + tile_offset(r, q) (= blocked_index(ld, 64 tr + r, 64 tc + q)).  The base is uniform over a
+// workgroup and computed once; the offset is a few 32-bit shifts, and with the accumulator coordinates of
+// for_each_acc most of it is a compile-time constant.  (Index arithmetic per element in 64 bits cost the update
+// launch of the Cholesky tens of microseconds of vector instructions, which also keep the matrix cores waiting.)
+__device__ __forceinline__ uint64_t tile_base(uint32_t ld, int tr, int tc) {
+  return (uint64_t)tr * TILE * ld + (uint64_t)tc * (2 * TILE * BLK_COLS);
+}
+__device__ __forceinline__ uint32_t tile_offset(int r, int q) {
+  return (uint32_t)((q >> 5) * (TILE * BLK_COLS) + (((r >> 4) * 2 + ((q & 31) >> 4)) * FRAG) + (r & 15) * 16 + (q & 15));
+}
+
 // Workgroup -> (cluster, item) for a launch of `per` items for each of `nc` clusters: a 1-D grid of
 // die_grid(per, nc) workgroups.  Workgroups go round-robin to the 8 dies, each with an L2 of its own: with
 // the cluster as the slow index of a plain grid the tiles of one cluster, which all read the same panel,
@@ -179,31 +192,39 @@ __device__ __forceinline__ bool die_local_item(int per, int nc, int& cluster, in
 // ---------------------------------------------------------------------------
 // Left-looking, with the bulk of every tile's update done one step ahead.  The launch of step k has two
 // kinds of workgroups:
-//   finish  tile (m, k), m >= k: subtract the contribution of column k - 1, the only one that was not final
-//           when the bulk was computed; the workgroup of the diagonal tile then factors and inverts it in LDS
-//   bulk    tile (m, k + 1), m >= k + 1: L <- A - sum over the columns < k, all final by now
+//   diagonal  tile (k, k): subtract the contribution of column k - 1 (the only one that was not final when the
+//             bulk of this tile was computed), then factor and invert the tile
+//   row m > k two tiles of the same block row, one after the other:
+//             finish (m, k): subtract the contribution of column k - 1, as above;
+//             bulk (m, k + 1): L <- A - sum over the columns < k, all final by now
 // The factorisation of the diagonal tile is serial and keeps one workgroup per cluster busy for tens of
 // microseconds; with the long products of the NEXT column in the same launch the rest of the chip has work
 // meanwhile, where a launch that only finished column k would idle behind its diagonal tiles.
-// Grid: the finish workgroups of all clusters first (n_finish per cluster), then the bulk ones.
+// Grid order = start order (workgroups are handed out in index order, a few thousand take tens of
+// microseconds): the diagonal tiles of all clusters first, since the launch cannot end before they do.  Finish
+// and bulk of a block row share a workgroup because, as workgroups of their own, the short finish ones either
+// delay the start of the long ones or wait behind them for a free slot: measured 25 us per launch.
 __global__ __launch_bounds__(256) void k_potrf_update(const ClusterInfo* __restrict__ cl, const float* __restrict__ Kd,
                                                       float* __restrict__ Lf, float* __restrict__ G, int k,
-                                                      int n_finish, int n_bulk, int grid_finish, int nc,
-                                                      PcgState* __restrict__ st) {
-  // the operand stages and, once the products are done, the tile being factored share one piece of LDS
-  // (34 KB per workgroup with the inverse: four workgroups per compute unit instead of three)
-  static_assert(2 * TILE * SP >= TILE * (TILE + 1), "the factored tile must fit in the operand stages");
+                                                      int n_rows, int grid_diag, int nc, PcgState* __restrict__ st) {
+  // the operand stages and, once the products are done, the tile on its way into the registers of the
+  // factorisation (then its exchange buffers) share one piece of LDS: 16.5 KB per workgroup
+  static_assert(2 * TILE * SP >= TILE * (TILE + 1), "the tile to be factored must fit in the operand stages");
   __shared__ __attribute__((aligned(16))) float stage[2 * TILE * SP];
-  __shared__ float sI[TILE][TILE + 1];
   float (*sA)[SP] = reinterpret_cast<float (*)[SP]>(stage);
   float (*sB)[SP] = reinterpret_cast<float (*)[SP]>(stage + TILE * SP);
   float (*sT)[TILE + 1] = reinterpret_cast<float (*)[TILE + 1]>(stage);
-  const bool bulk = (int)blockIdx.x >= grid_finish;
+  const int id = (int)blockIdx.x;
+  const bool diag = id < grid_diag;
   int ci, item;
-  if (!die_local_item(bulk ? n_bulk : n_finish, nc, ci, item, bulk ? (int)blockIdx.x - grid_finish : (int)blockIdx.x)) return;
+  if (diag) {
+    if (!die_local_item(1, nc, ci, item, id)) return;
+  } else {
+    if (!die_local_item(n_rows, nc, ci, item, id - grid_diag)) return;
+    item += 1;
+  }
   const ClusterInfo c = cl[ci];
-  const int col = bulk ? k + 1 : k;            // tile column this workgroup works on
-  const int mt = col + item;
+  const int mt = k + item;                     // block row of this workgroup
   if (mt >= (int)c.nt) return;
   const int tid = threadIdx.x;
   const int b = (int)c.b;
@@ -212,97 +233,121 @@ __global__ __launch_bounds__(256) void k_potrf_update(const ClusterInfo* __restr
   v4f acc[2][2];
   zero_acc(acc);
   Operand oa{L, c.ld, mt * TILE, b, 0};
-  Operand ob{L, c.ld, col * TILE, b, 0};
-  if (bulk) tile_gemm<false, false>(acc, oa, ob, 0, k * TILE, sA, sB, tid);
-  else if (k > 0) tile_gemm<false, false>(acc, oa, ob, (k - 1) * TILE, k * TILE, sA, sB, tid);
+  Operand ob{L, c.ld, k * TILE, b, 0};
+  if (k > 0) tile_gemm<false, false>(acc, oa, ob, (k - 1) * TILE, k * TILE, sA, sB, tid);
   // what the products are subtracted from: the assembled block, or the bulk result of the step before
-  const float* base = (bulk || k == 0) ? A : L;
-  if (bulk || mt != k) {
-    for_each_acc(acc, tid, [&](int r, int q, float v) {
-      const uint64_t at = blocked_index(c.ld, mt * TILE + r, col * TILE + q);
-      L[at] = base[at] - v;
-    });
+  const float* base = k == 0 ? A : L;
+  if (!diag) {
+    {
+      const uint64_t tb = tile_base(c.ld, mt, k);
+      const float* bt = base + tb;
+      float* lt = L + tb;
+      for_each_acc(acc, tid, [&](int r, int q, float v) {
+        const uint32_t at = tile_offset(r, q);
+        lt[at] = bt[at] - v;
+      });
+    }
+    zero_acc(acc);
+    Operand oc{L, c.ld, (k + 1) * TILE, b, 0};
+    if (k > 0) tile_gemm<false, false>(acc, oa, oc, 0, k * TILE, sA, sB, tid);
+    {
+      const uint64_t tb = tile_base(c.ld, mt, k + 1);
+      const float* at_ = A + tb;
+      float* lt = L + tb;
+      for_each_acc(acc, tid, [&](int r, int q, float v) {
+        const uint32_t at = tile_offset(r, q);
+        lt[at] = at_[at] - v;
+      });
+    }
     return;
   }
-  // ---- diagonal tile: factor in LDS; rows/cols past the cluster end behave as identity ----
+  // ---- diagonal tile: factor and invert it; rows/cols past the cluster end behave as identity ----
+  // This workgroup is the critical path of the whole launch (the next launch needs its result) and shares its
+  // compute unit with workgroups that keep the matrix cores busy, which slows every instruction it issues: so
+  // the tile lives in REGISTERS and a pivot costs one LDS round trip and one barrier.  Wave w owns the columns
+  // 16 w .. 16 w + 15 of all 64 rows, lane i the row i: a[u] = A[i][16 w + u], y[u] = Y[i][16 w + u].
+  // Elimination without square roots (A = Lu D Lu^T, Lu unit lower) applied to [A | I]:
+  //   pivot j:  m_i = a_ij / d_j (i > j);  a_ic -= m_i a_cj (c > j);  y_ic -= m_i y_jc (c <= j)
+  // leaves a_ic = (Lu D)_ic below the diagonal, d on it, and Y = Lu^-1; then L = Lu D^1/2, L^-1 = D^-1/2 Lu^-1.
+  // Per pivot the owners publish column j of A (one value per row) and row j of Y in LDS, double-buffered so
+  // that one barrier per pivot is enough.
   __syncthreads();                              // every wave is done reading the operand stages
   const int valid = min(TILE, b - k * TILE);
+  const float* bkk = base + tile_base(c.ld, k, k);
   for_each_acc(acc, tid, [&](int r, int q, float v) {
-    float x = base[blocked_index(c.ld, k * TILE + r, k * TILE + q)] - v;
+    float x = bkk[tile_offset(r, q)] - v;
     if (r >= valid || q >= valid) x = (r == q) ? 1.f : 0.f;
     sT[r][q] = x;
   });
   __syncthreads();
-  // Right-looking elimination with ONE barrier per pivot: column j is left unscaled (its entries are read as
-  // a_ij a_cj / d_j by the update) and the division by sqrt(d_j) is applied to all columns in a pass at the
-  // end; d_j = sT[j][j] is final once pivot j - 1 has been processed and is not touched afterwards.
+  const int w = tid >> 6, i = tid & 63;
+  float a[16], y[16];
+#pragma unroll
+  for (int u = 0; u < 16; ++u) {
+    a[u] = sT[i][16 * w + u];
+    y[u] = (16 * w + u == i) ? 1.f : 0.f;
+  }
+  __syncthreads();                              // sT is dead from here on: its memory holds the exchange buffers
+  float* colbuf = stage;                        // [2][64]  column j of A, by row
+  float* rowbuf = stage + 2 * TILE;             // [2][64]  row j of Y
+  float* dvec = stage + 4 * TILE;               // [64]     the pivots d_j
   bool bad = false;
-  for (int j = 0; j < TILE - 1; ++j) {
-    float dj = sT[j][j];
-    if (!(dj > 0.f) || !(dj < INFINITY)) { bad = true; dj = 1.f; }
-    const float rd = 1.f / dj;
-    const int i = tid >> 2;                // trailing update, row i, columns j < cc <= i
-    if (i > j) {
-      const float lij = sT[i][j] * rd;
-      for (int cc = j + 1 + (tid & 3); cc <= i; cc += 4) sT[i][cc] = fmaf(-lij, sT[cc][j], sT[i][cc]);
-    }
-    __syncthreads();
-  }
-  {
-    const float dl = sT[TILE - 1][TILE - 1];
-    if (!(dl > 0.f) || !(dl < INFINITY)) bad = true;
-  }
-  __syncthreads();
-  // scaling pass: L_ij = a_ij / sqrt(d_j), L_jj = sqrt(d_j) (non-positive pivots behave as 1, as above);
-  // the diagonal is read before anything is written
-  {
-    const int i = tid >> 2;
-    float col[TILE / 4];
+#pragma unroll 1
+  for (int jb = 0; jb < 4; ++jb) {
 #pragma unroll
-    for (int u = 0; u < TILE / 4; ++u) {
-      const int j = 4 * u + (tid & 3);
-      float dj = sT[j][j];
-      if (!(dj > 0.f) || !(dj < INFINITY)) dj = 1.f;
-      const float sj = sqrtf(dj);
-      col[u] = j < i ? sT[i][j] / sj : (j == i ? sj : 0.f);
-    }
-    __syncthreads();
+    for (int jj = 0; jj < 16; ++jj) {
+      const int j = 16 * jb + jj;
+      float* cb = colbuf + (j & 1) * TILE;
+      float* rb = rowbuf + (j & 1) * TILE;
+      if (w == jb) cb[i] = a[jj];
+      if (i == j) {
 #pragma unroll
-    for (int u = 0; u < TILE / 4; ++u) {
-      const int j = 4 * u + (tid & 3);
-      if (j <= i) sT[i][j] = col[u];
+        for (int u = 0; u < 16; u += 4) *reinterpret_cast<float4*>(rb + 16 * w + u) = make_float4(y[u], y[u + 1], y[u + 2], y[u + 3]);
+      }
+      __syncthreads();
+      float dj = cb[j];
+      if (!(dj > 0.f) || !(dj < INFINITY)) { bad = true; dj = 1.f; }
+      if (tid == 0) dvec[j] = dj;
+      const float mi = i > j ? cb[i] / dj : 0.f;
+      if (w > jb) {                             // all 16 columns of this wave lie right of the pivot
+#pragma unroll
+        for (int u = 0; u < 16; u += 4) {
+          const float4 cj = *reinterpret_cast<const float4*>(cb + 16 * w + u);
+          a[u] = fmaf(-mi, cj.x, a[u]); a[u + 1] = fmaf(-mi, cj.y, a[u + 1]);
+          a[u + 2] = fmaf(-mi, cj.z, a[u + 2]); a[u + 3] = fmaf(-mi, cj.w, a[u + 3]);
+        }
+      } else if (w == jb) {
+#pragma unroll
+        for (int u = jj + 1; u < 16; ++u) a[u] = fmaf(-mi, cb[16 * w + u], a[u]);
+      }
+      if (w <= jb) {                            // Y_j is zero right of column j
+#pragma unroll
+        for (int u = 0; u < 16; u += 4) {
+          const float4 yj = *reinterpret_cast<const float4*>(rb + 16 * w + u);
+          y[u] = fmaf(-mi, yj.x, y[u]); y[u + 1] = fmaf(-mi, yj.y, y[u + 1]);
+          y[u + 2] = fmaf(-mi, yj.z, y[u + 2]); y[u + 3] = fmaf(-mi, yj.w, y[u + 3]);
+        }
+      }
     }
   }
-  __syncthreads();
+  __syncthreads();                              // dvec complete
   if (bad && tid == 0) atomicMin(&st->bad_cluster, ci);
-  // ---- inverse of the lower-triangular tile: column cc by forward substitution, four lanes per column
-  // sharing each row's sum (lanes 4 cc .. 4 cc + 3 sit in one wave) ----
-  {
-    const int cc = tid >> 2, part = tid & 3;
-    if (part == 0) {
-      for (int i = 0; i < cc; ++i) sI[i][cc] = 0.f;
-      sI[cc][cc] = 1.f / sT[cc][cc];
-    }
-    for (int i = cc + 1; i < TILE; ++i) {
-      // the four lanes of a column run the same iterations, so the shuffles stay inside active lanes; the
-      // column's earlier entries were written by this wave, whose LDS accesses are served in order
-      float sacc = 0.f;
-      for (int j = cc + part; j < i; j += 4) sacc = fmaf(sT[i][j], sI[j][cc], sacc);
-      sacc += __shfl_xor(sacc, 1);
-      sacc += __shfl_xor(sacc, 2);
-      if (part == 0) sI[i][cc] = -sacc / sT[i][i];
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    }
-  }
-  __syncthreads();
+  // L_ic = a_ic / sqrt(d_c) (c < i), sqrt(d_i) on the diagonal;  (L^-1)_ic = y_ic / sqrt(d_i) (c <= i)
+  const float rsi = 1.f / sqrtf(dvec[i]);
   float* Y = G + c.koff;
-  for (int idx = tid; idx < TILE * TILE; idx += 256) {
-    const int r = idx >> 6, q = idx & 63;
-    const uint64_t at = blocked_index(c.ld, k * TILE + r, k * TILE + q);
-    L[at] = (q <= r) ? sT[r][q] : 0.f;
-    Y[at] = (q <= r) ? sI[r][q] : 0.f;
+  const uint64_t at = tile_base(c.ld, k, k) + tile_offset(i, 16 * w);     // one fragment row: 16 floats
+#pragma unroll
+  for (int u = 0; u < 16; u += 4) {
+    float lo[4], yo[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int cc = 16 * w + u + v;
+      const float sc = sqrtf(dvec[cc]);
+      lo[v] = cc < i ? a[u + v] / sc : (cc == i ? sc : 0.f);
+      yo[v] = cc <= i ? y[u + v] * rsi : 0.f;
+    }
+    *reinterpret_cast<float4*>(L + at + u) = make_float4(lo[0], lo[1], lo[2], lo[3]);
+    *reinterpret_cast<float4*>(Y + at + u) = make_float4(yo[0], yo[1], yo[2], yo[3]);
   }
 }
 
@@ -325,7 +370,8 @@ __global__ __launch_bounds__(256) void k_potrf_trsm(const ClusterInfo* __restric
   Operand ob{Y, c.ld, k * TILE, (int)c.ld, 1};          // Y_kk[c][j], lower triangular
   tile_gemm<false, false>(acc, oa, ob, k * TILE, (k + 1) * TILE, sA, sB, tid);
   __syncthreads();
-  for_each_acc(acc, tid, [&](int r, int q, float v) { L[blocked_index(c.ld, mt * TILE + r, k * TILE + q)] = v; });
+  float* lt = L + tile_base(c.ld, mt, k);
+  for_each_acc(acc, tid, [&](int r, int q, float v) { lt[tile_offset(r, q)] = v; });
 }
 
 // ---------------------------------------------------------------------------
@@ -358,9 +404,10 @@ __global__ __launch_bounds__(256) void k_trtri_stage1(const ClusterInfo* __restr
   __syncthreads();
   // mirror block: rows = columns of T (tile tn), columns = rows of T (tile tm)
 
+  float* yt = Y + tile_base(c.ld, tn, tm);
   for (int idx = tid; idx < TILE * TILE; idx += 256) {
     const int q = idx >> 6, r = idx & 63;
-    Y[blocked_index(c.ld, tn * TILE + q, tm * TILE + r)] = sT[r][q];
+    yt[tile_offset(q, r)] = sT[r][q];
   }
 }
 
@@ -383,7 +430,8 @@ __global__ __launch_bounds__(256) void k_trtri_stage2(const ClusterInfo* __restr
   Operand oa{Y, c.ld, tm * TILE, (int)c.b, 1};          // Y22[m][k], nonzero for k <= m
   Operand ob{Y, c.ld, tn * TILE, (int)c.ld, 0};         // OpB[n][k] = T[k][n], read from the mirror block
   tile_gemm<false, false>(acc, oa, ob, mid * TILE, (tm + 1) * TILE, sA, sB, tid);
-  for_each_acc(acc, tid, [&](int r, int q, float v) { Y[blocked_index(c.ld, tm * TILE + r, tn * TILE + q)] = -v; });
+  float* yt = Y + tile_base(c.ld, tm, tn);
+  for_each_acc(acc, tid, [&](int r, int q, float v) { yt[tile_offset(r, q)] = -v; });
 }
 
 // upper triangle <- transpose of the lower triangle (tile list of the assembly kernels)
@@ -396,14 +444,16 @@ __global__ __launch_bounds__(256) void k_mirror(const ClusterInfo* __restrict__ 
   float* Y = G + c.koff;
   const int tid = threadIdx.x;
 
+  const float* ys = Y + tile_base(c.ld, tr, tc);
+  float* yd = Y + tile_base(c.ld, tc, tr);
   for (int idx = tid; idx < TILE * TILE; idx += 256) {
     const int r = idx >> 6, q = idx & 63;
-    sT[r][q] = Y[blocked_index(c.ld, tr * TILE + r, tc * TILE + q)];
+    sT[r][q] = ys[tile_offset(r, q)];
   }
   __syncthreads();
   for (int idx = tid; idx < TILE * TILE; idx += 256) {
     const int r = idx >> 6, q = idx & 63;      // element (r, q) of the destination tile
-    if (tr != tc || q > r) Y[blocked_index(c.ld, tc * TILE + r, tr * TILE + q)] = sT[q][r];
+    if (tr != tc || q > r) yd[tile_offset(r, q)] = sT[q][r];
   }
 }
 
@@ -413,14 +463,16 @@ __global__ __launch_bounds__(256) void k_mirror_square(float* __restrict__ M, ui
   const int tr = (int)(blockIdx.x / (unsigned)nt), tc = (int)(blockIdx.x % (unsigned)nt);
   if (tc >= tr) return;
   const int tid = threadIdx.x;
+  const float* ms = M + tile_base(ld, tr, tc);
+  float* md = M + tile_base(ld, tc, tr);
   for (int idx = tid; idx < TILE * TILE; idx += 256) {
     const int r = idx >> 6, q = idx & 63;
-    sT[r][q] = M[blocked_index(ld, tr * TILE + r, tc * TILE + q)];
+    sT[r][q] = ms[tile_offset(r, q)];
   }
   __syncthreads();
   for (int idx = tid; idx < TILE * TILE; idx += 256) {
     const int r = idx >> 6, q = idx & 63;
-    M[blocked_index(ld, tc * TILE + r, tr * TILE + q)] = sT[q][r];
+    md[tile_offset(r, q)] = sT[q][r];
   }
 }
 
@@ -496,10 +548,10 @@ int launch_factor(nugpr_ctx* c, hipStream_t s) {
   c->lf_valid = true;
   hipLaunchKernelGGL(k_reset_bad, dim3(1), dim3(1), 0, s, c->d_state);
   for (int k = 0; k < L.ntmax; ++k) {
-    const int n_finish = L.ntmax - k, n_bulk = L.ntmax - k - 1;
-    const unsigned grid_finish = die_grid(n_finish, ncm), grid_bulk = n_bulk > 0 ? die_grid(n_bulk, ncm) : 0u;
-    hipLaunchKernelGGL(k_potrf_update, dim3(grid_finish + grid_bulk), dim3(256), 0, s, c->d_cl, c->Kd, c->Lf, c->G, k,
-                       n_finish, n_bulk, (int)grid_finish, ncm, c->d_state);
+    const int n_rows = L.ntmax - k - 1;         // block rows below the diagonal tile
+    const unsigned grid_diag = die_grid(1, ncm), grid_rows = n_rows > 0 ? die_grid(n_rows, ncm) : 0u;
+    hipLaunchKernelGGL(k_potrf_update, dim3(grid_diag + grid_rows), dim3(256), 0, s, c->d_cl, c->Kd, c->Lf, c->G, k,
+                       n_rows, (int)grid_diag, ncm, c->d_state);
     if (k + 1 < L.ntmax)
       hipLaunchKernelGGL(k_potrf_trsm, dim3(die_grid(L.ntmax - k - 1, ncm)), dim3(256), 0, s, c->d_cl, c->Lf, c->G, k,
                          L.ntmax - k - 1, ncm);
