@@ -97,6 +97,10 @@ struct Operand {
 };
 
 // acc[i][j] += OpA[64 x K] * OpB[64 x K]^T over k in [k0, k1), k0/k1 multiples of 32 (all callers pass tile boundaries).
+// The operands enter the matrix instruction in swapped roles (OpB as its row operand), which transposes the
+// 16 x 16 result inside the registers: lane l holds C[row l & 15][columns 4 (l >> 4) .. + 3], four consecutive
+// columns of one row, i.e. 16 bytes of a row-major fragment, and the 64 lanes of a wave one whole fragment
+// (1 KiB in one piece): tiles are read and written with one 16-byte access per lane and fragment.
 template <bool TA, bool TB>
 __device__ __forceinline__ void tile_gemm(v4f (&acc)[2][2], const Operand& A, const Operand& B, int k0, int k1,
                                           float (*sA)[SP], float (*sB)[SP], int tid) {
@@ -121,10 +125,10 @@ __device__ __forceinline__ void tile_gemm(v4f (&acc)[2][2], const Operand& A, co
       const float a1 = sA[wy * 32 + 16 + m][4 * ks + kk];
       const float b0 = sB[wx * 32 + m][4 * ks + kk];
       const float b1 = sB[wx * 32 + 16 + m][4 * ks + kk];
-      acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b0, acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b1, acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b0, acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1, acc[1][1], 0, 0, 0);
+      acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(b0, a0, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(b1, a0, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(b0, a1, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(b1, a1, acc[1][1], 0, 0, 0);
     }
   }
 }
@@ -147,14 +151,23 @@ __device__ __forceinline__ void for_each_acc(v4f (&acc)[2][2], int tid, F f) {
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int v = 0; v < 4; ++v)
-        f(wy * 32 + 16 * i + 4 * (lane >> 4) + v, wx * 32 + 16 * j + (lane & 15), acc[i][j][v]);
+        f(wy * 32 + 16 * i + (lane & 15), wx * 32 + 16 * j + 4 * (lane >> 4) + v, acc[i][j][v]);
+}
+// the same, four consecutive columns at a time: f(row, first column (a multiple of 4), the four values)
+template <class F>
+__device__ __forceinline__ void for_each_acc4(v4f (&acc)[2][2], int tid, F f) {
+  const int wave = tid >> 6, lane = tid & 63;
+  const int wy = wave >> 1, wx = wave & 1;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) f(wy * 32 + 16 * i + (lane & 15), wx * 32 + 16 * j + 4 * (lane >> 4), acc[i][j]);
 }
 
 // Blocked storage seen tile by tile: element (r, q) of the 64 x 64 tile (tr, tc) of a square block lies at
 // tile_base(ld, tr, tc) + tile_offset(r, q) (= blocked_index(ld, 64 tr + r, 64 tc + q)).  The base is uniform over a
 // workgroup and computed once; the offset is a few 32-bit shifts, and with the accumulator coordinates of
-// for_each_acc most of it is a compile-time constant.  (Index arithmetic per element in 64 bits cost the update
-// launch of the Cholesky tens of microseconds of vector instructions, which also keep the matrix cores waiting.)
+// for_each_acc most of it is a compile-time constant.
 __device__ __forceinline__ uint64_t tile_base(uint32_t ld, int tr, int tc) {
   return (uint64_t)tr * TILE * ld + (uint64_t)tc * (2 * TILE * BLK_COLS);
 }
@@ -242,9 +255,10 @@ __global__ __launch_bounds__(256) void k_potrf_update(const ClusterInfo* __restr
       const uint64_t tb = tile_base(c.ld, mt, k);
       const float* bt = base + tb;
       float* lt = L + tb;
-      for_each_acc(acc, tid, [&](int r, int q, float v) {
+      for_each_acc4(acc, tid, [&](int r, int q, const v4f& v) {
         const uint32_t at = tile_offset(r, q);
-        lt[at] = bt[at] - v;
+        const float4 x = *reinterpret_cast<const float4*>(bt + at);
+        *reinterpret_cast<float4*>(lt + at) = make_float4(x.x - v[0], x.y - v[1], x.z - v[2], x.w - v[3]);
       });
     }
     zero_acc(acc);
@@ -254,9 +268,10 @@ __global__ __launch_bounds__(256) void k_potrf_update(const ClusterInfo* __restr
       const uint64_t tb = tile_base(c.ld, mt, k + 1);
       const float* at_ = A + tb;
       float* lt = L + tb;
-      for_each_acc(acc, tid, [&](int r, int q, float v) {
+      for_each_acc4(acc, tid, [&](int r, int q, const v4f& v) {
         const uint32_t at = tile_offset(r, q);
-        lt[at] = at_[at] - v;
+        const float4 x = *reinterpret_cast<const float4*>(at_ + at);
+        *reinterpret_cast<float4*>(lt + at) = make_float4(x.x - v[0], x.y - v[1], x.z - v[2], x.w - v[3]);
       });
     }
     return;
@@ -274,10 +289,11 @@ __global__ __launch_bounds__(256) void k_potrf_update(const ClusterInfo* __restr
   __syncthreads();                              // every wave is done reading the operand stages
   const int valid = min(TILE, b - k * TILE);
   const float* bkk = base + tile_base(c.ld, k, k);
-  for_each_acc(acc, tid, [&](int r, int q, float v) {
-    float x = bkk[tile_offset(r, q)] - v;
-    if (r >= valid || q >= valid) x = (r == q) ? 1.f : 0.f;
-    sT[r][q] = x;
+  for_each_acc4(acc, tid, [&](int r, int q, const v4f& v) {
+    const float4 b4 = *reinterpret_cast<const float4*>(bkk + tile_offset(r, q));
+    const float x[4] = {b4.x - v[0], b4.y - v[1], b4.z - v[2], b4.w - v[3]};
+#pragma unroll
+    for (int u = 0; u < 4; ++u) sT[r][q + u] = (r >= valid || q + u >= valid) ? (r == q + u ? 1.f : 0.f) : x[u];
   });
   __syncthreads();
   const int w = tid >> 6, i = tid & 63;
@@ -371,7 +387,9 @@ __global__ __launch_bounds__(256) void k_potrf_trsm(const ClusterInfo* __restric
   tile_gemm<false, false>(acc, oa, ob, k * TILE, (k + 1) * TILE, sA, sB, tid);
   __syncthreads();
   float* lt = L + tile_base(c.ld, mt, k);
-  for_each_acc(acc, tid, [&](int r, int q, float v) { lt[tile_offset(r, q)] = v; });
+  for_each_acc4(acc, tid, [&](int r, int q, const v4f& v) {
+    *reinterpret_cast<float4*>(lt + tile_offset(r, q)) = make_float4(v[0], v[1], v[2], v[3]);
+  });
 }
 
 // ---------------------------------------------------------------------------
@@ -431,7 +449,9 @@ __global__ __launch_bounds__(256) void k_trtri_stage2(const ClusterInfo* __restr
   Operand ob{Y, c.ld, tn * TILE, (int)c.ld, 0};         // OpB[n][k] = T[k][n], read from the mirror block
   tile_gemm<false, false>(acc, oa, ob, mid * TILE, (tm + 1) * TILE, sA, sB, tid);
   float* yt = Y + tile_base(c.ld, tm, tn);
-  for_each_acc(acc, tid, [&](int r, int q, float v) { yt[tile_offset(r, q)] = -v; });
+  for_each_acc4(acc, tid, [&](int r, int q, const v4f& v) {
+    *reinterpret_cast<float4*>(yt + tile_offset(r, q)) = make_float4(-v[0], -v[1], -v[2], -v[3]);
+  });
 }
 
 // upper triangle <- transpose of the lower triangle (tile list of the assembly kernels)
