@@ -414,10 +414,23 @@ class Problem:
 
 
 class Factor:
-    """O6/O7 at the factor point theta_0: L, log det M, and B = [y | L Z]."""
+    """O6/O7 at the factor point theta_0: L, log det M, and B = [y | L Z].
 
-    def __init__(self, prob: Problem, theta0):
+    compensated_blocks = False: the paper's preconditioner, the factor of K_diag (Section 3.2; Algorithm 1 and
+    eq. (precond kypp) use it for the compensated matrix as well).
+    compensated_blocks = True (an option beyond the paper, for Problem(compensate=True)): the factor of the
+    diagonal blocks of the compensated matrix itself.  K'' of eq. (kypp) has the diagonal blocks
+    K_ii + W_i (C_ii - lambda_0 I) W_i^T, C_ii the kernel matrix of cluster i's own representatives; only the
+    coupling BETWEEN clusters is then left to the iteration."""
+
+    def __init__(self, prob: Problem, theta0, compensated_blocks=False):
         blocks = diag_blocks(prob.X, prob.offsets, theta0)
+        if compensated_blocks:
+            C = coupling(prob.reps, theta0)
+            lam0 = compensation_lambda(C)
+            r = prob.r
+            blocks = [B + W @ (C[i * r:(i + 1) * r, i * r:(i + 1) * r] - lam0 * np.eye(r)) @ W.T
+                      for i, (B, W) in enumerate(zip(blocks, prob.Ws))]
         self.Ls, self.logdetM = precond_factor(blocks)
         self.B = rhs(prob.y, self.Ls, prob.offsets, prob.probes)
         self.offsets = prob.offsets

@@ -708,6 +708,45 @@ def test_preconditioned_compensated_system_has_few_distinct_eigenvalues():
     assert abs(out["quad"] - prob.y @ np.linalg.solve(Kpp, prob.y)) < 1e-8
 
 
+def test_factor_of_the_compensated_diagonal_blocks():
+    # Factor(compensated_blocks=True) must be the Cholesky factor of the diagonal blocks of the dense K'' (built by
+    # dense_K, another route than the factor's own block formula); with Hadamard probes the loss is exact for ANY
+    # preconditioner, so it must equal the dense value to rounding; and the iteration needs fewer steps than
+    # with the factor of K_diag because only the coupling between clusters is left.
+    sizes = [16, 16, 16, 16]
+    w = I.make_small(n_clusters=4, sizes=sizes, d=2, rank=2, t=1, seed=41, ell=1.5, spacing=3.5, sigma_blob=0.3)
+    prob = O.Problem(w.X, w.y, w.offsets, I.hadamard_probes(64), 2, compensate=True)
+    Kpp = prob.dense(w.theta)
+    fac = O.Factor(prob, w.theta, compensated_blocks=True)
+    for i, L in enumerate(fac.Ls):
+        si = slice(w.offsets[i], w.offsets[i + 1])
+        assert np.allclose(L @ L.T, Kpp[si, si], rtol=1e-12, atol=1e-12)
+        assert not np.allclose(L @ L.T, O.diag_blocks(prob.X, prob.offsets, w.theta)[i], atol=1e-3)
+    R = np.random.default_rng(5).standard_normal((64, 3))
+    Z = fac.apply(R)
+    for i in range(4):
+        si = slice(w.offsets[i], w.offsets[i + 1])
+        assert np.allclose(Z[si], np.linalg.solve(Kpp[si, si], R[si]), rtol=1e-10, atol=1e-12)
+    sign, ld = np.linalg.slogdet(Kpp)
+    out = O.mll(prob, fac, w.theta, 1e-14, 200)
+    assert out["logdet"] == pytest.approx(ld, abs=1e-8)
+    assert out["nll"] == pytest.approx(exact_gp_nll(Kpp, w.y.astype(np.float64)), rel=1e-10)
+    plain = O.mll(prob, O.Factor(prob, w.theta), w.theta, 1e-14, 200)
+    assert plain["nll"] == pytest.approx(out["nll"], rel=1e-10)
+    # a stale factor point: still exact
+    theta0 = w.theta * np.array([1.2, 0.9, 1.1, 0.8])
+    out0 = O.mll(prob, O.Factor(prob, theta0, compensated_blocks=True), w.theta, 1e-14, 200)
+    assert out0["logdet"] == pytest.approx(ld, abs=1e-8)
+    # more points per representative: the compensation's diagonal blocks dominate the spectrum that the factor of
+    # K_diag leaves to the iteration (up to n_c r + 1 distinct eigenvalues), the factor of the whole blocks removes them
+    w2 = I.make_small(n_clusters=4, sizes=[128] * 4, d=3, rank=8, t=8, seed=44, ell=1.0, spacing=8.0, sigma_blob=0.5,
+                      tol=1e-8, max_iter=200)
+    prob2 = O.Problem(w2.X, w2.y, w2.offsets, w2.probes, 8, compensate=True)
+    it_plain = O.mll(prob2, O.Factor(prob2, w2.theta), w2.theta, 1e-8, 200)["iters"].max()
+    it_comp = O.mll(prob2, O.Factor(prob2, w2.theta, compensated_blocks=True), w2.theta, 1e-8, 200)["iters"].max()
+    assert it_comp <= 6 and it_plain >= 3 * it_comp
+
+
 # ---------------------------------------------------------------- Pade log-determinant
 def test_pade22_is_the_2_2_approximant_of_the_logarithm():
     # P(1+u) - log(1+u) Q(1+u) = O(u^5): exact polynomial arithmetic on the series of log(1+u)
