@@ -101,6 +101,9 @@ def main():
     ap.add_argument("--compensate", action="store_true",
                     help="solve with the compensated operator K'' of eqs. (krep), (kypp) (needed where the "
                          "uncompensated K' is not positive definite: configuration 5)")
+    ap.add_argument("--precond-compensated", action="store_true",
+                    help="with --compensate: precondition with the factor of the diagonal blocks of K'' itself "
+                         "(NUGPR_PRECOND_COMPENSATED) instead of the paper's factor of K_diag")
     ap.add_argument("--max-iter", type=int, default=0, help="PCG iteration limit (0 = the configuration's own)")
     ap.add_argument("--copy-probe-gib", type=float, default=0.0,
                     help="also run a plain copy kernel of this many GiB three times (reference dispatch for "
@@ -132,7 +135,7 @@ def main():
     max_iter = args.max_iter if args.max_iter > 0 else w.max_iter
     ctx = Context(w.X, w.y, w.offsets, w.probes, w.rank, tol=w.tol, max_iter=max_iter, fd_step=w.fd_step,
                   lr=w.lr, isotropic=w.isotropic, device=dev, acc_fp32=(args.acc == "fp32"),
-                  compensate=args.compensate)
+                  compensate=args.compensate, precond_compensated=args.precond_compensated)
     p, T = ctx.p, ctx.T
     phi0 = np.log(w.theta)
     zeros = np.zeros(p)
@@ -296,7 +299,8 @@ def main():
                                "(factor + %d loss evaluations + Adam)" % (args.config, n, ctx.d, nc, r, ctx.t,
                                                                           w.tol, 1 + 2 * p),
                    "protocol": "every timed step starts from theta_0 (Adam's update is computed, not fed back)",
-                   "acc": args.acc, "operator": "K'' (compensated, eq. (kypp))" if args.compensate else
+                   "acc": args.acc, "operator": ("K'' (compensated, eq. (kypp))" + (", preconditioned by the factor of its own diagonal blocks"
+                                                                   if args.precond_compensated else "")) if args.compensate else
                    "K' (eq. (odsplit))", "max_iter": max_iter, "status_codes": codes, "step_ms": [round(x, 2) for x in step_ms],
                    "per_step": per_step(stats, args.steps)},
         "pcg_iters_per_solve": stats["pcg_iterations"] / max(stats["pcg_solves"], 1),

@@ -109,6 +109,19 @@ enum {
                                   stands (lambda_min then lies between 0 and the estimate: a kernel matrix is
                                   positive semi-definite); otherwise the assembly returns NUGPR_ERR_INVALID.
                                   Default: the uncompensated K' of eq. (odsplit). */
+  ,
+  NUGPR_PRECOND_COMPENSATED = 64u /* with NUGPR_COMPENSATE and the default (one-hot) basis: nugpr_precond_factor
+                                  factors the diagonal blocks of K'' itself, K_ii + W_i (C_ii - lambda_0 I) W_i^T
+                                  (eq. (kypp); C_ii = kernel matrix of cluster i's own representatives), so that
+                                  only the coupling BETWEEN clusters is left to the iteration.  An option beyond
+                                  the paper, whose preconditioner is the factor of K_diag for K'' as well
+                                  (eq. (precond kypp)): with many points per representative that leaves up to
+                                  n_clusters * rank large eigenvalues to CG (133 iterations on the 1 M point
+                                  configuration, against a handful with this flag).  The loss is the same
+                                  quantity either way (log det M changes with the factor and the estimate of
+                                  the remainder with it).  nugpr_precond_factor returns NUGPR_ERR_STATE if the
+                                  basis is not the one-hot one (supplied by the caller, or Nystrom weights).
+                                  Default: the factor of K_diag. */
 };
 
 /* Problem description (Section 2.1 notation; Section 3.3 for representatives). */
@@ -140,7 +153,8 @@ typedef struct {
   double lr;           /* Adam learning rate (paper: 0.05)                             */
   double beta1, beta2, eps;  /* Adam moments / epsilon (0 selects 0.9, 0.999, 1e-8)    */
   uint32_t flags;      /* NUGPR_ISOTROPIC | NUGPR_ACC_FP32 | NUGPR_NO_SHORTCUTS |
-                          NUGPR_LOGDET_PADE | NUGPR_FD_FORWARD | NUGPR_COMPENSATE, or 0 */
+                          NUGPR_LOGDET_PADE | NUGPR_FD_FORWARD | NUGPR_COMPENSATE |
+                          NUGPR_PRECOND_COMPENSATED, or 0 */
   int32_t fd_max_halvings;   /* NUGPR_FD_FORWARD: cap on the halvings per hyperparameter,
                                 1..30 (0 selects 8)                                    */
   double fd_threshold; /* NUGPR_FD_FORWARD: stop when |g - g_prev| <= fd_threshold |g|

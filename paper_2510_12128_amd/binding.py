@@ -24,6 +24,7 @@ NUGPR_NO_SHORTCUTS = 4
 NUGPR_LOGDET_PADE = 8
 NUGPR_FD_FORWARD = 16
 NUGPR_COMPENSATE = 32
+NUGPR_PRECOND_COMPENSATED = 64
 
 EXPORT_K, EXPORT_L, EXPORT_LINV, EXPORT_C, EXPORT_W, EXPORT_B, EXPORT_REPS = range(7)
 
@@ -196,7 +197,8 @@ class Context:
 
     def __init__(self, X, y, offsets, probes, rank, tol=1e-6, max_iter=100, fd_step=1e-3, lr=0.05,
                  isotropic=False, reps=None, W=None, device="cuda:0", acc_fp32=False, no_shortcuts=False,
-                 logdet_pade=False, fd_forward=False, fd_threshold=0.0, fd_max_halvings=0, compensate=False):
+                 logdet_pade=False, fd_forward=False, fd_threshold=0.0, fd_max_halvings=0, compensate=False,
+                 precond_compensated=False):
         import torch
         self.torch = torch
         self.lib = load_library()
@@ -234,7 +236,8 @@ class Context:
         pr = Params(tol=tol, max_iter=max_iter, fd_step=fd_step, lr=lr, beta1=0.0, beta2=0.0, eps=0.0,
                     flags=(NUGPR_ISOTROPIC if isotropic else 0) | (NUGPR_ACC_FP32 if acc_fp32 else 0)
                     | (NUGPR_NO_SHORTCUTS if no_shortcuts else 0) | (NUGPR_LOGDET_PADE if logdet_pade else 0)
-                    | (NUGPR_FD_FORWARD if fd_forward else 0) | (NUGPR_COMPENSATE if compensate else 0),
+                    | (NUGPR_FD_FORWARD if fd_forward else 0) | (NUGPR_COMPENSATE if compensate else 0)
+                    | (NUGPR_PRECOND_COMPENSATED if precond_compensated else 0),
                     fd_max_halvings=int(fd_max_halvings), fd_threshold=float(fd_threshold))
         self.params = pr
         self.max_iter = int(max_iter)

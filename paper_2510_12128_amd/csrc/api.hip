@@ -270,6 +270,10 @@ int nugpr_create(nugpr_ctx** out, const nugpr_problem* pb, const nugpr_params* p
     set_error("NUGPR_COMPENSATE with n_clusters * rank > 512 needs the default (fp64) arithmetic mode");
     return NUGPR_ERR_INVALID;
   }
+  if ((prm->flags & NUGPR_PRECOND_COMPENSATED) && (!L.compensate || pb->W)) {
+    set_error("NUGPR_PRECOND_COMPENSATED needs NUGPR_COMPENSATE and the default basis (W = null)");
+    return NUGPR_ERR_INVALID;
+  }
   if (!pb->X || !pb->y || (pb->n_probes > 0 && !pb->probes)) { set_error("X, y or probes is null"); return NUGPR_ERR_INVALID; }
   if (!pb->workspace || (reinterpret_cast<uintptr_t>(pb->workspace) & 255u)) {
     set_error("workspace is null or not 256-byte aligned");

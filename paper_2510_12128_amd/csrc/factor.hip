@@ -217,8 +217,8 @@ __device__ __forceinline__ bool die_local_item(int per, int nc, int& cluster, in
 // microseconds): the diagonal tiles of all clusters first, since the launch cannot end before they do.  Finish
 // and bulk of a block row share a workgroup because, as workgroups of their own, the short finish ones either
 // delay the start of the long ones or wait behind them for a free slot: measured 25 us per launch.
-__global__ __launch_bounds__(256) void k_potrf_update(const ClusterInfo* __restrict__ cl, const float* __restrict__ Kd,
-                                                      float* __restrict__ Lf, float* __restrict__ G, int k,
+__global__ __launch_bounds__(256) void k_potrf_update(const ClusterInfo* __restrict__ cl, const float* Kd,
+                                                      float* Lf, float* __restrict__ G, int k,
                                                       int n_rows, int grid_diag, int nc, PcgState* __restrict__ st) {
   // the operand stages and, once the products are done, the tile on its way into the registers of the
   // factorisation (then its exchange buffers) share one piece of LDS: 16.5 KB per workgroup
@@ -557,6 +557,40 @@ __global__ void k_set_col0(VT* __restrict__ B, const float* __restrict__ y, int6
     B[p * T] = (VT)y[p];
 }
 
+// Diagonal blocks of the compensated matrix (eq. (kypp)) with the one-hot basis: tile (tr, tc), tc <= tr, of
+// cluster ci gets  K_ii[p][q] + Cc[a(p)][a(q)],  a(p) = the row of the coupling matrix that point p belongs to and
+// Cc = C - lambda_0 I as stored (same-cluster entries kept, float(alpha - lambda_0) on the diagonal).  Reads the
+// lower triangle of Cc element-wise (row >= column), which every storage mode keeps.  One workgroup per tile of
+// the assembly's tile list; writes the spare blocks, where the factorisation then runs in place.
+__global__ __launch_bounds__(256) void k_compensated_blocks(const ClusterInfo* __restrict__ cl,
+                                                            const uint64_t* __restrict__ tiles,
+                                                            const float* __restrict__ Kd, float* __restrict__ out,
+                                                            const float* __restrict__ Cc, uint32_t ldc,
+                                                            const int32_t* __restrict__ assign) {
+  __shared__ int32_t ar[TILE], ac[TILE];
+  const uint64_t t = tiles[blockIdx.x];
+  const int ci = (int)(t >> 32), tr = (int)((t >> 16) & 0xffff), tc = (int)(t & 0xffff);
+  const ClusterInfo c = cl[ci];
+  const int tid = threadIdx.x;
+  if (tid < TILE) {
+    const uint32_t p = (uint32_t)(tr * TILE + tid);
+    ar[tid] = p < c.b ? assign[c.row0 + p] : -1;
+  } else if (tid < 2 * TILE) {
+    const uint32_t q = (uint32_t)(tc * TILE + tid - TILE);
+    ac[tid - TILE] = q < c.b ? assign[c.row0 + q] : -1;
+  }
+  __syncthreads();
+  const uint64_t tb = tile_base(c.ld, tr, tc);
+  for (int idx = tid; idx < TILE * TILE; idx += 256) {
+    const int r = idx >> 6, q = idx & 63;
+    const uint32_t at = tile_offset(r, q);
+    float v = Kd[c.koff + tb + at];
+    const int a = ar[r], b = ac[q];
+    if (a >= 0 && b >= 0) v += Cc[blocked_index(ldc, (uint32_t)max(a, b), (uint32_t)min(a, b))];
+    out[c.koff + tb + at] = v;
+  }
+}
+
 int launch_factor(nugpr_ctx* c, hipStream_t s) {
   const Layout& L = c->L;
   // clusters of similar size: one die per cluster; otherwise every cluster over all dies (see die_local_item)
@@ -566,11 +600,20 @@ int launch_factor(nugpr_ctx* c, hipStream_t s) {
   const int ncm = even ? L.nc : -L.nc;
   c->Lf = c->Kd2;                 // the factor goes into the spare blocks (see nugpr_ctx::lf_valid)
   c->lf_valid = true;
+  // what is factored: the assembled K_ii, or (NUGPR_PRECOND_COMPENSATED) the diagonal blocks of K'' formed in the
+  // spare blocks, where the factorisation then runs in place (every tile is read before it is written)
+  const float* Afac = c->Kd;
+  if (c->params.flags & NUGPR_PRECOND_COMPENSATED) {
+    if (!c->onehot) { set_error("NUGPR_PRECOND_COMPENSATED needs the default one-hot basis"); return NUGPR_ERR_STATE; }
+    hipLaunchKernelGGL(k_compensated_blocks, dim3((unsigned)L.n_diag_tiles), dim3(256), 0, s, c->d_cl, c->d_tiles, c->Kd,
+                       c->Kd2, c->C, (uint32_t)L.ldc, c->assign);
+    Afac = c->Kd2;
+  }
   hipLaunchKernelGGL(k_reset_bad, dim3(1), dim3(1), 0, s, c->d_state);
   for (int k = 0; k < L.ntmax; ++k) {
     const int n_rows = L.ntmax - k - 1;         // block rows below the diagonal tile
     const unsigned grid_diag = die_grid(1, ncm), grid_rows = n_rows > 0 ? die_grid(n_rows, ncm) : 0u;
-    hipLaunchKernelGGL(k_potrf_update, dim3(grid_diag + grid_rows), dim3(256), 0, s, c->d_cl, c->Kd, c->Lf, c->G, k,
+    hipLaunchKernelGGL(k_potrf_update, dim3(grid_diag + grid_rows), dim3(256), 0, s, c->d_cl, Afac, c->Lf, c->G, k,
                        n_rows, (int)grid_diag, ncm, c->d_state);
     if (k + 1 < L.ntmax)
       hipLaunchKernelGGL(k_potrf_trsm, dim3(die_grid(L.ntmax - k - 1, ncm)), dim3(256), 0, s, c->d_cl, c->Lf, c->G, k,

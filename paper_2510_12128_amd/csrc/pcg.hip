@@ -625,7 +625,8 @@ int run_split_op(nugpr_ctx* c, const void* D, void* out, int T, hipStream_t s) {
   StripPort up{};
   up.A = c->G; up.in = D; up.out = c->Vv; up.nin = 1;
   if ((rc = launch_strip(c->tab_upG, up, up, T, c->acc64, s))) return rc;                 // U = Y^T D
-  const bool identity = c->build_gen == c->factor_gen && !c->general_route && !(c->params.flags & NUGPR_NO_SHORTCUTS);
+  const bool identity = c->build_gen == c->factor_gen && !c->general_route &&
+                        !(c->params.flags & (NUGPR_NO_SHORTCUTS | NUGPR_PRECOND_COMPENSATED));
   StripPort lo{};
   lo.A = c->G; lo.in = c->Uv; lo.out = out; lo.nin = 1;
   if (!identity) {

@@ -598,3 +598,34 @@ def test_config5_memory_capacity_run(lib):
                   nll=cout["nll"])
     assert crel < 1e-4, crel
     cctx.close()
+    del cctx, Xs, Bg
+    gc.collect()
+    torch.cuda.empty_cache()
+    # ---- the same operator with the factor of ITS OWN diagonal blocks as preconditioner (NUGPR_PRECOND_COMPENSATED):
+    # a handful of iterations instead of 134, the same solution on sampled rows, and a whole train step
+    pctx = make_ctx(lib, w, compensate=True, precond_compensated=True)          # the configuration's max_iter (100)
+    pctx.nugpr_build_blocks(w.theta)
+    assert pctx.nugpr_precond_factor()[0] == 0
+    t0 = time.perf_counter()
+    pout = pctx.nugpr_mll(w.theta)
+    t_pmll = time.perf_counter() - t0
+    assert pout["code"] == 0 and np.isfinite(pout["nll"]), pout
+    Bg = pctx.nugpr_export(B.EXPORT_B)
+    code, Xs, piters, _, _ = pctx.nugpr_pcg_solve(Bg)
+    assert code == 0 and int(piters.max()) <= 12, piters
+    Xd = Xs.cpu().numpy().astype(np.float64)
+    Bd = Bg.cpu().numpy().astype(np.float64)
+    res = cop.rows(Xd, cop.project(Xd), pts) - Bd[pts]
+    prel = float(np.max(np.abs(res)) / np.max(np.abs(Bd)))
+    # column 0 (the targets y) is the same system for both preconditioners: <y, K''^-1 y> must agree
+    assert abs(pout["quad"] - cout["quad"]) <= 1e-4 * abs(cout["quad"]), (pout["quad"], cout["quad"])
+    t0 = time.perf_counter()
+    step = pctx.nugpr_train_step(np.log(w.theta), np.zeros(pctx.p), np.zeros(pctx.p), 0)
+    t_step = time.perf_counter() - t0
+    assert step["code"] == 0 and np.all(np.isfinite(step["grad"])), step
+    assert abs(step["nll0"] - pout["nll"]) <= 1e-9 * abs(pout["nll"])
+    record_metric("fullsize:C5-compensated-own-blocks", iters=int(piters.max()), row_residual=prel, nll=pout["nll"],
+                  nll_with_the_factor_of_K_diag=cout["nll"], loss_seconds=t_pmll, train_step_seconds=t_step,
+                  grad_norm=float(np.linalg.norm(step["grad"])))
+    assert prel < 1e-4, prel
+    pctx.close()
