@@ -8,13 +8,16 @@ Quantities follow eq. (loss function), eq. (logdet) and eq. (numerical gradient)
 paper in the central-difference form on log(theta) (h = 1e-3), all evaluations sharing
 the preconditioner factored at theta_0 and the same probes.
 
-    python tests/golden/make_golden.py [C3 C4 C3-adam20 C3c-adam20 ...] [--workers N] [--steps K]
+    python tests/golden/make_golden.py [C3 C4 C3-adam20 C3c-adam20 C3p-adam20 ...] [--workers N] [--steps K]
 
   C3, C4       base loss + central-difference gradient components (several lengthscales, the output
                scale, the noise) at the configured hyperparameters
   C3c-adam20   the same 20 steps with the compensated operator K'' of eqs. (krep), (kypp), which stays
                positive definite when the lengthscales grow (the uncompensated K' of C3-adam20 does not:
                that record ends with the step at which the oracle finds it indefinite)
+  C3p-adam20   the same with K'' preconditioned by the factor of its own diagonal blocks (the oracle's
+               Factor(compensated_blocks=True)): the same losses up to the stochastic log-determinant estimate, far
+               fewer PCG iterations, so all 20 steps are affordable
   C3-adam20    configuration 3's own workload: 20 passes of Algorithm 1's loop body (factor at theta_0,
                base loss, central differences with that factor and the same probes, Adam with
                gamma = 0.05 on log theta); per step the base loss, the whole gradient and the
@@ -90,17 +93,18 @@ def run_point(name, workers):
                 logdet_precond=base["logdet_precond"], max_iters=int(base["iters"].max()), grad=grad)
 
 
-def run_adam(name, steps, workers, save, compensate=False):
+def run_adam(name, steps, workers, save, compensate=False, own_blocks=False):
     w = I.make_config(name)
     prob = O.Problem(w.X, w.y, w.offsets, w.probes, w.rank, compensate=compensate)
     phi = np.log(w.theta)
     p = phi.shape[0]
     m, v, step = np.zeros(p), np.zeros(p), 0
     rec = dict(config=name, n=w.n, theta0=list(map(float, w.theta)), tol=w.tol, max_iter=w.max_iter,
-               fd_step=w.fd_step, lr=w.lr, compensate=bool(compensate), steps_requested=steps, steps=[])
+               fd_step=w.fd_step, lr=w.lr, compensate=bool(compensate), precond_compensated=bool(own_blocks),
+               steps_requested=steps, steps=[])
     t0 = time.time()
     for it in range(steps):
-        fac = O.Factor(prob, np.exp(phi))
+        fac = O.Factor(prob, np.exp(phi), compensated_blocks=own_blocks)
         _STATE.update(prob=prob, fac=fac, tol=w.tol, max_iter=w.max_iter)
         pts = [phi]
         for i in range(p):
@@ -148,8 +152,9 @@ if __name__ == "__main__":
                 data[key] = rec
                 write()
             base = nm[:-len("-adam20")]
-            comp = base.endswith("c")               # "C3c-adam20": the compensated operator of eqs. (krep), (kypp)
-            run_adam(base[:-1] if comp else base, nsteps, workers, save, compensate=comp)
+            own = base.endswith("p")                # "C3p-adam20": K'' and the factor of its own diagonal blocks
+            comp = own or base.endswith("c")        # "C3c-adam20": the compensated operator of eqs. (krep), (kypp)
+            run_adam(base[:-1] if comp else base, nsteps, workers, save, compensate=comp, own_blocks=own)
         else:
             data[nm] = run_point(nm, workers)
             write()

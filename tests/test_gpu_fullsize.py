@@ -397,7 +397,7 @@ def test_config3_full_size_matches_stored_oracle_values(lib):
     ctx.close()
 
 
-def run_stored_trajectory(lib, key, compensate):
+def run_stored_trajectory(lib, key, compensate, own_blocks=False):
     """Configuration 3's own workload, 20 Adam steps on log(theta) at n = 131072, against the oracle's stored
     run of the same steps (tests/golden/make_golden.py): per step the base loss to 1e-4, the whole gradient to
     1e-4 of its norm, log(theta) after the update."""
@@ -405,7 +405,8 @@ def run_stored_trajectory(lib, key, compensate):
     w = I.make_config("C3")
     assert np.allclose(gold["theta0"], w.theta) and gold["lr"] == w.lr and gold["fd_step"] == w.fd_step
     assert bool(gold.get("compensate", False)) == compensate
-    ctx = make_ctx(lib, w, compensate=compensate)
+    assert bool(gold.get("precond_compensated", False)) == own_blocks
+    ctx = make_ctx(lib, w, compensate=compensate, precond_compensated=own_blocks)
     p = ctx.p
     phi, m, v, st = np.log(w.theta), np.zeros(p), np.zeros(p), 0
     worst_nll = worst_g = worst_phi = 0.0
@@ -449,6 +450,12 @@ def test_config3_twenty_adam_steps_match_the_stored_oracle_run(lib):
 def test_config3_twenty_adam_steps_with_the_compensated_operator(lib):
     # Algorithm 1 solves with the compensated K'' (eqs. (krep), (kypp)), which stays positive definite: all 20 steps
     run_stored_trajectory(lib, "C3c-adam20", compensate=True)
+
+
+def test_config3_twenty_adam_steps_with_the_compensated_operator_and_its_own_preconditioner(lib):
+    # the whole workload of configuration 3, all 20 steps: K'' preconditioned by the factor of its own diagonal blocks
+    # (NUGPR_PRECOND_COMPENSATED), which the oracle can afford at this size (a few PCG iterations per solve)
+    run_stored_trajectory(lib, "C3p-adam20", compensate=True, own_blocks=True)
 
 
 def test_adam_trajectory_matches_oracle_on_config1(lib):
